@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the GG constrained tensor pass on one MI355X.
+
+A step is one whole pass (per-segment fit -> step Delta = alpha/16 -> quantise -> Map ->
+Exp-Golomb-0 bit count and u_max) over the flat 1.5-billion-element fp32 gradient bucket of a
+28-layer transformer (253 segments), inputs resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--small] [--no-cpu] [--extra]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "GG fit+quantize+rate+penalty: Gelem/s and % of HBM roofline on 1 MI355X"
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+ALGO_BYTES_PER_ELEM = 8.0      # fp32 bucket: 4 B read by the moment sweep + 4 B read by the rate sweep
+
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this same command, scaled by a plain-copy calibration; the summaries live under profiles/.
+# None until measured for the kernel that currently ships.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--small", action="store_true", help="1/64-scale bucket (quick functional run)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--extra", action="store_true", help="also time the penalty variant and the sampler")
+    ap.add_argument("--cpu-sample-elems", type=int, default=380_000_000)
+    return ap.parse_args()
+
+
+def time_steps(fn, steps, torch):
+    """Wall time of `steps` back-to-back calls, bracketed by synchronisation, plus HIP-event time."""
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        fn()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return wall_ms / steps, ev0.elapsed_time(ev1) / steps
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import gg_inputs
+    import paper_2506_00486_amd as gg
+
+    gg.lib()  # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    layout = gg_inputs.gradient_bucket_1p5b()
+    if args.small:
+        layout = gg_inputs.scaled_layout(layout, 64, ragged=False)
+    t_gen = time.perf_counter()
+    flat, off, _, _ = gg_inputs.make_bucket(layout, seed=3, device=dev, dtype=torch.float32)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+    n, S = int(off[-1]), len(layout)
+    ws = gg.Workspace(n, S, device=dev)
+    fit = torch.empty(S * 40, dtype=torch.uint8, device=dev)
+    rate = torch.empty(S * 48, dtype=torch.uint8, device=dev)
+
+    def step():
+        gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, eg_k=0, fit=fit, rate=rate)
+
+    for _ in range(args.warmup):
+        step()
+    ms_wall, ms_ev = time_steps(step, args.steps, torch)
+    value = n / (ms_wall * 1e-3) / 1e9
+
+    # dominant kernel: the rate sweep (k_quant).  Timed on its own stream-ordered call with HIP events:
+    # the call also enqueues three tiny kernels (table upload, per-unit parameters, finalisation).
+    frec = gg.fit_records(fit)
+    delta = gg.gg_delta_from_fit(fit, S, 16.0)
+    rate2 = torch.empty(S * 48, dtype=torch.uint8, device=dev)
+
+    def rate_only():
+        lib_rc = gg.lib().gg_quantize_rate_segmented(flat.data_ptr(), 0, off.ctypes.data, S, delta.data_ptr(), 0, 0, 0,
+                                                     None, None, rate2.data_ptr(), ws.ptr, ws.bytes,
+                                                     torch.cuda.current_stream().cuda_stream)
+        assert lib_rc == 0
+
+    def fit_only():
+        gg.gg_fit_segmented(flat, off, ws, out=fit)
+
+    rate_only()
+    _, ms_rate = time_steps(rate_only, args.steps, torch)
+    _, ms_fit = time_steps(fit_only, args.steps, torch)
+    assert rate2.cpu().numpy().tobytes() == rate.cpu().numpy().tobytes()
+    algo_bytes_kernel = 4.0 * n
+    achieved = algo_bytes_kernel / (ms_rate * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "k_quant (rate sweep)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
+                "algorithmic_bytes_per_launch": algo_bytes_kernel, "avg_launch_ms": round(ms_rate, 4),
+                "fit_sweep_ms": round(ms_fit, 4),
+                "whole_pass": {"algorithmic_bytes": ALGO_BYTES_PER_ELEM * n, "ms": round(ms_ev, 4),
+                               "achieved": round(ALGO_BYTES_PER_ELEM * n / (ms_ev * 1e-3) / 1e9, 1),
+                               "frac": round(ALGO_BYTES_PER_ELEM * n / (ms_ev * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}}
+
+    out = {"metric": METRIC, "value": round(value, 2), "unit": "Gelem/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms_wall, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": ("flat fp32 gradient bucket, 28-layer transformer (hidden 1536, FFN 8960, vocab 151936, "
+                                   "GQA kv 256), %d segments, %d elements, GGD(alpha~LogU(1e-5,1e-3), beta~U(0.5,1.5)) seed 3; "
+                                   "one gg_fused_segmented call: per-segment fit, Delta=alpha/16, EG-0 bits + u_max" % (S, n))
+                      + (" [1/64 scale]" if args.small else ""),
+                      "elements": n, "segments": S, "input_generation_s": round(t_gen, 2)},
+           "roofline": roofline}
+
+    if args.extra:
+        extra = {}
+        grad = torch.zeros(n, dtype=torch.float32, device=dev)
+
+        def step_pen():
+            gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, eg_k=0, fit=fit, rate=rate, lam=1e-4, grad=grad)
+
+        step_pen()
+        _, ms_pen = time_steps(step_pen, max(3, args.steps // 2), torch)
+        extra["with_penalty_written"] = {"ms": round(ms_pen, 4), "Gelem/s": round(n / ms_pen / 1e6, 2),
+                                         "algorithmic_GB/s": round(12.0 * n / ms_pen / 1e6, 1)}
+        del grad
+        ns = 202_383_360 if not args.small else 202_383_360 // 64
+        xs = torch.empty(ns, dtype=torch.bfloat16, device=dev)
+
+        def step_sample():
+            gg.gg_sample(ns, 0.0156, 0.9, seed=4, out=xs)
+
+        step_sample()
+        _, ms_s = time_steps(step_sample, 5, torch)
+        extra["gg_sample_bf16"] = {"elements": ns, "ms": round(ms_s, 4), "Gsamples/s": round(ns / ms_s / 1e6, 2)}
+        out["extra"] = extra
+
+    if not args.no_cpu:
+        import oracle
+        # bounded sample: the leading whole segments of the same bucket, ~cpu_sample_elems elements
+        k = int(np.searchsorted(off, args.cpu_sample_elems, side="right")) - 1
+        k = max(1, min(k, S))
+        m = int(off[k])
+        host = flat[:m].cpu().numpy()
+        t0 = time.perf_counter()
+        ofits, orates = oracle.fused_segmented(host, off[:k + 1], delta_div=16.0)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(m / dt / 1e9, 4), "unit": "Gelem/s", "cores": 1, "kind": "oracle",
+                               "sample": "first %d segments (%d elements) of the same bucket, %.1f s" % (k, m, dt)}
+        # the sample doubles as a last sanity check of the timed configuration
+        rrec = gg.rate_records(rate)
+        for s in range(k):
+            assert abs(float(frec[s]["beta"]) - ofits[s].beta) <= 1e-4 * ofits[s].beta, (s, frec[s], ofits[s])
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,285 @@
+"""ctypes binding of libgg.so: same names as the C ABI (include/gg.h), argument marshalling only.
+
+Tensors are torch tensors on the GPU (float32 or bfloat16 inputs).  Result records come back as
+device byte tensors; `fit_records` / `rate_records` copy them to the host as numpy structured
+arrays.  All work is enqueued on torch's current stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+GG_F32, GG_BF16 = 0, 1
+GG_FLOOR, GG_NEAREST_EVEN = 0, 1
+GG_F_EMPTY, GG_F_DEGENERATE, GG_F_BETA_CLAMPED_LO, GG_F_BETA_CLAMPED_HI, GG_F_NONFINITE, GG_F_SATURATED = \
+    1, 2, 4, 8, 16, 32
+
+# host views of gg_fit_t (40 bytes) and gg_rate_t (48 bytes)
+FIT_DTYPE = np.dtype([("sum_abs", "<f8"), ("sum_sq", "<f8"), ("n", "<u8"), ("beta", "<f4"), ("alpha", "<f4"),
+                      ("flags", "<u4"), ("_pad", "<u4")])
+RATE_DTYPE = np.dtype([("eg_bits", "<u8"), ("n", "<u8"), ("n_clamped", "<u8"), ("entropy_bits", "<f8"),
+                       ("u_max", "<u4"), ("fl_bits", "<u4"), ("delta", "<f4"), ("flags", "<u4")])
+assert FIT_DTYPE.itemsize == 40 and RATE_DTYPE.itemsize == 48
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class GGError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {lib().gg_strerror(code).decode()} ({code})")
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libgg.so")
+
+
+def lib():
+    """The loaded libgg.so.  Raises if it has not been built: there is no fallback path."""
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_2506_00486_amd.build` "
+                               "(or __graft_entry__.build()); libgg has no CPU fallback")
+        L = C.CDLL(path)
+        vp, i32, i64, u32, u64, f32, f64, sz = (C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64, C.c_float,
+                                                C.c_double, C.c_size_t)
+        ci = C.c_int
+        sig = {
+            "gg_strerror": (C.c_char_p, [ci]),
+            "gg_workspace_bytes": (ci, [i64, i32, i32, C.POINTER(sz)]),
+            "gg_fit": (ci, [vp, ci, i64, vp, vp, sz, vp]),
+            "gg_fit_segmented": (ci, [vp, ci, vp, i32, vp, vp, sz, vp]),
+            "gg_fit_rows": (ci, [vp, ci, i64, i64, vp, vp, vp, sz, vp]),
+            "gg_quantize_rate": (ci, [vp, ci, i64, f32, ci, ci, i32, vp, vp, vp, vp, sz, vp]),
+            "gg_quantize_rate_segmented": (ci, [vp, ci, vp, i32, vp, ci, ci, i32, vp, vp, vp, vp, sz, vp]),
+            "gg_quantize_rate_rows": (ci, [vp, ci, i64, i64, vp, ci, ci, vp, vp, vp, sz, vp]),
+            "gg_delta_from_fit": (ci, [vp, i32, f32, vp, vp]),
+            "gg_penalty_grad": (ci, [vp, ci, i64, f32, f32, f32, vp, ci, vp]),
+            "gg_penalty_grad_segmented": (ci, [vp, ci, vp, i32, vp, f32, vp, ci, vp, sz, vp]),
+            "gg_sample": (ci, [vp, ci, i64, f32, f32, u64, u32, u64, vp]),
+            "gg_philox_words": (ci, [vp, i64, u64, u32, u64, u32, vp]),
+            "gg_init_alpha": (f64, [i64, f64, f64]),
+            "gg_compression_ratio": (f64, [f64, f64]),
+            "gg_fused_segmented": (ci, [vp, ci, vp, i32, f32, vp, ci, ci, i32, vp, vp, f32, vp, ci, vp, vp, vp, sz, vp]),
+            "gg_fused_rows": (ci, [vp, ci, i64, i64, f32, vp, ci, ci, vp, f32, vp, ci, vp, vp, vp, vp, sz, vp]),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _LIB = L
+    return _LIB
+
+
+# ---- marshalling helpers ------------------------------------------------------------------------
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return GG_F32
+    if t.dtype == torch.bfloat16:
+        return GG_BF16
+    raise TypeError(f"libgg takes float32 or bfloat16 tensors, got {t.dtype}")
+
+
+def _dev(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("libgg needs contiguous tensors in GPU memory")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _f32(v) -> float:
+    return float(np.float32(v))
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise GGError(code, where)
+
+
+def _offsets(offsets: Sequence[int]) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(offsets, dtype=np.int64))
+
+
+def workspace_bytes(n_total: int, n_units: int = 1, nbins: int = 0) -> int:
+    out = C.c_size_t(0)
+    _check(lib().gg_workspace_bytes(int(n_total), int(n_units), int(nbins), C.byref(out)), "gg_workspace_bytes")
+    return out.value
+
+
+class Workspace:
+    """A caller-owned device scratch buffer sized by gg_workspace_bytes."""
+
+    def __init__(self, n_total: int, n_units: int = 1, nbins: int = 0, device="cuda"):
+        self.bytes = workspace_bytes(n_total, n_units, nbins)
+        self.buf = torch.empty(self.bytes, dtype=torch.uint8, device=device)
+
+    @property
+    def ptr(self) -> int:
+        return self.buf.data_ptr()
+
+
+def _records(n: int, itemsize: int, device) -> torch.Tensor:
+    return torch.empty(max(n, 1) * itemsize, dtype=torch.uint8, device=device)
+
+
+def fit_records(t: torch.Tensor, n: Optional[int] = None) -> np.ndarray:
+    a = t.cpu().numpy().view(FIT_DTYPE)
+    return a if n is None else a[:n]
+
+
+def rate_records(t: torch.Tensor, n: Optional[int] = None) -> np.ndarray:
+    a = t.cpu().numpy().view(RATE_DTYPE)
+    return a if n is None else a[:n]
+
+
+# ---- entry points (names and argument order follow include/gg.h) --------------------------------
+def gg_fit(x: torch.Tensor, ws: Workspace, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    out = out if out is not None else _records(1, 40, x.device)
+    _check(lib().gg_fit(_dev(x), _dtype_code(x), x.numel(), _dev(out), ws.ptr, ws.bytes, _stream()), "gg_fit")
+    return out
+
+
+def gg_fit_segmented(x: torch.Tensor, offsets, ws: Workspace, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    off = _offsets(offsets)
+    S = off.size - 1
+    out = out if out is not None else _records(S, 40, x.device)
+    _check(lib().gg_fit_segmented(_dev(x), _dtype_code(x), off.ctypes.data, S, _dev(out), ws.ptr, ws.bytes, _stream()),
+           "gg_fit_segmented")
+    return out
+
+
+def gg_fit_rows(x: torch.Tensor, rows: int, cols: int, ws: Workspace, want_total: bool = False):
+    out = _records(rows, 40, x.device)
+    total = _records(1, 40, x.device) if want_total else None
+    _check(lib().gg_fit_rows(_dev(x), _dtype_code(x), rows, cols, _dev(out), _dev(total), ws.ptr, ws.bytes, _stream()),
+           "gg_fit_rows")
+    return (out, total) if want_total else out
+
+
+def gg_quantize_rate(x: torch.Tensor, delta: float, ws: Workspace, eg_k: int = 0, round_mode: int = GG_FLOOR,
+                     nbins: int = 0, want_symbols: bool = False):
+    """Returns (rate record tensor, hist uint64-as-int64 tensor or None, symbols int32 tensor or None)."""
+    hist = torch.empty(nbins, dtype=torch.int64, device=x.device) if nbins > 0 else None
+    sym = torch.empty(x.numel(), dtype=torch.int32, device=x.device) if want_symbols else None
+    out = _records(1, 48, x.device)
+    _check(lib().gg_quantize_rate(_dev(x), _dtype_code(x), x.numel(), _f32(delta), eg_k, round_mode, nbins, _dev(hist),
+                                  _dev(sym), _dev(out), ws.ptr, ws.bytes, _stream()), "gg_quantize_rate")
+    return out, hist, sym
+
+
+def gg_quantize_rate_segmented(x: torch.Tensor, offsets, delta: torch.Tensor, ws: Workspace, eg_k: int = 0,
+                               round_mode: int = GG_FLOOR, nbins: int = 0, want_symbols: bool = False):
+    off = _offsets(offsets)
+    S = off.size - 1
+    hist = torch.empty(max(S, 1) * nbins, dtype=torch.int64, device=x.device) if nbins > 0 else None
+    sym = torch.empty(x.numel(), dtype=torch.int32, device=x.device) if want_symbols else None
+    out = _records(S, 48, x.device)
+    _check(lib().gg_quantize_rate_segmented(_dev(x), _dtype_code(x), off.ctypes.data, S, _dev(delta), eg_k, round_mode,
+                                            nbins, _dev(hist), _dev(sym), _dev(out), ws.ptr, ws.bytes, _stream()),
+           "gg_quantize_rate_segmented")
+    return out, hist, sym
+
+
+def gg_quantize_rate_rows(x: torch.Tensor, rows: int, cols: int, delta: torch.Tensor, ws: Workspace, eg_k: int = 0,
+                          round_mode: int = GG_FLOOR, want_symbols: bool = False):
+    sym = torch.empty(x.numel(), dtype=torch.int32, device=x.device) if want_symbols else None
+    out = _records(rows, 48, x.device)
+    _check(lib().gg_quantize_rate_rows(_dev(x), _dtype_code(x), rows, cols, _dev(delta), eg_k, round_mode, _dev(sym),
+                                       _dev(out), ws.ptr, ws.bytes, _stream()), "gg_quantize_rate_rows")
+    return out, sym
+
+
+def gg_delta_from_fit(fit: torch.Tensor, S: int, delta_div: float) -> torch.Tensor:
+    out = torch.empty(max(S, 1), dtype=torch.float32, device=fit.device)
+    _check(lib().gg_delta_from_fit(_dev(fit), S, _f32(delta_div), _dev(out), _stream()), "gg_delta_from_fit")
+    return out
+
+
+def gg_penalty_grad(w: torch.Tensor, alpha: float, beta: float, lam: float, grad: Optional[torch.Tensor] = None,
+                    accumulate: bool = False) -> torch.Tensor:
+    if grad is None:
+        grad = torch.empty(w.numel(), dtype=torch.float32, device=w.device)
+    _check(lib().gg_penalty_grad(_dev(w), _dtype_code(w), w.numel(), _f32(alpha), _f32(beta), _f32(lam), _dev(grad),
+                                 int(bool(accumulate)), _stream()), "gg_penalty_grad")
+    return grad
+
+
+def gg_penalty_grad_segmented(w: torch.Tensor, offsets, fit: torch.Tensor, lam: float, ws: Workspace,
+                              grad: Optional[torch.Tensor] = None, accumulate: bool = False) -> torch.Tensor:
+    off = _offsets(offsets)
+    S = off.size - 1
+    if grad is None:
+        grad = torch.empty(w.numel(), dtype=torch.float32, device=w.device)
+    _check(lib().gg_penalty_grad_segmented(_dev(w), _dtype_code(w), off.ctypes.data, S, _dev(fit), _f32(lam), _dev(grad),
+                                           int(bool(accumulate)), ws.ptr, ws.bytes, _stream()),
+           "gg_penalty_grad_segmented")
+    return grad
+
+
+def gg_sample(n: int, alpha: float, beta: float, seed: int, stream_id: int = 0, offset: int = 0,
+              dtype=torch.float32, device="cuda", out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty(n, dtype=dtype, device=device)
+    _check(lib().gg_sample(_dev(out), _dtype_code(out), n, _f32(alpha), _f32(beta), int(seed), int(stream_id),
+                           int(offset), _stream()), "gg_sample")
+    return out
+
+
+def gg_philox_words(n: int, seed: int, stream_id: int = 0, offset: int = 0, attempt: int = 0, device="cuda"):
+    out = torch.empty(4 * max(n, 1), dtype=torch.int32, device=device)
+    _check(lib().gg_philox_words(_dev(out), n, int(seed), int(stream_id), int(offset), int(attempt), _stream()),
+           "gg_philox_words")
+    return out[: 4 * n]
+
+
+def gg_init_alpha(d_in: int, shape: float, xi: float = 1.0) -> float:
+    return lib().gg_init_alpha(int(d_in), float(shape), float(xi))
+
+
+def gg_compression_ratio(mean_bits: float, fl_bits: float) -> float:
+    return lib().gg_compression_ratio(float(mean_bits), float(fl_bits))
+
+
+def gg_fused_segmented(x: torch.Tensor, offsets, ws: Workspace, delta_div: float = 16.0,
+                       delta: Optional[torch.Tensor] = None, eg_k: int = 0, round_mode: int = GG_FLOOR,
+                       nbins: int = 0, want_symbols: bool = False, lam: float = 0.0,
+                       grad: Optional[torch.Tensor] = None, accumulate: bool = False, want_rate: bool = True,
+                       fit: Optional[torch.Tensor] = None, rate: Optional[torch.Tensor] = None):
+    """Returns dict(fit=, rate=, hist=, symbols=, grad=) of device tensors (None where not requested)."""
+    off = _offsets(offsets)
+    S = off.size - 1
+    fit = fit if fit is not None else _records(S, 40, x.device)
+    if want_rate and rate is None:
+        rate = _records(S, 48, x.device)
+    hist = torch.empty(max(S, 1) * nbins, dtype=torch.int64, device=x.device) if (nbins > 0 and want_rate) else None
+    sym = torch.empty(x.numel(), dtype=torch.int32, device=x.device) if (want_symbols and want_rate) else None
+    _check(lib().gg_fused_segmented(_dev(x), _dtype_code(x), off.ctypes.data, S, _f32(delta_div), _dev(delta), eg_k,
+                                    round_mode, nbins if hist is not None else 0, _dev(hist), _dev(sym), _f32(lam),
+                                    _dev(grad), int(bool(accumulate)), _dev(fit), _dev(rate) if want_rate else None,
+                                    ws.ptr, ws.bytes, _stream()), "gg_fused_segmented")
+    return dict(fit=fit, rate=rate if want_rate else None, hist=hist, symbols=sym, grad=grad)
+
+
+def gg_fused_rows(x: torch.Tensor, rows: int, cols: int, ws: Workspace, delta_div: float = 16.0,
+                  delta: Optional[torch.Tensor] = None, eg_k: int = 0, round_mode: int = GG_FLOOR,
+                  want_symbols: bool = False, lam: float = 0.0, grad: Optional[torch.Tensor] = None,
+                  accumulate: bool = False, want_rate: bool = True, want_total: bool = False):
+    fit = _records(rows, 40, x.device)
+    total = _records(1, 40, x.device) if want_total else None
+    rate = _records(rows, 48, x.device) if want_rate else None
+    sym = torch.empty(x.numel(), dtype=torch.int32, device=x.device) if (want_symbols and want_rate) else None
+    _check(lib().gg_fused_rows(_dev(x), _dtype_code(x), rows, cols, _f32(delta_div), _dev(delta), eg_k, round_mode,
+                               _dev(sym), _f32(lam), _dev(grad), int(bool(accumulate)), _dev(fit), _dev(total),
+                               _dev(rate), ws.ptr, ws.bytes, _stream()), "gg_fused_rows")
+    return dict(fit=fit, total=total, rate=rate, symbols=sym, grad=grad)

@@ -1,0 +1,181 @@
+// gg_device.h -- device-side building blocks of libgg (gfx950 / CDNA4, wave64).
+//
+// Lane exchange by DPP inside a 16-lane row and by ds_bpermute across rows, wave and
+// block reductions with a fixed combination order (so every result is reproducible),
+// 128-bit element loads for fp32 / bf16, the chunk walker all streaming kernels share,
+// and the Philox4x32-10 block function.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gg {
+
+constexpr int kBlock = 256;          // threads per workgroup: 4 wave64
+constexpr int kWaves = kBlock / 64;
+constexpr int kChunk = 16384;        // elements per work item (64 KiB of fp32, 32 KiB of bf16)
+
+// ---------------------------------------------------------------------------------------------
+// lane exchange
+// ---------------------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+}
+
+// DPP controls: quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror.
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+template <int CTRL, typename V>
+__device__ __forceinline__ V dpp_xchg(V v) {
+    static_assert(sizeof(V) == 4 || sizeof(V) == 8, "32- or 64-bit values only");
+    if constexpr (sizeof(V) == 4) {
+        uint32_t w = dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v));
+        return __builtin_bit_cast(V, w);
+    } else {
+        uint64_t b = __builtin_bit_cast(uint64_t, v);
+        uint32_t lo = dpp_u32<CTRL>((uint32_t)b), hi = dpp_u32<CTRL>((uint32_t)(b >> 32));
+        return __builtin_bit_cast(V, ((uint64_t)hi << 32) | lo);
+    }
+}
+
+// All-lanes reduction of a wave64 with a commutative op.  After each step both partners hold
+// op(a, b) computed from the same two operands, so every lane ends with the same bits.
+template <typename V, typename Op>
+__device__ __forceinline__ V wave_reduce(V v, Op op) {
+    v = op(v, dpp_xchg<kDppXor1>(v));        // pairs
+    v = op(v, dpp_xchg<kDppXor2>(v));        // quads
+    v = op(v, dpp_xchg<kDppHalfMirror>(v));  // groups of 8
+    v = op(v, dpp_xchg<kDppMirror>(v));      // rows of 16
+    v = op(v, __shfl_xor(v, 16, 64));
+    v = op(v, __shfl_xor(v, 32, 64));
+    return v;
+}
+
+struct OpAdd { template <typename V> __device__ V operator()(V a, V b) const { return a + b; } };
+struct OpMax { template <typename V> __device__ V operator()(V a, V b) const { return a > b ? a : b; } };
+struct OpOr  { template <typename V> __device__ V operator()(V a, V b) const { return a | b; } };
+
+// Block reduction: wave results go through LDS and every thread combines them in wave order.
+// `slot` must have kWaves entries; consecutive calls must use different slots or be separated
+// by the barrier this function ends with.
+template <typename V, typename Op>
+__device__ __forceinline__ V block_reduce(V v, Op op, V *slot) {
+    v = wave_reduce(v, op);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) slot[wave] = v;
+    __syncthreads();
+    V r = slot[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) r = op(r, slot[w]);
+    __syncthreads();
+    return r;
+}
+
+// ---------------------------------------------------------------------------------------------
+// element access: 16 bytes per lane per load
+// ---------------------------------------------------------------------------------------------
+struct bf16_t { uint16_t bits; };
+
+template <typename T> struct Elem;
+
+template <> struct Elem<float> {
+    static constexpr int W = 4;
+    using raw = float4;
+    static __device__ __forceinline__ raw loadv(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+    static __device__ __forceinline__ void unpack(const raw &r, float (&v)[W]) {
+        v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+    }
+    static __device__ __forceinline__ float load1(const float *p) { return *p; }
+};
+
+template <> struct Elem<bf16_t> {
+    static constexpr int W = 8;
+    using raw = uint4;
+    static __device__ __forceinline__ raw loadv(const bf16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+    static __device__ __forceinline__ void unpack(const raw &r, float (&v)[W]) {
+        // bf16 is the high half of an fp32: widening is a shift (even element) or a mask (odd)
+        v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+        v[4] = __uint_as_float(r.z << 16); v[5] = __uint_as_float(r.z & 0xffff0000u);
+        v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ float load1(const bf16_t *p) {
+        return __uint_as_float((uint32_t)p->bits << 16);
+    }
+};
+
+// fp32 -> bf16, round to nearest even, NaN kept quiet
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t b = __float_as_uint(f);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((b >> 16) | 0x0040u);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return (uint16_t)(b >> 16);
+}
+
+// ---------------------------------------------------------------------------------------------
+// chunk walker.  Elements [start, start+len) of x are visited once each by the block:
+// a scalar head up to the first 16-byte boundary, 128-bit vectors (U loads in flight per
+// lane), and a scalar tail.  `x` itself must be 16-byte aligned, so the boundary is a
+// property of the element index.  body.vec(v, idx) gets W consecutive elements starting at
+// element index idx (a multiple of W); body.one(v, idx) gets one.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int U, typename Body>
+__device__ __forceinline__ void process_chunk(const T *__restrict__ x, int64_t start, int len, Body &body) {
+    constexpr int W = Elem<T>::W;
+    const int tid = threadIdx.x;
+    int head = (int)((W - (int)(start % W)) % W);
+    if (head > len) head = len;
+    if (tid < head) body.one(Elem<T>::load1(x + start + tid), start + tid);
+
+    const int64_t vstart = start + head;
+    const int nvec = (len - head) / W;
+    const T *__restrict__ p = x + vstart;
+    int i = tid;
+    for (; i + (U - 1) * kBlock < nvec; i += U * kBlock) {
+        typename Elem<T>::raw r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[u] = Elem<T>::loadv(p + (int64_t)(i + u * kBlock) * W);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float v[W];
+            Elem<T>::unpack(r[u], v);
+            body.vec(v, vstart + (int64_t)(i + u * kBlock) * W);
+        }
+    }
+    for (; i < nvec; i += kBlock) {
+        typename Elem<T>::raw r = Elem<T>::loadv(p + (int64_t)i * W);
+        float v[W];
+        Elem<T>::unpack(r, v);
+        body.vec(v, vstart + (int64_t)i * W);
+    }
+    const int done = head + nvec * W;
+    if (tid < len - done) body.one(Elem<T>::load1(x + start + done + tid), start + done + tid);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of multiply-hi/lo mixing, key bumped by the
+// Weyl constants after each round.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// top 23 bits of a word -> uniform in (0,1), exact in fp32
+__device__ __forceinline__ float unit_open(uint32_t w) {
+    return ((float)(w >> 9) + 0.5f) * 0x1p-23f;
+}
+
+}  // namespace gg

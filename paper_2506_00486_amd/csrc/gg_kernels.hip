@@ -1,0 +1,1070 @@
+// gg_kernels.hip -- HIP kernels and the C ABI of libgg (see include/gg.h).
+//
+// Launch structure of one pass over a buffer cut into units (segments / rows / one tensor):
+//   k_upload_i64      segment offsets and per-unit chunk prefix -> workspace (through kernel args)
+//   k_fit_partials    one work item = one chunk of <= kChunk elements of one unit:
+//                     sum|x|, sum x^2 in fp32 per lane, fp64 across the block -> partials[chunk]
+//   k_fit_finalize    one wave per unit: fixed-order fp64 sum of its partials, 64-way parallel
+//                     bracketing of the moment-ratio equation, Eq. 2 for alpha; derives the
+//                     unit's quantiser / penalty parameters and clears its rate record
+//   k_quant           re-reads x: quantise, Map, Exp-Golomb bits, u_max, optional LDS-privatised
+//                     histogram, symbols, penalty gradient; integer atomics into the rate record
+//   k_rate_finalize   fixed-length bits, flags, histogram entropy in fp64
+// All reductions are order-fixed (floating point) or integer, so results are reproducible.
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <cmath>
+#include <type_traits>
+#include <vector>
+
+#include "../../include/gg.h"
+#include "gg_device.h"
+
+namespace gg {
+
+// ---------------------------------------------------------------------------------------------
+// unit geometry
+// ---------------------------------------------------------------------------------------------
+struct SegView {
+    const int64_t *off;    // device: S+1 element offsets, or nullptr for uniform rows
+    const int64_t *cpre;   // device: S+1 chunk prefix sums (with off)
+    int64_t cols;          // uniform: elements per row
+    int64_t cpr;           // uniform: chunks per row
+    int32_t S;
+};
+
+struct ChunkLoc {
+    int64_t start;   // first element
+    int64_t c;       // chunk index inside the unit
+    int32_t seg;
+    int32_t len;
+};
+
+__device__ __forceinline__ ChunkLoc locate(const SegView &sv, int64_t chunk) {
+    ChunkLoc L;
+    if (sv.off == nullptr) {
+        const int64_t seg = chunk / sv.cpr;
+        L.c = chunk - seg * sv.cpr;
+        L.seg = (int32_t)seg;
+        L.start = seg * sv.cols + L.c * kChunk;
+        const int64_t rest = sv.cols - L.c * kChunk;
+        L.len = (int32_t)(rest < kChunk ? rest : kChunk);
+    } else {
+        int lo = 0, hi = sv.S;  // largest s with cpre[s] <= chunk (skips empty units)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (sv.cpre[mid] <= chunk) lo = mid; else hi = mid;
+        }
+        L.seg = lo;
+        L.c = chunk - sv.cpre[lo];
+        L.start = sv.off[lo] + L.c * kChunk;
+        const int64_t rest = sv.off[lo + 1] - L.start;
+        L.len = (int32_t)(rest < kChunk ? rest : kChunk);
+    }
+    return L;
+}
+
+__device__ __forceinline__ int64_t unit_len(const SegView &sv, int seg) {
+    return sv.off ? sv.off[seg + 1] - sv.off[seg] : sv.cols;
+}
+__device__ __forceinline__ int64_t unit_chunk0(const SegView &sv, int seg) {
+    return sv.off ? sv.cpre[seg] : (int64_t)seg * sv.cpr;
+}
+__device__ __forceinline__ int64_t unit_chunk1(const SegView &sv, int seg) {
+    return sv.off ? sv.cpre[seg + 1] : (int64_t)(seg + 1) * sv.cpr;
+}
+
+// per-unit parameters of the second sweep
+constexpr uint32_t kSkipRate = 1u;   // no usable step: symbols 0, nothing accumulated
+constexpr uint32_t kPenZero = 2u;    // alpha == 0: penalty contributes 0
+struct SegParam {
+    float inv_delta;
+    float delta;
+    float pen_coef;    // lambda * beta / alpha
+    float inv_alpha;
+    float beta_m1;
+    uint32_t flags;
+    uint32_t _pad[2];
+};
+
+// ---------------------------------------------------------------------------------------------
+// small utility kernels
+// ---------------------------------------------------------------------------------------------
+constexpr int kPackI64 = 448;  // 3584 bytes of kernel arguments per launch
+struct PackI64 { int64_t v[kPackI64]; };
+
+__global__ void k_upload_i64(PackI64 pack, int count, int64_t *dst) {
+    for (int i = threadIdx.x; i < count; i += blockDim.x) dst[i] = pack.v[i];
+}
+
+__global__ void k_fill_u64(uint64_t *p, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = 0;
+}
+
+// ---------------------------------------------------------------------------------------------
+// sweep 1: moments
+// ---------------------------------------------------------------------------------------------
+struct FitBody {
+    float s1[4] = {0.f, 0.f, 0.f, 0.f};
+    float s2[4] = {0.f, 0.f, 0.f, 0.f};
+    template <int W>
+    __device__ __forceinline__ void vec(const float (&v)[W], int64_t) {
+#pragma unroll
+        for (int j = 0; j < W; ++j) {
+            s1[j & 3] += fabsf(v[j]);
+            s2[j & 3] = __builtin_fmaf(v[j], v[j], s2[j & 3]);
+        }
+    }
+    __device__ __forceinline__ void one(float v, int64_t) {
+        s1[0] += fabsf(v);
+        s2[0] = __builtin_fmaf(v, v, s2[0]);
+    }
+};
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_fit_partials(SegView sv, const T *__restrict__ x,
+                                                         double2 *__restrict__ partials) {
+    __shared__ double red[2][kWaves];
+    const int64_t chunk = blockIdx.x;
+    const ChunkLoc L = locate(sv, chunk);
+    FitBody body;
+    process_chunk<T, 4>(x, L.start, L.len, body);
+    // lanes hold sums of <= 16 products each in fp32; everything above is fp64
+    double a = ((double)body.s1[0] + (double)body.s1[1]) + ((double)body.s1[2] + (double)body.s1[3]);
+    double b = ((double)body.s2[0] + (double)body.s2[1]) + ((double)body.s2[2] + (double)body.s2[3]);
+    a = wave_reduce(a, OpAdd());
+    b = wave_reduce(b, OpAdd());
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { red[0][wave] = a; red[1][wave] = b; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double2 r;
+        r.x = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+        r.y = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+        partials[chunk] = r;
+    }
+}
+
+// log of the moment ratio rho(b) = Gamma(2/b)^2 / (Gamma(1/b) Gamma(3/b)) of a GGD (from Eq. 1, 3)
+__device__ __forceinline__ double log_rho(double b) {
+    const double r = 1.0 / b;
+    return 2.0 * lgamma(2.0 * r) - lgamma(r) - lgamma(3.0 * r);
+}
+
+// Wave-cooperative fit from the moments.  The root of log_rho(b) = log(rho_hat) is bracketed by
+// evaluating 64 log-spaced shapes at once (one per lane); each round shrinks the bracket 65-fold.
+__device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, gg_fit_t &f) {
+    const int lane = threadIdx.x & 63;
+    f.sum_abs = s1; f.sum_sq = s2; f.n = n; f.beta = 0.f; f.alpha = 0.f; f.flags = 0; f._pad = 0;
+    if (n == 0) { f.flags = GG_F_EMPTY; return; }
+    if (!isfinite(s1) || !isfinite(s2)) { f.flags = GG_F_NONFINITE; f.beta = 2.f; return; }
+    if (s2 == 0.0) { f.flags = GG_F_DEGENERATE; f.beta = 2.f; return; }
+    const double m1 = s1 / (double)n, m2 = s2 / (double)n;
+    const double target = log(m1 * m1 / m2);
+    double b;
+    if (!(target > log_rho(GG_BETA_MIN))) {
+        b = GG_BETA_MIN; f.flags = GG_F_BETA_CLAMPED_LO;
+    } else if (!(target < log_rho(GG_BETA_MAX))) {
+        b = GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI;
+    } else {
+        double llo = log(GG_BETA_MIN), lhi = log(GG_BETA_MAX);
+        for (int round = 0; round < 6; ++round) {
+            const double step = (lhi - llo) * (1.0 / 65.0);
+            const double cand = exp(llo + step * (double)(lane + 1));
+            const bool below = log_rho(cand) < target;   // rho increases with b
+            const int cnt = __popcll(__ballot(below));
+            const double nlo = llo + step * (double)cnt;
+            lhi = cnt == 64 ? lhi : llo + step * (double)(cnt + 1);
+            llo = nlo;
+        }
+        b = exp(0.5 * (llo + lhi));
+    }
+    const double r = 1.0 / b;
+    f.beta = (float)b;
+    f.alpha = (float)sqrt(m2 * exp(lgamma(r) - lgamma(3.0 * r)));   // Eq. 2 with sigma^2 = m2
+}
+
+// where the step and the penalty parameters of a unit come from
+struct PrepArgs {
+    const gg_fit_t *fit;       // device fits (penalty parameters, and alpha for delta_div > 0) or nullptr
+    const float *delta_dev;    // device per-unit steps or nullptr
+    float delta_div;           // > 0: Delta = alpha / delta_div
+    float delta_scalar;        // used when delta_div <= 0 and delta_dev == nullptr
+    float lambda;
+    SegParam *params;          // device out
+    gg_rate_t *rate;           // device out (cleared) or nullptr
+    int want_pen;
+};
+
+__device__ __forceinline__ void prepare_unit(const PrepArgs &a, int seg, int64_t n, float alpha, float beta) {
+    SegParam p;
+    p.flags = 0; p._pad[0] = p._pad[1] = 0;
+    float delta;
+    if (a.delta_div > 0.f) delta = (float)((double)alpha / (double)a.delta_div);  // == one fp32 division
+    else delta = a.delta_dev ? a.delta_dev[seg] : a.delta_scalar;
+    const bool ok = delta > 0.f && isfinite(delta);
+    p.delta = delta;
+    p.inv_delta = ok ? (float)(1.0 / (double)delta) : 0.f;                        // == 1.0f / delta
+    if (!ok) p.flags |= kSkipRate;
+    if (a.want_pen && alpha > 0.f && isfinite(alpha) && isfinite(beta)) {
+        p.inv_alpha = (float)(1.0 / (double)alpha);
+        p.pen_coef = (float)((double)a.lambda * (double)beta / (double)alpha);
+        p.beta_m1 = beta - 1.0f;
+    } else {
+        p.inv_alpha = 0.f; p.pen_coef = 0.f; p.beta_m1 = 0.f;
+        p.flags |= kPenZero;
+    }
+    a.params[seg] = p;
+    if (a.rate) {
+        gg_rate_t r;
+        r.eg_bits = 0; r.n = (uint64_t)n; r.n_clamped = 0; r.entropy_bits = 0.0;
+        r.u_max = 0; r.fl_bits = 0; r.delta = delta;
+        r.flags = n == 0 ? GG_F_EMPTY : (ok ? 0u : GG_F_DEGENERATE);
+        a.rate[seg] = r;
+    }
+}
+
+__global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *__restrict__ partials,
+                                                     gg_fit_t *__restrict__ out, PrepArgs prep, int do_prep) {
+    const int seg = blockIdx.x, lane = threadIdx.x;
+    const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
+    double s1 = 0.0, s2 = 0.0;
+    for (int64_t c = c0 + lane; c < c1; c += 64) {   // lane-strided, ascending: a fixed order
+        const double2 p = partials[c];
+        s1 += p.x; s2 += p.y;
+    }
+    s1 = wave_reduce(s1, OpAdd());
+    s2 = wave_reduce(s2, OpAdd());
+    const int64_t n = unit_len(sv, seg);
+    gg_fit_t f;
+    solve_fit(s1, s2, (uint64_t)n, f);
+    if (lane == 0) {
+        out[seg] = f;
+        if (do_prep) prepare_unit(prep, seg, n, f.alpha, f.beta);
+    }
+}
+
+// fit of the whole matrix from the per-row sums (one wave, fixed order)
+__global__ __launch_bounds__(64) void k_fit_total(const gg_fit_t *__restrict__ rows, int64_t n_rows,
+                                                  gg_fit_t *__restrict__ out) {
+    const int lane = threadIdx.x;
+    double s1 = 0.0, s2 = 0.0;
+    uint64_t n = 0;
+    for (int64_t r = lane; r < n_rows; r += 64) { s1 += rows[r].sum_abs; s2 += rows[r].sum_sq; n += rows[r].n; }
+    s1 = wave_reduce(s1, OpAdd());
+    s2 = wave_reduce(s2, OpAdd());
+    n = wave_reduce(n, OpAdd());
+    gg_fit_t f;
+    solve_fit(s1, s2, n, f);
+    if (lane == 0) out[0] = f;
+}
+
+// parameters for calls that do not fit first (one thread per unit)
+__global__ void k_seg_prepare(SegView sv, PrepArgs prep) {
+    const int seg = blockIdx.x * blockDim.x + threadIdx.x;
+    if (seg >= sv.S) return;
+    float alpha = 0.f, beta = 0.f;
+    if (prep.fit) { alpha = prep.fit[seg].alpha; beta = prep.fit[seg].beta; }
+    prepare_unit(prep, seg, unit_len(sv, seg), alpha, beta);
+}
+
+__global__ void k_delta_from_fit(const gg_fit_t *__restrict__ fit, int32_t S, float delta_div,
+                                 float *__restrict__ out) {
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s < S) out[s] = (float)((double)fit[s].alpha / (double)delta_div);
+}
+
+// ---------------------------------------------------------------------------------------------
+// sweep 2: quantise / rate / histogram / symbols / penalty
+// ---------------------------------------------------------------------------------------------
+struct QuantArgs {
+    const SegParam *params;   // device per-unit parameters, or nullptr to use `single`
+    SegParam single;
+    gg_rate_t *rate;          // device, per unit (RATE)
+    uint32_t eg_add;          // 2^k
+    uint32_t eg_const;        // 63 - k:  len(u) = eg_const - 2 clz(u + 2^k)
+    // EXTRA
+    int32_t *symbols;
+    uint64_t *hist;           // S * nbins
+    int32_t nbins;
+    int32_t lbins;            // bins privatised in LDS
+    // PEN
+    float *grad;
+    int accumulate;
+    // work split
+    int64_t n_chunks;
+    int32_t chunks_per_block;
+};
+
+constexpr float kQLim = 1073741824.0f;  // 2^30
+
+// v_log_f32 / v_exp_f32 with the denormal range of the argument rescaled
+__device__ __forceinline__ float log2_full(float t) {
+    const bool tiny = t < 0x1p-100f;
+    const float l = __builtin_amdgcn_logf(tiny ? t * 0x1p+64f : t);
+    return tiny ? l - 64.0f : l;
+}
+
+template <int MODE, bool RATE, bool PEN, bool EXTRA>
+struct QuantBody {
+    // unit parameters
+    float inv_delta, inv_alpha, beta_m1, pen_coef;
+    bool pen_live, hist_live;
+    uint32_t eg_add;
+    // outputs
+    int32_t *symbols; float *grad; int accumulate;
+    uint32_t *lds_hist; uint64_t *ghist; uint32_t last_bin, lbins;
+    // per-lane accumulators
+    uint32_t clz_sum = 0, u_max = 0, n_clamped = 0, nan_seen = 0;
+
+    __device__ __forceinline__ int32_t quant(float x) {
+        float t = x * inv_delta;                       // the one fp32 rounding of the quantiser
+        if (t != t) { nan_seen = 1; t = 0.f; }
+        t = __builtin_amdgcn_fmed3f(t, -kQLim, kQLim);
+        // m = -q: floor(t) = -ceil(-t), rint is odd-symmetric
+        const float r = MODE == GG_FLOOR ? ceilf(-t) : rintf(-t);
+        const int32_t m = (int32_t)r;
+        // Map(q) = q > 0 ? 2q-1 : -2q  is the zig-zag code of m = -q
+        const uint32_t u = ((uint32_t)m << 1) ^ (uint32_t)(m >> 31);
+        clz_sum += (uint32_t)__builtin_clz(u + eg_add);
+        u_max = u > u_max ? u : u_max;
+        if constexpr (EXTRA) {
+            if (hist_live) {
+                const uint32_t bin = u < last_bin ? u : last_bin;
+                n_clamped += u > last_bin ? 1u : 0u;
+                if (bin < lbins) atomicAdd(&lds_hist[bin], 1u);
+                else atomicAdd(reinterpret_cast<unsigned long long *>(&ghist[bin]), 1ull);
+            }
+        }
+        return -m;
+    }
+
+    __device__ __forceinline__ float penalty(float w) {
+        const float a = fabsf(w);
+        const float e = __builtin_amdgcn_exp2f(beta_m1 * log2_full(a * inv_alpha));
+        float p = pen_coef * e;
+        p = w < 0.f ? -p : p;
+        return (a > 0.f && pen_live) ? p : 0.f;       // sign(0) = 0; NaN inputs give 0
+    }
+
+    template <int W>
+    __device__ __forceinline__ void vec(const float (&v)[W], int64_t idx) {
+        if constexpr (RATE) {
+            int32_t q[W];
+#pragma unroll
+            for (int j = 0; j < W; ++j) q[j] = quant(v[j]);
+            if constexpr (EXTRA) {
+                if (symbols) {
+#pragma unroll
+                    for (int j = 0; j < W; j += 4)
+                        *reinterpret_cast<int4 *>(symbols + idx + j) = make_int4(q[j], q[j + 1], q[j + 2], q[j + 3]);
+                }
+            }
+        }
+        if constexpr (PEN) {
+#pragma unroll
+            for (int j = 0; j < W; j += 4) {
+                float4 g = make_float4(penalty(v[j]), penalty(v[j + 1]), penalty(v[j + 2]), penalty(v[j + 3]));
+                float4 *dst = reinterpret_cast<float4 *>(grad + idx + j);
+                if (accumulate) {
+                    const float4 o = *dst;
+                    g.x += o.x; g.y += o.y; g.z += o.z; g.w += o.w;
+                }
+                *dst = g;
+            }
+        }
+    }
+
+    __device__ __forceinline__ void one(float v, int64_t idx) {
+        if constexpr (RATE) {
+            const int32_t q = quant(v);
+            if constexpr (EXTRA) { if (symbols) symbols[idx] = q; }
+        }
+        if constexpr (PEN) {
+            const float g = penalty(v);
+            grad[idx] = accumulate ? grad[idx] + g : g;
+        }
+    }
+};
+
+template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
+__global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restrict__ x, QuantArgs a) {
+    extern __shared__ uint32_t lds_hist[];
+    __shared__ uint32_t red[4][kWaves];
+    const int tid = threadIdx.x;
+    const bool want_hist = EXTRA && a.hist != nullptr;
+    if (want_hist) {
+        for (int b = tid; b < a.lbins; b += kBlock) lds_hist[b] = 0;
+        __syncthreads();
+    }
+    int hist_seg = -1;
+
+    auto flush_hist = [&](int seg) {   // merge the block-private bins into the unit's histogram
+        __syncthreads();
+        if (seg >= 0) {
+            uint64_t *g = a.hist + (int64_t)seg * a.nbins;
+            for (int b = tid; b < a.lbins; b += kBlock) {
+                const uint32_t c = lds_hist[b];
+                if (c) { atomicAdd(reinterpret_cast<unsigned long long *>(&g[b]), (unsigned long long)c); lds_hist[b] = 0; }
+            }
+        }
+        __syncthreads();
+    };
+
+    const int64_t first = (int64_t)blockIdx.x * a.chunks_per_block;
+    int64_t last = first + a.chunks_per_block;
+    if (last > a.n_chunks) last = a.n_chunks;
+    for (int64_t chunk = first; chunk < last; ++chunk) {
+        const ChunkLoc L = locate(sv, chunk);
+        const SegParam P = a.params ? a.params[L.seg] : a.single;
+        const bool rate_live = RATE && !(P.flags & kSkipRate);
+        if (want_hist && L.seg != hist_seg) { flush_hist(hist_seg); hist_seg = L.seg; }
+
+        QuantBody<MODE, RATE, PEN, EXTRA> body;
+        body.inv_delta = P.inv_delta; body.inv_alpha = P.inv_alpha; body.beta_m1 = P.beta_m1;
+        body.pen_coef = P.pen_coef; body.pen_live = !(P.flags & kPenZero);
+        body.hist_live = want_hist && rate_live;
+        body.eg_add = a.eg_add;
+        body.symbols = a.symbols; body.grad = a.grad; body.accumulate = a.accumulate;
+        body.lds_hist = lds_hist;
+        body.ghist = want_hist ? a.hist + (int64_t)L.seg * a.nbins : nullptr;
+        body.last_bin = (uint32_t)(a.nbins > 0 ? a.nbins - 1 : 0);
+        body.lbins = (uint32_t)a.lbins;
+        process_chunk<T, 4>(x, L.start, L.len, body);
+
+        if constexpr (RATE) {
+            const uint32_t clz = block_reduce(body.clz_sum, OpAdd(), red[0]);
+            const uint32_t um = block_reduce(body.u_max, OpMax(), red[1]);
+            const uint32_t nan = block_reduce(body.nan_seen, OpOr(), red[2]);
+            uint32_t ncl = 0;
+            if constexpr (EXTRA) ncl = block_reduce(body.n_clamped, OpAdd(), red[3]);
+            if (tid == 0 && rate_live) {
+                gg_rate_t *r = a.rate + L.seg;
+                const uint64_t bits = (uint64_t)L.len * a.eg_const - 2ull * clz;
+                atomicAdd(reinterpret_cast<unsigned long long *>(&r->eg_bits), (unsigned long long)bits);
+                atomicMax(&r->u_max, um);
+                if (ncl) atomicAdd(reinterpret_cast<unsigned long long *>(&r->n_clamped), (unsigned long long)ncl);
+                if (nan) atomicOr(&r->flags, GG_F_NONFINITE);
+            }
+        }
+    }
+    if (want_hist) flush_hist(hist_seg);
+}
+
+__global__ __launch_bounds__(kBlock) void k_rate_finalize(gg_rate_t *__restrict__ rate, const uint64_t *__restrict__ hist,
+                                                          int32_t nbins) {
+    __shared__ double red[kWaves];
+    const int seg = blockIdx.x, tid = threadIdx.x;
+    gg_rate_t *r = rate + seg;
+    const uint32_t flags = r->flags;
+    const uint64_t n = r->n;
+    double h = 0.0;
+    if (hist && n > 0 && !(flags & GG_F_DEGENERATE)) {
+        const uint64_t *g = hist + (int64_t)seg * nbins;
+        const double inv_n = 1.0 / (double)n;
+        for (int b = tid; b < nbins; b += kBlock) {   // ascending bins per lane, fixed tree above
+            const uint64_t c = g[b];
+            if (c) { const double p = (double)c * inv_n; h -= p * log2(p); }
+        }
+    }
+    h = block_reduce(h, OpAdd(), red);
+    if (tid == 0) {
+        const uint32_t um = r->u_max;
+        uint32_t f = flags;
+        if (um >= 2147483647u) f |= GG_F_SATURATED;
+        r->flags = f;
+        r->fl_bits = (flags & GG_F_DEGENERATE) ? 0u : (um ? 32u - (uint32_t)__builtin_clz(um) : 1u);
+        r->entropy_bits = h;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// sampler
+// ---------------------------------------------------------------------------------------------
+constexpr int kMaxAttempts = 64;
+
+struct SampleArgs {
+    float alpha, a /* 1/beta */, d, c;
+    int boost;
+    uint32_t key0, key1, stream_id;
+    uint64_t offset;
+    int64_t n;
+};
+
+__device__ __forceinline__ float gg_draw(const SampleArgs &s, uint64_t idx) {
+    float gam = s.d;            // fallback if every attempt is rejected (probability < 1e-80)
+    uint32_t w3_first = 0;
+    for (uint32_t attempt = 0; attempt < (uint32_t)kMaxAttempts; ++attempt) {
+        uint32_t w[4];
+        philox4x32_10(attempt, s.stream_id, (uint32_t)idx, (uint32_t)(idx >> 32), s.key0, s.key1, w);
+        if (attempt == 0) w3_first = w[3];
+        // Box-Muller: v_cos_f32 takes its argument in revolutions
+        const float rad = sqrtf(-2.0f * 0.69314718056f * __builtin_amdgcn_logf(unit_open(w[0])));
+        const float z = rad * __builtin_amdgcn_cosf(unit_open(w[1]));
+        const float t = 1.0f + s.c * z;
+        const float v = t * t * t;
+        if (v <= 0.f) continue;
+        const float lu = 0.69314718056f * __builtin_amdgcn_logf(unit_open(w[2]));
+        const float lv = 0.69314718056f * __builtin_amdgcn_logf(v);
+        if (lu < 0.5f * z * z + s.d - s.d * v + s.d * lv) { gam = s.d * v; break; }
+    }
+    // G^(1/beta); with the boost G = G' U^beta so G^(1/beta) = G'^(1/beta) U
+    float mag = __builtin_amdgcn_exp2f(s.a * __builtin_amdgcn_logf(gam));
+    if (s.boost) mag *= unit_open(w3_first);
+    const float xv = s.alpha * mag;
+    return (w3_first & 1u) ? -xv : xv;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_sample(T *__restrict__ out, SampleArgs s) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.n; i += stride) {
+        const float v = gg_draw(s, s.offset + (uint64_t)i);
+        if constexpr (sizeof(T) == 2) out[i].bits = f32_to_bf16_rne(v);
+        else out[i] = v;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_philox_words(uint32_t *__restrict__ out, int64_t n, uint32_t key0, uint32_t key1,
+                                                         uint32_t stream_id, uint64_t offset, uint32_t attempt) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+        const uint64_t idx = offset + (uint64_t)i;
+        uint32_t w[4];
+        philox4x32_10(attempt, stream_id, (uint32_t)idx, (uint32_t)(idx >> 32), key0, key1, w);
+        *reinterpret_cast<uint4 *>(out + 4 * i) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// =============================================================================================
+// host side
+// =============================================================================================
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct WsLayout {
+    size_t off_bytes, cpre_bytes, params_bytes, partials_bytes, total;
+    size_t off_at, cpre_at, params_at, partials_at;
+};
+
+static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
+    WsLayout w;
+    const size_t S = (size_t)n_units;
+    const size_t max_chunks = (size_t)(n_total / kChunk) + S + 1;
+    w.off_bytes = align_up((S + 1) * sizeof(int64_t), 256);
+    w.cpre_bytes = w.off_bytes;
+    w.params_bytes = align_up(S * sizeof(SegParam), 256);
+    w.partials_bytes = align_up(max_chunks * sizeof(double2), 256);
+    w.off_at = 256;
+    w.cpre_at = w.off_at + w.off_bytes;
+    w.params_at = w.cpre_at + w.cpre_bytes;
+    w.partials_at = w.params_at + w.params_bytes;
+    w.total = w.partials_at + w.partials_bytes;
+    return w;
+}
+
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline bool aligned8(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; }
+
+constexpr int64_t kMaxUnits = 1 << 24;
+constexpr int64_t kMaxChunks = 2147483647LL;
+
+// A validated description of how a buffer is cut into units, plus where its tables live.
+struct Geometry {
+    SegView sv{};
+    int64_t n_total = 0, n_chunks = 0;
+    int32_t S = 0;
+    WsLayout wl{};
+    char *ws = nullptr;
+    std::vector<int64_t> off, cpre;   // host copies (segmented only)
+    SegParam *params() const { return reinterpret_cast<SegParam *>(ws + wl.params_at); }
+    double2 *partials() const { return reinterpret_cast<double2 *>(ws + wl.partials_at); }
+};
+
+static int geometry_uniform(int64_t rows, int64_t cols, void *ws, size_t ws_bytes, bool need_ws, Geometry &g) {
+    if (rows < 0 || cols < 0 || rows > kMaxUnits) return GG_ERR_INVALID_ARG;
+    if (rows > 0 && cols > INT64_MAX / rows) return GG_ERR_INVALID_ARG;
+    g.S = (int32_t)rows;
+    g.n_total = rows * cols;
+    const int64_t cpr = (cols + kChunk - 1) / kChunk;
+    if (cpr > 0 && rows > kMaxChunks / cpr) return GG_ERR_INVALID_ARG;
+    g.n_chunks = rows * cpr;
+    g.sv.off = nullptr; g.sv.cpre = nullptr; g.sv.cols = cols; g.sv.cpr = cpr; g.sv.S = g.S;
+    g.wl = ws_layout(g.n_total, rows > 0 ? rows : 1);
+    if (need_ws) {
+        if (!ws || ws_bytes < g.wl.total || !aligned16(ws)) return GG_ERR_WORKSPACE;
+        g.ws = static_cast<char *>(ws);
+    }
+    return GG_OK;
+}
+
+static int geometry_segmented(const int64_t *offsets, int32_t S, void *ws, size_t ws_bytes, Geometry &g) {
+    if (!offsets || S < 0 || S > kMaxUnits) return S < 0 || !offsets ? GG_ERR_INVALID_ARG : GG_ERR_BAD_SEGMENTS;
+    if (offsets[0] < 0) return GG_ERR_BAD_SEGMENTS;
+    g.S = S;
+    g.off.assign(offsets, offsets + S + 1);
+    g.cpre.resize((size_t)S + 1);
+    int64_t chunks = 0;
+    for (int32_t s = 0; s < S; ++s) {
+        if (offsets[s + 1] < offsets[s]) return GG_ERR_BAD_SEGMENTS;
+        g.cpre[s] = chunks;
+        chunks += (offsets[s + 1] - offsets[s] + kChunk - 1) / kChunk;
+        if (chunks > kMaxChunks) return GG_ERR_BAD_SEGMENTS;
+    }
+    g.cpre[S] = chunks;
+    g.n_chunks = chunks;
+    g.n_total = offsets[S];   // elements of the buffer the units index into
+    g.wl = ws_layout(g.n_total, S > 0 ? S : 1);
+    if (!ws || ws_bytes < g.wl.total || !aligned16(ws)) return GG_ERR_WORKSPACE;
+    g.ws = static_cast<char *>(ws);
+    g.sv.off = reinterpret_cast<const int64_t *>(g.ws + g.wl.off_at);
+    g.sv.cpre = reinterpret_cast<const int64_t *>(g.ws + g.wl.cpre_at);
+    g.sv.cols = 0; g.sv.cpr = 1; g.sv.S = S;
+    return GG_OK;
+}
+
+static int check_launch() { return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP; }
+
+// tables travel as kernel arguments: asynchronous, no pinned staging, no allocation
+static int upload_i64(const std::vector<int64_t> &v, int64_t *dst, hipStream_t st) {
+    for (size_t base = 0; base < v.size(); base += kPackI64) {
+        PackI64 pack;
+        const int count = (int)((v.size() - base) < (size_t)kPackI64 ? v.size() - base : kPackI64);
+        memcpy(pack.v, v.data() + base, (size_t)count * sizeof(int64_t));
+        hipLaunchKernelGGL(k_upload_i64, dim3(1), dim3(256), 0, st, pack, count, dst + base);
+    }
+    return check_launch();
+}
+
+static int upload_geometry(const Geometry &g, hipStream_t st) {
+    if (g.sv.off == nullptr) return GG_OK;
+    int rc = upload_i64(g.off, const_cast<int64_t *>(g.sv.off), st);
+    if (rc != GG_OK) return rc;
+    return upload_i64(g.cpre, const_cast<int64_t *>(g.sv.cpre), st);
+}
+
+template <typename F>
+static int by_dtype(int dtype, F &&f) {
+    if (dtype == GG_F32) return f(static_cast<const float *>(nullptr));
+    if (dtype == GG_BF16) return f(static_cast<const bf16_t *>(nullptr));
+    return GG_ERR_BAD_DTYPE;
+}
+
+static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out, const PrepArgs *prep, hipStream_t st) {
+    if (g.n_chunks > 0) {
+        int rc = by_dtype(dtype, [&](auto *tag) {
+            using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
+            hipLaunchKernelGGL(k_fit_partials<T>, dim3((unsigned)g.n_chunks), dim3(kBlock), 0, st, g.sv,
+                               static_cast<const T *>(x), g.partials());
+            return check_launch();
+        });
+        if (rc != GG_OK) return rc;
+    }
+    if (g.S > 0) {
+        PrepArgs p{};
+        if (prep) p = *prep;
+        hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(), out, p, prep ? 1 : 0);
+        return check_launch();
+    }
+    return GG_OK;
+}
+
+struct QuantOpts {
+    bool rate = false, pen = false;
+    int eg_k = 0, round_mode = GG_FLOOR;
+    int32_t nbins = 0;
+    uint64_t *hist = nullptr;
+    int32_t *symbols = nullptr;
+    float *grad = nullptr;
+    int accumulate = 0;
+    gg_rate_t *rate_out = nullptr;
+    const SegParam *params = nullptr;
+    SegParam single{};
+};
+
+constexpr int kMaxLdsBins = 12288;   // 48 KiB of block-private bins; higher symbols go to L2 atomics
+
+template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
+static int launch_quant_inst(const Geometry &g, const void *x, const QuantOpts &o, hipStream_t st) {
+    QuantArgs a{};
+    a.params = o.params; a.single = o.single; a.rate = o.rate_out;
+    a.eg_add = 1u << o.eg_k; a.eg_const = 63u - (uint32_t)o.eg_k;
+    a.symbols = o.symbols; a.hist = o.hist; a.nbins = o.nbins;
+    a.lbins = o.hist ? (o.nbins < kMaxLdsBins ? o.nbins : kMaxLdsBins) : 0;
+    a.grad = o.grad; a.accumulate = o.accumulate;
+    a.n_chunks = g.n_chunks;
+    // with a histogram each block keeps its private bins over a run of chunks
+    int64_t cpb = 1;
+    if (o.hist) {
+        const int64_t target_blocks = 256 * 8;
+        cpb = (g.n_chunks + target_blocks - 1) / target_blocks;
+        if (cpb < 1) cpb = 1;
+    }
+    a.chunks_per_block = (int32_t)cpb;
+    const int64_t blocks = (g.n_chunks + cpb - 1) / cpb;
+    const size_t lds = (size_t)a.lbins * sizeof(uint32_t);
+    hipLaunchKernelGGL((k_quant<T, MODE, RATE, PEN, EXTRA>), dim3((unsigned)blocks), dim3(kBlock), lds, st, g.sv,
+                       static_cast<const T *>(x), a);
+    return check_launch();
+}
+
+template <typename T, int MODE>
+static int launch_quant_mode(const Geometry &g, const void *x, const QuantOpts &o, hipStream_t st) {
+    const bool extra = o.hist || o.symbols;
+    if (o.rate && !o.pen && !extra) return launch_quant_inst<T, MODE, true, false, false>(g, x, o, st);
+    if (o.rate && o.pen && !extra) return launch_quant_inst<T, MODE, true, true, false>(g, x, o, st);
+    if (o.rate && !o.pen && extra) return launch_quant_inst<T, MODE, true, false, true>(g, x, o, st);
+    if (o.rate && o.pen && extra) return launch_quant_inst<T, MODE, true, true, true>(g, x, o, st);
+    return GG_ERR_INVALID_ARG;
+}
+
+static int launch_quant(const Geometry &g, const void *x, int dtype, const QuantOpts &o, hipStream_t st) {
+    if (g.n_chunks == 0) return GG_OK;
+    return by_dtype(dtype, [&](auto *tag) {
+        using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
+        if (!o.rate) return launch_quant_inst<T, GG_FLOOR, false, true, false>(g, x, o, st);
+        if (o.round_mode == GG_FLOOR) return launch_quant_mode<T, GG_FLOOR>(g, x, o, st);
+        return launch_quant_mode<T, GG_NEAREST_EVEN>(g, x, o, st);
+    });
+}
+
+static int launch_fill_u64(uint64_t *p, int64_t n, hipStream_t st) {
+    if (n <= 0) return GG_OK;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)blocks), dim3(256), 0, st, p, n);
+    return check_launch();
+}
+
+static int launch_rate_finalize(const Geometry &g, gg_rate_t *rate, const uint64_t *hist, int32_t nbins, hipStream_t st) {
+    if (g.S == 0) return GG_OK;
+    hipLaunchKernelGGL(k_rate_finalize, dim3((unsigned)g.S), dim3(kBlock), 0, st, rate, hist, nbins);
+    return check_launch();
+}
+
+static int launch_seg_prepare(const Geometry &g, const PrepArgs &p, hipStream_t st) {
+    if (g.S == 0) return GG_OK;
+    hipLaunchKernelGGL(k_seg_prepare, dim3((unsigned)((g.S + 255) / 256)), dim3(256), 0, st, g.sv, p);
+    return check_launch();
+}
+
+static int check_rate_args(int eg_k, int round_mode, int32_t nbins, const uint64_t *hist, const int32_t *symbols) {
+    if (eg_k < 0 || eg_k > GG_MAX_EG_K) return GG_ERR_INVALID_ARG;
+    if (round_mode != GG_FLOOR && round_mode != GG_NEAREST_EVEN) return GG_ERR_INVALID_ARG;
+    if (nbins != 0 && (nbins < 2 || nbins > GG_MAX_BINS)) return GG_ERR_INVALID_ARG;
+    if (nbins != 0 && (!hist || !aligned8(hist))) return GG_ERR_INVALID_ARG;
+    if (symbols && !aligned16(symbols)) return GG_ERR_INVALID_ARG;
+    return GG_OK;
+}
+
+// the second sweep and its finalisation, shared by every rate/penalty entry point
+static int run_second_sweep(const Geometry &g, const void *x, int dtype, QuantOpts &o, hipStream_t st) {
+    int rc;
+    if (o.rate && o.nbins > 0 && (rc = launch_fill_u64(o.hist, (int64_t)g.S * o.nbins, st)) != GG_OK) return rc;
+    if (!o.rate) { o.hist = nullptr; o.symbols = nullptr; o.nbins = 0; }
+    if (o.nbins == 0) o.hist = nullptr;
+    if (o.rate || o.pen) {
+        if ((rc = launch_quant(g, x, dtype, o, st)) != GG_OK) return rc;
+    }
+    if (o.rate) return launch_rate_finalize(g, o.rate_out, o.hist, o.nbins, st);
+    return GG_OK;
+}
+
+static int fused_common(Geometry &g, const void *x, int dtype, float delta_div, const float *delta_dev, int eg_k,
+                        int round_mode, int32_t nbins, uint64_t *hist, int32_t *symbols, float lambda, float *grad,
+                        int accumulate, gg_fit_t *fit, gg_fit_t *total_fit, gg_rate_t *rate, hipStream_t st) {
+    int rc;
+    if ((rc = upload_geometry(g, st)) != GG_OK) return rc;
+    PrepArgs p{};
+    p.fit = nullptr; p.delta_dev = delta_dev; p.delta_div = delta_div; p.delta_scalar = 0.f;
+    p.lambda = lambda; p.params = g.params(); p.rate = rate; p.want_pen = grad != nullptr;
+    if ((rc = launch_fit(g, x, dtype, fit, &p, st)) != GG_OK) return rc;
+    if (total_fit) {
+        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(64), 0, st, fit, (int64_t)g.S, total_fit);
+        if ((rc = check_launch()) != GG_OK) return rc;
+    }
+    QuantOpts o;
+    o.rate = rate != nullptr; o.pen = grad != nullptr; o.eg_k = eg_k; o.round_mode = round_mode;
+    o.nbins = nbins; o.hist = hist; o.symbols = symbols; o.grad = grad; o.accumulate = accumulate;
+    o.rate_out = rate; o.params = g.params();
+    return run_second_sweep(g, x, dtype, o, st);
+}
+
+}  // namespace gg
+
+// =============================================================================================
+// C ABI
+// =============================================================================================
+using namespace gg;
+
+extern "C" {
+
+const char *gg_strerror(int code) {
+    switch (code) {
+        case GG_OK: return "ok";
+        case GG_ERR_INVALID_ARG: return "invalid argument";
+        case GG_ERR_BAD_DTYPE: return "unsupported dtype";
+        case GG_ERR_BAD_SEGMENTS: return "bad segment table";
+        case GG_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case GG_ERR_HIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+int gg_workspace_bytes(int64_t n_total, int32_t n_units, int32_t nbins, size_t *bytes_out_host) {
+    if (!bytes_out_host || n_total < 0 || n_units < 0 || n_units > kMaxUnits || nbins < 0 || nbins > GG_MAX_BINS)
+        return GG_ERR_INVALID_ARG;
+    *bytes_out_host = ws_layout(n_total, n_units > 0 ? n_units : 1).total;
+    return GG_OK;
+}
+
+double gg_init_alpha(int64_t d_in, double shape, double xi) {
+    if (d_in <= 0 || !(shape > 0.0) || !(xi > 0.0)) return NAN;
+    return sqrt(xi / (double)d_in * exp(lgamma(1.0 / shape) - lgamma(3.0 / shape)));
+}
+
+double gg_compression_ratio(double mean_bits, double fl_bits) { return 1.0 - mean_bits / fl_bits; }
+
+static int check_x(const void *x, int dtype, int64_t n) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    if (n < 0) return GG_ERR_INVALID_ARG;
+    if (n > 0 && (!x || !aligned16(x))) return GG_ERR_INVALID_ARG;
+    return GG_OK;
+}
+
+int gg_fit(const void *x_dev, int dtype, int64_t n, gg_fit_t *out_dev, void *ws_dev, size_t ws_bytes, void *stream) {
+    int rc = check_x(x_dev, dtype, n);
+    if (rc != GG_OK) return rc;
+    if (!out_dev || !aligned8(out_dev)) return GG_ERR_INVALID_ARG;
+    Geometry g;
+    if ((rc = geometry_uniform(1, n, ws_dev, ws_bytes, true, g)) != GG_OK) return rc;
+    return launch_fit(g, x_dev, dtype, out_dev, nullptr, (hipStream_t)stream);
+}
+
+int gg_fit_segmented(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S, gg_fit_t *out_dev,
+                     void *ws_dev, size_t ws_bytes, void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    Geometry g;
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    if (rc != GG_OK) return rc;
+    if ((rc = check_x(x_dev, dtype, g.n_total)) != GG_OK) return rc;
+    if (S > 0 && (!out_dev || !aligned8(out_dev))) return GG_ERR_INVALID_ARG;
+    if ((rc = upload_geometry(g, (hipStream_t)stream)) != GG_OK) return rc;
+    return launch_fit(g, x_dev, dtype, out_dev, nullptr, (hipStream_t)stream);
+}
+
+int gg_fit_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, gg_fit_t *out_dev, gg_fit_t *total_out_dev,
+                void *ws_dev, size_t ws_bytes, void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    Geometry g;
+    int rc = geometry_uniform(rows, cols, ws_dev, ws_bytes, true, g);
+    if (rc != GG_OK) return rc;
+    if ((rc = check_x(x_dev, dtype, g.n_total)) != GG_OK) return rc;
+    if (rows > 0 && (!out_dev || !aligned8(out_dev))) return GG_ERR_INVALID_ARG;
+    if (total_out_dev && !aligned8(total_out_dev)) return GG_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = launch_fit(g, x_dev, dtype, out_dev, nullptr, st)) != GG_OK) return rc;
+    if (total_out_dev) {
+        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(64), 0, st, out_dev, rows, total_out_dev);
+        return check_launch();
+    }
+    return GG_OK;
+}
+
+int gg_quantize_rate(const void *x_dev, int dtype, int64_t n, float delta, int eg_k, int round_mode, int32_t nbins,
+                     uint64_t *hist_dev, int32_t *symbols_dev, gg_rate_t *out_dev, void *ws_dev, size_t ws_bytes,
+                     void *stream) {
+    int rc = check_x(x_dev, dtype, n);
+    if (rc != GG_OK) return rc;
+    if (!(delta > 0.f) || !std::isfinite(delta)) return GG_ERR_INVALID_ARG;
+    if ((rc = check_rate_args(eg_k, round_mode, nbins, hist_dev, symbols_dev)) != GG_OK) return rc;
+    if (!out_dev || !aligned8(out_dev)) return GG_ERR_INVALID_ARG;
+    Geometry g;
+    if ((rc = geometry_uniform(1, n, ws_dev, ws_bytes, true, g)) != GG_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    PrepArgs p{};
+    p.delta_div = 0.f; p.delta_scalar = delta; p.params = g.params(); p.rate = out_dev; p.want_pen = 0;
+    if ((rc = launch_seg_prepare(g, p, st)) != GG_OK) return rc;
+    QuantOpts o;
+    o.rate = true; o.eg_k = eg_k; o.round_mode = round_mode; o.nbins = nbins; o.hist = hist_dev;
+    o.symbols = symbols_dev; o.rate_out = out_dev; o.params = g.params();
+    return run_second_sweep(g, x_dev, dtype, o, st);
+}
+
+int gg_quantize_rate_segmented(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S,
+                               const float *delta_dev, int eg_k, int round_mode, int32_t nbins, uint64_t *hist_dev,
+                               int32_t *symbols_dev, gg_rate_t *out_dev, void *ws_dev, size_t ws_bytes, void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    Geometry g;
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    if (rc != GG_OK) return rc;
+    if ((rc = check_x(x_dev, dtype, g.n_total)) != GG_OK) return rc;
+    if ((rc = check_rate_args(eg_k, round_mode, nbins, hist_dev, symbols_dev)) != GG_OK) return rc;
+    if (S > 0 && (!delta_dev || !out_dev || !aligned8(out_dev))) return GG_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = upload_geometry(g, st)) != GG_OK) return rc;
+    PrepArgs p{};
+    p.delta_dev = delta_dev; p.delta_div = 0.f; p.params = g.params(); p.rate = out_dev; p.want_pen = 0;
+    if ((rc = launch_seg_prepare(g, p, st)) != GG_OK) return rc;
+    QuantOpts o;
+    o.rate = true; o.eg_k = eg_k; o.round_mode = round_mode; o.nbins = nbins; o.hist = hist_dev;
+    o.symbols = symbols_dev; o.rate_out = out_dev; o.params = g.params();
+    return run_second_sweep(g, x_dev, dtype, o, st);
+}
+
+int gg_quantize_rate_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, const float *delta_dev, int eg_k,
+                          int round_mode, int32_t *symbols_dev, gg_rate_t *out_dev, void *ws_dev, size_t ws_bytes,
+                          void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    Geometry g;
+    int rc = geometry_uniform(rows, cols, ws_dev, ws_bytes, true, g);
+    if (rc != GG_OK) return rc;
+    if ((rc = check_x(x_dev, dtype, g.n_total)) != GG_OK) return rc;
+    if ((rc = check_rate_args(eg_k, round_mode, 0, nullptr, symbols_dev)) != GG_OK) return rc;
+    if (rows > 0 && (!delta_dev || !out_dev || !aligned8(out_dev))) return GG_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    PrepArgs p{};
+    p.delta_dev = delta_dev; p.delta_div = 0.f; p.params = g.params(); p.rate = out_dev; p.want_pen = 0;
+    if ((rc = launch_seg_prepare(g, p, st)) != GG_OK) return rc;
+    QuantOpts o;
+    o.rate = true; o.eg_k = eg_k; o.round_mode = round_mode; o.symbols = symbols_dev; o.rate_out = out_dev;
+    o.params = g.params();
+    return run_second_sweep(g, x_dev, dtype, o, st);
+}
+
+int gg_delta_from_fit(const gg_fit_t *fit_dev, int32_t S, float delta_div, float *delta_out_dev, void *stream) {
+    if (S < 0 || !(delta_div > 0.f) || !std::isfinite(delta_div)) return GG_ERR_INVALID_ARG;
+    if (S == 0) return GG_OK;
+    if (!fit_dev || !delta_out_dev) return GG_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_delta_from_fit, dim3((unsigned)((S + 255) / 256)), dim3(256), 0, (hipStream_t)stream, fit_dev, S,
+                       delta_div, delta_out_dev);
+    return check_launch();
+}
+
+int gg_penalty_grad(const void *w_dev, int dtype, int64_t n, float alpha, float beta, float lambda, float *grad_dev,
+                    int accumulate, void *stream) {
+    int rc = check_x(w_dev, dtype, n);
+    if (rc != GG_OK) return rc;
+    if (!(alpha > 0.f) || !std::isfinite(alpha) || !(beta > 0.f) || !std::isfinite(beta) || !std::isfinite(lambda))
+        return GG_ERR_INVALID_ARG;
+    if (n > 0 && (!grad_dev || !aligned16(grad_dev))) return GG_ERR_INVALID_ARG;
+    Geometry g;
+    if ((rc = geometry_uniform(1, n, nullptr, 0, false, g)) != GG_OK) return rc;
+    QuantOpts o;
+    o.pen = true; o.grad = grad_dev; o.accumulate = accumulate ? 1 : 0;
+    o.single.inv_alpha = (float)(1.0 / (double)alpha);
+    o.single.pen_coef = (float)((double)lambda * (double)beta / (double)alpha);
+    o.single.beta_m1 = beta - 1.0f;
+    o.single.flags = kSkipRate;
+    return run_second_sweep(g, w_dev, dtype, o, (hipStream_t)stream);
+}
+
+int gg_penalty_grad_segmented(const void *w_dev, int dtype, const int64_t *offsets_host, int32_t S,
+                              const gg_fit_t *fit_dev, float lambda, float *grad_dev, int accumulate, void *ws_dev,
+                              size_t ws_bytes, void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    Geometry g;
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    if (rc != GG_OK) return rc;
+    if ((rc = check_x(w_dev, dtype, g.n_total)) != GG_OK) return rc;
+    if (!std::isfinite(lambda)) return GG_ERR_INVALID_ARG;
+    if (S > 0 && !fit_dev) return GG_ERR_INVALID_ARG;
+    if (g.n_total > 0 && (!grad_dev || !aligned16(grad_dev))) return GG_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = upload_geometry(g, st)) != GG_OK) return rc;
+    PrepArgs p{};
+    p.fit = fit_dev; p.delta_div = 0.f; p.delta_scalar = 0.f; p.lambda = lambda; p.params = g.params();
+    p.rate = nullptr; p.want_pen = 1;
+    if ((rc = launch_seg_prepare(g, p, st)) != GG_OK) return rc;
+    QuantOpts o;
+    o.pen = true; o.grad = grad_dev; o.accumulate = accumulate ? 1 : 0; o.params = g.params();
+    return run_second_sweep(g, w_dev, dtype, o, st);
+}
+
+int gg_sample(void *out_dev, int dtype, int64_t n, float alpha, float beta, uint64_t seed, uint32_t stream_id,
+              uint64_t offset, void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    if (n < 0 || !(alpha >= 0.f) || !std::isfinite(alpha) || !(beta >= (float)GG_BETA_MIN) || !(beta <= (float)GG_BETA_MAX))
+        return GG_ERR_INVALID_ARG;
+    if (n == 0) return GG_OK;
+    if (!out_dev || !aligned16(out_dev)) return GG_ERR_INVALID_ARG;
+    SampleArgs s{};
+    const double a = 1.0 / (double)beta;
+    s.boost = a < 1.0;
+    const double d = (s.boost ? a + 1.0 : a) - 1.0 / 3.0;
+    s.alpha = alpha; s.a = (float)a; s.d = (float)d; s.c = (float)(1.0 / sqrt(9.0 * d));
+    s.key0 = (uint32_t)seed; s.key1 = (uint32_t)(seed >> 32); s.stream_id = stream_id; s.offset = offset; s.n = n;
+    int64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == GG_F32) hipLaunchKernelGGL(k_sample<float>, dim3((unsigned)blocks), dim3(kBlock), 0, st, (float *)out_dev, s);
+    else hipLaunchKernelGGL(k_sample<bf16_t>, dim3((unsigned)blocks), dim3(kBlock), 0, st, (bf16_t *)out_dev, s);
+    return check_launch();
+}
+
+int gg_philox_words(uint32_t *out_dev, int64_t n, uint64_t seed, uint32_t stream_id, uint64_t offset, uint32_t attempt,
+                    void *stream) {
+    if (n < 0) return GG_ERR_INVALID_ARG;
+    if (n == 0) return GG_OK;
+    if (!out_dev || !aligned16(out_dev)) return GG_ERR_INVALID_ARG;
+    int64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(k_philox_words, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream, out_dev, n,
+                       (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, offset, attempt);
+    return check_launch();
+}
+
+static int check_fused(int eg_k, int round_mode, int32_t nbins, uint64_t *hist, int32_t *symbols, float delta_div,
+                       const float *delta_dev, float lambda, float *grad, gg_fit_t *fit, gg_rate_t *rate, int32_t S,
+                       int64_t n_total) {
+    if (S > 0 && (!fit || !aligned8(fit))) return GG_ERR_INVALID_ARG;
+    if (rate) {
+        int rc = check_rate_args(eg_k, round_mode, nbins, hist, symbols);
+        if (rc != GG_OK) return rc;
+        if (!aligned8(rate)) return GG_ERR_INVALID_ARG;
+        if (!(delta_div > 0.f) && !delta_dev && S > 0) return GG_ERR_INVALID_ARG;
+        if (delta_div > 0.f && !std::isfinite(delta_div)) return GG_ERR_INVALID_ARG;
+    }
+    if (grad && (!aligned16(grad) || !std::isfinite(lambda))) return GG_ERR_INVALID_ARG;
+    (void)n_total;
+    return GG_OK;
+}
+
+int gg_fused_segmented(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S, float delta_div,
+                       const float *delta_dev, int eg_k, int round_mode, int32_t nbins, uint64_t *hist_dev,
+                       int32_t *symbols_dev, float lambda, float *grad_dev, int accumulate, gg_fit_t *fit_dev,
+                       gg_rate_t *rate_dev, void *ws_dev, size_t ws_bytes, void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    Geometry g;
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    if (rc != GG_OK) return rc;
+    if ((rc = check_x(x_dev, dtype, g.n_total)) != GG_OK) return rc;
+    if ((rc = check_fused(eg_k, round_mode, nbins, hist_dev, symbols_dev, delta_div, delta_dev, lambda, grad_dev, fit_dev,
+                          rate_dev, S, g.n_total)) != GG_OK)
+        return rc;
+    return fused_common(g, x_dev, dtype, delta_div, delta_dev, eg_k, round_mode, nbins, hist_dev, symbols_dev, lambda,
+                        grad_dev, accumulate ? 1 : 0, fit_dev, nullptr, rate_dev, (hipStream_t)stream);
+}
+
+int gg_fused_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, float delta_div, const float *delta_dev,
+                  int eg_k, int round_mode, int32_t *symbols_dev, float lambda, float *grad_dev, int accumulate,
+                  gg_fit_t *fit_dev, gg_fit_t *total_fit_dev, gg_rate_t *rate_dev, void *ws_dev, size_t ws_bytes,
+                  void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    Geometry g;
+    int rc = geometry_uniform(rows, cols, ws_dev, ws_bytes, true, g);
+    if (rc != GG_OK) return rc;
+    if ((rc = check_x(x_dev, dtype, g.n_total)) != GG_OK) return rc;
+    if ((rc = check_fused(eg_k, round_mode, 0, nullptr, symbols_dev, delta_div, delta_dev, lambda, grad_dev, fit_dev,
+                          rate_dev, g.S, g.n_total)) != GG_OK)
+        return rc;
+    if (total_fit_dev && !aligned8(total_fit_dev)) return GG_ERR_INVALID_ARG;
+    return fused_common(g, x_dev, dtype, delta_div, delta_dev, eg_k, round_mode, 0, nullptr, symbols_dev, lambda, grad_dev,
+                        accumulate ? 1 : 0, fit_dev, total_fit_dev, rate_dev, (hipStream_t)stream);
+}
+
+}  // extern "C"

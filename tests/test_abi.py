@@ -1,0 +1,125 @@
+"""CPU-only checks of the boundary: the shared library loads, exports every symbol the header
+declares, and rejects invalid arguments on the host before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _lib():
+    import paper_2506_00486_amd as gg
+    if not os.path.exists(gg.lib_path()):
+        from paper_2506_00486_amd import build
+        build.build()
+    return gg
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "gg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    gg = _lib()
+    names = declared_functions()
+    assert len(names) >= 17
+    for n in names:
+        assert hasattr(gg.lib(), n), n
+    # and the binding offers the same names
+    for n in names:
+        if n in ("gg_strerror", "gg_workspace_bytes"):
+            continue
+        assert hasattr(gg, n), n
+
+
+def test_struct_sizes_match_header():
+    gg = _lib()
+    assert gg.FIT_DTYPE.itemsize == 40 and gg.RATE_DTYPE.itemsize == 48
+    assert gg.FIT_DTYPE.fields["beta"][1] == 24 and gg.FIT_DTYPE.fields["flags"][1] == 32
+    assert gg.RATE_DTYPE.fields["u_max"][1] == 32 and gg.RATE_DTYPE.fields["delta"][1] == 40
+
+
+def test_strerror_and_workspace_size():
+    gg = _lib()
+    L = gg.lib()
+    assert L.gg_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert L.gg_strerror(code) not in (b"ok", b"unknown error")
+    small = gg.workspace_bytes(1 << 20, 1)
+    big = gg.workspace_bytes(1543655424, 253)
+    assert 0 < small < big < 64 << 20
+    out = C.c_size_t(0)
+    assert L.gg_workspace_bytes(-1, 1, 0, C.byref(out)) == -1
+    assert L.gg_workspace_bytes(10, -1, 0, C.byref(out)) == -1
+    assert L.gg_workspace_bytes(10, 1, 0, None) == -1
+
+
+def test_invalid_arguments_are_rejected_on_the_host():
+    """Every call below fails validation before any launch, so no GPU is needed.  The device
+    pointers are fake but well-aligned addresses that are never dereferenced."""
+    gg = _lib()
+    L = gg.lib()
+    P = 0x10000  # aligned fake device address
+    ws_bytes = gg.workspace_bytes(1 << 20, 4)
+    off = np.array([0, 10, 5, 20], dtype=np.int64)  # decreasing
+    ok_off = np.array([0, 10, 15, 20], dtype=np.int64)
+    assert L.gg_fit(P, 7, 100, P, P, ws_bytes, None) == -2                       # dtype
+    assert L.gg_fit(P, 0, -5, P, P, ws_bytes, None) == -1                        # n < 0
+    assert L.gg_fit(None, 0, 100, P, P, ws_bytes, None) == -1                    # null x
+    assert L.gg_fit(P + 4, 0, 100, P, P, ws_bytes, None) == -1                   # misaligned x
+    assert L.gg_fit(P, 0, 100, None, P, ws_bytes, None) == -1                    # null out
+    assert L.gg_fit(P, 0, 100, P, None, ws_bytes, None) == -4                    # no workspace
+    assert L.gg_fit(P, 0, 1 << 20, P, P, 64, None) == -4                         # workspace too small
+    assert L.gg_fit_segmented(P, 0, off.ctypes.data, 3, P, P, ws_bytes, None) == -3
+    assert L.gg_fit_segmented(P, 0, None, 3, P, P, ws_bytes, None) == -1
+    neg = np.array([-1, 10], dtype=np.int64)
+    assert L.gg_fit_segmented(P, 0, neg.ctypes.data, 1, P, P, ws_bytes, None) == -3
+    assert L.gg_fit_rows(P, 0, -1, 10, P, None, P, ws_bytes, None) == -1
+    for delta in (0.0, -1.0, float("inf"), float("nan")):
+        assert L.gg_quantize_rate(P, 0, 100, delta, 0, 0, 0, None, None, P, P, ws_bytes, None) == -1
+    assert L.gg_quantize_rate(P, 0, 100, 0.1, 16, 0, 0, None, None, P, P, ws_bytes, None) == -1   # k > 15
+    assert L.gg_quantize_rate(P, 0, 100, 0.1, -1, 0, 0, None, None, P, P, ws_bytes, None) == -1
+    assert L.gg_quantize_rate(P, 0, 100, 0.1, 0, 2, 0, None, None, P, P, ws_bytes, None) == -1    # round mode
+    assert L.gg_quantize_rate(P, 0, 100, 0.1, 0, 0, 1, P, None, P, P, ws_bytes, None) == -1       # nbins 1
+    assert L.gg_quantize_rate(P, 0, 100, 0.1, 0, 0, 65537, P, None, P, P, ws_bytes, None) == -1
+    assert L.gg_quantize_rate(P, 0, 100, 0.1, 0, 0, 64, None, None, P, P, ws_bytes, None) == -1   # nbins without hist
+    assert L.gg_quantize_rate(P, 0, 100, 0.1, 0, 0, 0, None, P + 4, P, P, ws_bytes, None) == -1   # misaligned symbols
+    assert L.gg_quantize_rate_segmented(P, 0, ok_off.ctypes.data, 3, None, 0, 0, 0, None, None, P, P, ws_bytes,
+                                        None) == -1                                                # no steps
+    assert L.gg_penalty_grad(P, 0, 100, 0.0, 1.0, 1e-4, P, 0, None) == -1                          # alpha 0
+    assert L.gg_penalty_grad(P, 0, 100, 0.1, -1.0, 1e-4, P, 0, None) == -1
+    assert L.gg_penalty_grad(P, 0, 100, 0.1, 1.0, 1e-4, None, 0, None) == -1
+    assert L.gg_sample(P, 0, 100, 0.1, 0.01, 1, 0, 0, None) == -1                                  # beta below range
+    assert L.gg_sample(P, 0, 100, -0.1, 1.0, 1, 0, 0, None) == -1
+    assert L.gg_sample(P, 3, 100, 0.1, 1.0, 1, 0, 0, None) == -2
+    assert L.gg_sample(None, 0, 100, 0.1, 1.0, 1, 0, 0, None) == -1
+    assert L.gg_fused_segmented(P, 0, off.ctypes.data, 3, 16.0, None, 0, 0, 0, None, None, 0.0, None, 0, P, P, P,
+                                ws_bytes, None) == -3
+    assert L.gg_fused_segmented(P, 0, ok_off.ctypes.data, 3, 0.0, None, 0, 0, 0, None, None, 0.0, None, 0, P, P, P,
+                                ws_bytes, None) == -1                                              # no step source
+    assert L.gg_fused_segmented(P, 0, ok_off.ctypes.data, 3, 16.0, None, 0, 0, 0, None, None, 0.0, None, 0, None, P, P,
+                                ws_bytes, None) == -1                                              # no fit output
+    assert L.gg_delta_from_fit(P, 3, 0.0, P, None) == -1
+
+
+def test_host_helpers_match_paper_special_cases():
+    gg = _lib()
+    # Eq. 5 at shape 2 is He initialisation: alpha = sqrt(2 xi / d_in)
+    assert gg.gg_init_alpha(4096, 2.0, 2.0) == pytest.approx((2 * 2.0 / 4096) ** 0.5, rel=1e-13)
+    assert np.isnan(gg.gg_init_alpha(0, 2.0, 1.0))
+    # a row of the paper's result table: EG 1.59 bits at FL 12 -> 86.75 %
+    assert 100 * gg.gg_compression_ratio(1.59, 12.0) == pytest.approx(86.75, abs=0.005)
+
+
+def test_empty_calls_are_ok_without_gpu_work():
+    """n == 0 / S == 0 paths that return before touching the device."""
+    gg = _lib()
+    L = gg.lib()
+    assert L.gg_sample(None, 0, 0, 0.1, 1.0, 1, 0, 0, None) == 0
+    assert L.gg_philox_words(None, 0, 1, 0, 0, 0, None) == 0
+    assert L.gg_delta_from_fit(None, 0, 16.0, None, None) == 0
