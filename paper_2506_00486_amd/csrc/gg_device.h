@@ -77,12 +77,26 @@ __device__ __forceinline__ V block_reduce(V v, Op op, V *slot) {
 // ---------------------------------------------------------------------------------------------
 struct bf16_t { uint16_t bits; };
 
+// The inputs are streamed exactly once per sweep, so their loads are marked non-temporal: on
+// gfx950 that keeps the stream from displacing L2 contents and measurably raises read bandwidth.
+#ifndef GG_STREAM_LOADS
+#define GG_STREAM_LOADS 1
+#endif
+typedef float gg_f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int gg_u4 __attribute__((ext_vector_type(4)));
+
 template <typename T> struct Elem;
 
 template <> struct Elem<float> {
     static constexpr int W = 4;
-    using raw = float4;
-    static __device__ __forceinline__ raw loadv(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+    using raw = gg_f4;
+    static __device__ __forceinline__ raw loadv(const float *p) {
+#if GG_STREAM_LOADS
+        return __builtin_nontemporal_load(reinterpret_cast<const gg_f4 *>(p));
+#else
+        return *reinterpret_cast<const gg_f4 *>(p);
+#endif
+    }
     static __device__ __forceinline__ void unpack(const raw &r, float (&v)[W]) {
         v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
     }
@@ -91,8 +105,14 @@ template <> struct Elem<float> {
 
 template <> struct Elem<bf16_t> {
     static constexpr int W = 8;
-    using raw = uint4;
-    static __device__ __forceinline__ raw loadv(const bf16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+    using raw = gg_u4;
+    static __device__ __forceinline__ raw loadv(const bf16_t *p) {
+#if GG_STREAM_LOADS
+        return __builtin_nontemporal_load(reinterpret_cast<const gg_u4 *>(p));
+#else
+        return *reinterpret_cast<const gg_u4 *>(p);
+#endif
+    }
     static __device__ __forceinline__ void unpack(const raw &r, float (&v)[W]) {
         // bf16 is the high half of an fp32: widening is a shift (even element) or a mask (odd)
         v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
@@ -171,6 +191,18 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
         k1 += 0xBB67AE85u;
     }
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// ln Gamma(x) for x > 0 in fp64: push the argument above 10 with Gamma(x) = Gamma(x+1)/x, then the
+// Stirling series  (x-1/2) ln x - x + ln(2 pi)/2 + sum_k B_2k / (2k (2k-1) x^(2k-1)).
+// Truncation error at x >= 10 is below 1e-16.
+__host__ __device__ __forceinline__ double lgamma_pos(double x) {
+    double prod = 1.0;
+    while (x < 10.0) { prod *= x; x += 1.0; }
+    const double xi = 1.0 / x, y = xi * xi;
+    const double series = xi * (1.0 / 12.0 - y * (1.0 / 360.0 - y * (1.0 / 1260.0 - y * (1.0 / 1680.0 -
+                          y * (1.0 / 1188.0 - y * (691.0 / 360360.0 - y * (1.0 / 156.0)))))));
+    return (x - 0.5) * log(x) - x + 0.91893853320467274178 + series - log(prod);
 }
 
 // top 23 bits of a word -> uniform in (0,1), exact in fp32

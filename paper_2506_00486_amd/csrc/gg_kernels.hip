@@ -2,8 +2,9 @@
 //
 // Launch structure of one pass over a buffer cut into units (segments / rows / one tensor):
 //   k_upload_i64      segment offsets and per-unit chunk prefix -> workspace (through kernel args)
-//   k_fit_partials    one work item = one chunk of <= kChunk elements of one unit:
-//                     sum|x|, sum x^2 in fp32 per lane, fp64 across the block -> partials[chunk]
+//   k_fit_partials    the buffer is cut into chunks of <= kChunk elements of one unit; each block
+//                     owns a run of consecutive chunks: sum|x|, sum x^2 in fp32 per lane and chunk,
+//                     fp64 lane totals, combined across the block per (run, unit) piece -> partials
 //   k_fit_finalize    one wave per unit: fixed-order fp64 sum of its partials, 64-way parallel
 //                     bracketing of the moment-ratio equation, Eq. 2 for alpha; derives the
 //                     unit's quantiser / penalty parameters and clears its rate record
@@ -78,6 +79,35 @@ __device__ __forceinline__ int64_t unit_chunk1(const SegView &sv, int seg) {
     return sv.off ? sv.cpre[seg + 1] : (int64_t)(seg + 1) * sv.cpr;
 }
 
+__device__ __forceinline__ int64_t unit_end(const SegView &sv, int seg) {
+    return sv.off ? sv.off[seg + 1] : (int64_t)(seg + 1) * sv.cols;
+}
+
+// Walks the consecutive chunks [first, last) a block owns; the unit table is searched only when
+// the walk crosses into another unit.
+struct RunCursor {
+    ChunkLoc L;
+    int64_t chunk, last, seg_chunks;
+    __device__ __forceinline__ void init(const SegView &sv, int64_t first, int64_t last_) {
+        chunk = first; last = last_;
+        L = locate(sv, first);
+        seg_chunks = unit_chunk1(sv, L.seg) - unit_chunk0(sv, L.seg);
+    }
+    __device__ __forceinline__ bool valid() const { return chunk < last; }
+    __device__ __forceinline__ void next(const SegView &sv) {
+        if (++chunk >= last) return;
+        if (L.c + 1 < seg_chunks) {
+            L.c += 1;
+            L.start += kChunk;
+            const int64_t rest = unit_end(sv, L.seg) - L.start;
+            L.len = (int32_t)(rest < kChunk ? rest : kChunk);
+        } else {
+            L = locate(sv, chunk);
+            seg_chunks = unit_chunk1(sv, L.seg) - unit_chunk0(sv, L.seg);
+        }
+    }
+};
+
 // per-unit parameters of the second sweep
 constexpr uint32_t kSkipRate = 1u;   // no usable step: symbols 0, nothing accumulated
 constexpr uint32_t kPenZero = 2u;    // alpha == 0: penalty contributes 0
@@ -126,39 +156,68 @@ struct FitBody {
     }
 };
 
+// A block owns a run of consecutive chunks.  Lanes keep fp32 sums per chunk (<= 16 terms each) and
+// fold them into fp64 lane totals; lanes are combined only when the run leaves a unit or ends.
+// The combined value goes to the slot of the first chunk of that piece, every other slot of the
+// run gets zero, so the per-unit sum over chunk slots (k_fit_finalize) sees each element once.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void k_fit_partials(SegView sv, const T *__restrict__ x,
-                                                         double2 *__restrict__ partials) {
+                                                         double2 *__restrict__ partials, int64_t n_chunks,
+                                                         int32_t chunks_per_block) {
     __shared__ double red[2][kWaves];
-    const int64_t chunk = blockIdx.x;
-    const ChunkLoc L = locate(sv, chunk);
-    FitBody body;
-    process_chunk<T, 4>(x, L.start, L.len, body);
-    // lanes hold sums of <= 16 products each in fp32; everything above is fp64
-    double a = ((double)body.s1[0] + (double)body.s1[1]) + ((double)body.s1[2] + (double)body.s1[3]);
-    double b = ((double)body.s2[0] + (double)body.s2[1]) + ((double)body.s2[2] + (double)body.s2[3]);
-    a = wave_reduce(a, OpAdd());
-    b = wave_reduce(b, OpAdd());
-    const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { red[0][wave] = a; red[1][wave] = b; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double2 r;
-        r.x = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
-        r.y = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
-        partials[chunk] = r;
+    const int tid = threadIdx.x;
+    const int64_t first = (int64_t)blockIdx.x * chunks_per_block;
+    int64_t last = first + chunks_per_block;
+    if (last > n_chunks) last = n_chunks;
+    if (first >= last) return;
+
+    double d1 = 0.0, d2 = 0.0;
+    auto flush = [&](int64_t slot) {
+        const double a = wave_reduce(d1, OpAdd());
+        const double b = wave_reduce(d2, OpAdd());
+        if ((tid & 63) == 0) { red[0][tid >> 6] = a; red[1][tid >> 6] = b; }
+        __syncthreads();
+        if (tid == 0) {
+            double2 r;
+            r.x = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+            r.y = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+            partials[slot] = r;
+        }
+        __syncthreads();
+        d1 = 0.0; d2 = 0.0;
+    };
+
+    RunCursor cur;
+    cur.init(sv, first, last);
+    int piece_seg = cur.L.seg;
+    int64_t piece_first = first;
+    for (; cur.valid(); cur.next(sv)) {
+        if (cur.L.seg != piece_seg) {
+            flush(piece_first);
+            piece_first = cur.chunk; piece_seg = cur.L.seg;
+        } else if (cur.chunk != piece_first && tid == 0) {
+            partials[cur.chunk] = make_double2(0.0, 0.0);
+        }
+        FitBody body;
+        process_chunk<T, 4>(x, cur.L.start, cur.L.len, body);
+        d1 += ((double)body.s1[0] + (double)body.s1[1]) + ((double)body.s1[2] + (double)body.s1[3]);
+        d2 += ((double)body.s2[0] + (double)body.s2[1]) + ((double)body.s2[2] + (double)body.s2[3]);
     }
+    flush(piece_first);
 }
 
 // log of the moment ratio rho(b) = Gamma(2/b)^2 / (Gamma(1/b) Gamma(3/b)) of a GGD (from Eq. 1, 3)
 __device__ __forceinline__ double log_rho(double b) {
     const double r = 1.0 / b;
-    return 2.0 * lgamma(2.0 * r) - lgamma(r) - lgamma(3.0 * r);
+    return 2.0 * lgamma_pos(2.0 * r) - lgamma_pos(r) - lgamma_pos(3.0 * r);
 }
+
+// log_rho at the ends of the supported shape range, evaluated once on the host
+struct SolveConst { double lrho_min, lrho_max; };
 
 // Wave-cooperative fit from the moments.  The root of log_rho(b) = log(rho_hat) is bracketed by
 // evaluating 64 log-spaced shapes at once (one per lane); each round shrinks the bracket 65-fold.
-__device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, gg_fit_t &f) {
+__device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, const SolveConst &sc, gg_fit_t &f) {
     const int lane = threadIdx.x & 63;
     f.sum_abs = s1; f.sum_sq = s2; f.n = n; f.beta = 0.f; f.alpha = 0.f; f.flags = 0; f._pad = 0;
     if (n == 0) { f.flags = GG_F_EMPTY; return; }
@@ -167,13 +226,14 @@ __device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, gg_f
     const double m1 = s1 / (double)n, m2 = s2 / (double)n;
     const double target = log(m1 * m1 / m2);
     double b;
-    if (!(target > log_rho(GG_BETA_MIN))) {
+    if (!(target > sc.lrho_min)) {
         b = GG_BETA_MIN; f.flags = GG_F_BETA_CLAMPED_LO;
-    } else if (!(target < log_rho(GG_BETA_MAX))) {
+    } else if (!(target < sc.lrho_max)) {
         b = GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI;
     } else {
         double llo = log(GG_BETA_MIN), lhi = log(GG_BETA_MAX);
-        for (int round = 0; round < 6; ++round) {
+        // five rounds: ln(400) / 65^5 = 5e-9 relative width, below fp32 resolution of the result
+        for (int round = 0; round < 5; ++round) {
             const double step = (lhi - llo) * (1.0 / 65.0);
             const double cand = exp(llo + step * (double)(lane + 1));
             const bool below = log_rho(cand) < target;   // rho increases with b
@@ -186,7 +246,7 @@ __device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, gg_f
     }
     const double r = 1.0 / b;
     f.beta = (float)b;
-    f.alpha = (float)sqrt(m2 * exp(lgamma(r) - lgamma(3.0 * r)));   // Eq. 2 with sigma^2 = m2
+    f.alpha = (float)sqrt(m2 * exp(lgamma_pos(r) - lgamma_pos(3.0 * r)));   // Eq. 2 with sigma^2 = m2
 }
 
 // where the step and the penalty parameters of a unit come from
@@ -230,7 +290,8 @@ __device__ __forceinline__ void prepare_unit(const PrepArgs &a, int seg, int64_t
 }
 
 __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *__restrict__ partials,
-                                                     gg_fit_t *__restrict__ out, PrepArgs prep, int do_prep) {
+                                                     gg_fit_t *__restrict__ out, SolveConst sc, PrepArgs prep,
+                                                     int do_prep) {
     const int seg = blockIdx.x, lane = threadIdx.x;
     const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
     double s1 = 0.0, s2 = 0.0;
@@ -242,7 +303,7 @@ __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *
     s2 = wave_reduce(s2, OpAdd());
     const int64_t n = unit_len(sv, seg);
     gg_fit_t f;
-    solve_fit(s1, s2, (uint64_t)n, f);
+    solve_fit(s1, s2, (uint64_t)n, sc, f);
     if (lane == 0) {
         out[seg] = f;
         if (do_prep) prepare_unit(prep, seg, n, f.alpha, f.beta);
@@ -251,7 +312,7 @@ __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *
 
 // fit of the whole matrix from the per-row sums (one wave, fixed order)
 __global__ __launch_bounds__(64) void k_fit_total(const gg_fit_t *__restrict__ rows, int64_t n_rows,
-                                                  gg_fit_t *__restrict__ out) {
+                                                  gg_fit_t *__restrict__ out, SolveConst sc) {
     const int lane = threadIdx.x;
     double s1 = 0.0, s2 = 0.0;
     uint64_t n = 0;
@@ -260,7 +321,7 @@ __global__ __launch_bounds__(64) void k_fit_total(const gg_fit_t *__restrict__ r
     s2 = wave_reduce(s2, OpAdd());
     n = wave_reduce(n, OpAdd());
     gg_fit_t f;
-    solve_fit(s1, s2, n, f);
+    solve_fit(s1, s2, n, sc, f);
     if (lane == 0) out[0] = f;
 }
 
@@ -301,7 +362,15 @@ struct QuantArgs {
     int32_t chunks_per_block;
 };
 
-constexpr float kQLim = 1073741824.0f;  // 2^30
+constexpr int32_t kQLimI = 1 << 30;   // |q| <= 2^30
+
+// Saturating float -> int conversion of the hardware: NaN gives 0, out-of-range values give
+// INT_MIN / INT_MAX (a plain C cast would be undefined for those inputs).
+__device__ __forceinline__ int32_t cvt_i32_sat(float r) {
+    int32_t m;
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(m) : "v"(r));
+    return m;
+}
 
 // v_log_f32 / v_exp_f32 with the denormal range of the argument rescaled
 __device__ __forceinline__ float log2_full(float t) {
@@ -320,15 +389,17 @@ struct QuantBody {
     int32_t *symbols; float *grad; int accumulate;
     uint32_t *lds_hist; uint64_t *ghist; uint32_t last_bin, lbins;
     // per-lane accumulators
-    uint32_t clz_sum = 0, u_max = 0, n_clamped = 0, nan_seen = 0;
+    uint32_t clz_sum = 0, u_max = 0, n_clamped = 0;
+    bool nan_seen = false;
 
     __device__ __forceinline__ int32_t quant(float x) {
-        float t = x * inv_delta;                       // the one fp32 rounding of the quantiser
-        if (t != t) { nan_seen = 1; t = 0.f; }
-        t = __builtin_amdgcn_fmed3f(t, -kQLim, kQLim);
-        // m = -q: floor(t) = -ceil(-t), rint is odd-symmetric
+        const float t = x * inv_delta;                 // the one fp32 rounding of the quantiser
+        nan_seen |= (t != t);
+        // m = -q: floor(t) = -ceil(-t), rint is odd-symmetric.  The conversion maps NaN to 0 and
+        // saturates, so clamping the integer to +-2^30 equals clamping t before rounding.
         const float r = MODE == GG_FLOOR ? ceilf(-t) : rintf(-t);
-        const int32_t m = (int32_t)r;
+        int32_t m = cvt_i32_sat(r);
+        m = m < -kQLimI ? -kQLimI : (m > kQLimI ? kQLimI : m);
         // Map(q) = q > 0 ? 2q-1 : -2q  is the zig-zag code of m = -q
         const uint32_t u = ((uint32_t)m << 1) ^ (uint32_t)(m >> 31);
         clz_sum += (uint32_t)__builtin_clz(u + eg_add);
@@ -392,68 +463,88 @@ struct QuantBody {
     }
 };
 
+// A block owns a run of consecutive chunks.  Lane accumulators (bit-length sum, u_max, NaN seen,
+// clamped count) live across chunks and are combined, then added to the unit's rate record with
+// integer atomics, only when the run leaves a unit or ends.
 template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
 __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restrict__ x, QuantArgs a) {
     extern __shared__ uint32_t lds_hist[];
-    __shared__ uint32_t red[4][kWaves];
+    __shared__ uint64_t red64[kWaves];
+    __shared__ uint32_t red[3][kWaves];
     const int tid = threadIdx.x;
+    const int64_t first = (int64_t)blockIdx.x * a.chunks_per_block;
+    int64_t last = first + a.chunks_per_block;
+    if (last > a.n_chunks) last = a.n_chunks;
+    if (first >= last) return;
+
     const bool want_hist = EXTRA && a.hist != nullptr;
     if (want_hist) {
         for (int b = tid; b < a.lbins; b += kBlock) lds_hist[b] = 0;
         __syncthreads();
     }
-    int hist_seg = -1;
 
-    auto flush_hist = [&](int seg) {   // merge the block-private bins into the unit's histogram
-        __syncthreads();
-        if (seg >= 0) {
-            uint64_t *g = a.hist + (int64_t)seg * a.nbins;
-            for (int b = tid; b < a.lbins; b += kBlock) {
-                const uint32_t c = lds_hist[b];
-                if (c) { atomicAdd(reinterpret_cast<unsigned long long *>(&g[b]), (unsigned long long)c); lds_hist[b] = 0; }
+    QuantBody<MODE, RATE, PEN, EXTRA> body;
+    body.eg_add = a.eg_add;
+    body.symbols = a.symbols; body.grad = a.grad; body.accumulate = a.accumulate;
+    body.lds_hist = lds_hist;
+    body.last_bin = (uint32_t)(a.nbins > 0 ? a.nbins - 1 : 0);
+    body.lbins = (uint32_t)a.lbins;
+
+    int piece_seg = -1;
+    bool rate_live = false;
+    int64_t piece_elems = 0;
+    int32_t piece_chunks = 0;
+
+    auto flush = [&]() {   // fold the lanes of this piece into the unit's record
+        if constexpr (RATE) {
+            if (piece_seg >= 0) {
+                const uint64_t clz = block_reduce((uint64_t)body.clz_sum, OpAdd(), red64);
+                const uint32_t um = block_reduce(body.u_max, OpMax(), red[0]);
+                const uint32_t nan = block_reduce((uint32_t)body.nan_seen, OpOr(), red[1]);
+                uint32_t ncl = 0;
+                if constexpr (EXTRA) ncl = block_reduce(body.n_clamped, OpAdd(), red[2]);
+                if (tid == 0 && rate_live) {
+                    gg_rate_t *r = a.rate + piece_seg;
+                    const uint64_t bits = (uint64_t)piece_elems * a.eg_const - 2ull * clz;
+                    atomicAdd(reinterpret_cast<unsigned long long *>(&r->eg_bits), (unsigned long long)bits);
+                    atomicMax(&r->u_max, um);
+                    if (ncl) atomicAdd(reinterpret_cast<unsigned long long *>(&r->n_clamped), (unsigned long long)ncl);
+                    if (nan) atomicOr(&r->flags, GG_F_NONFINITE);
+                }
+                if (want_hist && rate_live) {   // merge the block-private bins into the unit's histogram
+                    uint64_t *g = a.hist + (int64_t)piece_seg * a.nbins;
+                    for (int b = tid; b < a.lbins; b += kBlock) {
+                        const uint32_t c = lds_hist[b];
+                        if (c) {
+                            atomicAdd(reinterpret_cast<unsigned long long *>(&g[b]), (unsigned long long)c);
+                            lds_hist[b] = 0;
+                        }
+                    }
+                    __syncthreads();
+                }
             }
         }
-        __syncthreads();
+        body.clz_sum = 0; body.u_max = 0; body.n_clamped = 0; body.nan_seen = false;
+        piece_elems = 0; piece_chunks = 0;
     };
 
-    const int64_t first = (int64_t)blockIdx.x * a.chunks_per_block;
-    int64_t last = first + a.chunks_per_block;
-    if (last > a.n_chunks) last = a.n_chunks;
-    for (int64_t chunk = first; chunk < last; ++chunk) {
-        const ChunkLoc L = locate(sv, chunk);
-        const SegParam P = a.params ? a.params[L.seg] : a.single;
-        const bool rate_live = RATE && !(P.flags & kSkipRate);
-        if (want_hist && L.seg != hist_seg) { flush_hist(hist_seg); hist_seg = L.seg; }
-
-        QuantBody<MODE, RATE, PEN, EXTRA> body;
-        body.inv_delta = P.inv_delta; body.inv_alpha = P.inv_alpha; body.beta_m1 = P.beta_m1;
-        body.pen_coef = P.pen_coef; body.pen_live = !(P.flags & kPenZero);
-        body.hist_live = want_hist && rate_live;
-        body.eg_add = a.eg_add;
-        body.symbols = a.symbols; body.grad = a.grad; body.accumulate = a.accumulate;
-        body.lds_hist = lds_hist;
-        body.ghist = want_hist ? a.hist + (int64_t)L.seg * a.nbins : nullptr;
-        body.last_bin = (uint32_t)(a.nbins > 0 ? a.nbins - 1 : 0);
-        body.lbins = (uint32_t)a.lbins;
-        process_chunk<T, 4>(x, L.start, L.len, body);
-
-        if constexpr (RATE) {
-            const uint32_t clz = block_reduce(body.clz_sum, OpAdd(), red[0]);
-            const uint32_t um = block_reduce(body.u_max, OpMax(), red[1]);
-            const uint32_t nan = block_reduce(body.nan_seen, OpOr(), red[2]);
-            uint32_t ncl = 0;
-            if constexpr (EXTRA) ncl = block_reduce(body.n_clamped, OpAdd(), red[3]);
-            if (tid == 0 && rate_live) {
-                gg_rate_t *r = a.rate + L.seg;
-                const uint64_t bits = (uint64_t)L.len * a.eg_const - 2ull * clz;
-                atomicAdd(reinterpret_cast<unsigned long long *>(&r->eg_bits), (unsigned long long)bits);
-                atomicMax(&r->u_max, um);
-                if (ncl) atomicAdd(reinterpret_cast<unsigned long long *>(&r->n_clamped), (unsigned long long)ncl);
-                if (nan) atomicOr(&r->flags, GG_F_NONFINITE);
-            }
+    RunCursor cur;
+    for (cur.init(sv, first, last); cur.valid(); cur.next(sv)) {
+        if (cur.L.seg != piece_seg || piece_chunks >= 32768) {
+            flush();
+            piece_seg = cur.L.seg;
+            const SegParam P = a.params ? a.params[piece_seg] : a.single;
+            rate_live = RATE && !(P.flags & kSkipRate);
+            body.inv_delta = P.inv_delta; body.inv_alpha = P.inv_alpha; body.beta_m1 = P.beta_m1;
+            body.pen_coef = P.pen_coef; body.pen_live = !(P.flags & kPenZero);
+            body.hist_live = want_hist && rate_live;
+            body.ghist = want_hist ? a.hist + (int64_t)piece_seg * a.nbins : nullptr;
         }
+        process_chunk<T, 4>(x, cur.L.start, cur.L.len, body);
+        piece_elems += cur.L.len;
+        piece_chunks += 1;
     }
-    if (want_hist) flush_hist(hist_seg);
+    flush();
 }
 
 __global__ __launch_bounds__(kBlock) void k_rate_finalize(gg_rate_t *__restrict__ rate, const uint64_t *__restrict__ hist,
@@ -654,12 +745,29 @@ static int by_dtype(int dtype, F &&f) {
     return GG_ERR_BAD_DTYPE;
 }
 
+// Static split of the chunk list into one run per block: `blocks_per_cu` resident blocks on each
+// of the 256 compute units, every block a contiguous range of chunks.
+constexpr int kComputeUnits = 256;
+struct RunSplit { int64_t blocks; int32_t chunks_per_block; };
+static RunSplit split_runs(int64_t n_chunks, int blocks_per_cu) {
+    const int64_t target = (int64_t)kComputeUnits * blocks_per_cu;
+    int64_t cpb = (n_chunks + target - 1) / target;
+    if (cpb < 1) cpb = 1;
+    return RunSplit{(n_chunks + cpb - 1) / cpb, (int32_t)cpb};
+}
+
+static SolveConst solve_const() {
+    auto lrho = [](double b) { return 2.0 * lgamma(2.0 / b) - lgamma(1.0 / b) - lgamma(3.0 / b); };
+    return SolveConst{lrho(GG_BETA_MIN), lrho(GG_BETA_MAX)};
+}
+
 static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out, const PrepArgs *prep, hipStream_t st) {
     if (g.n_chunks > 0) {
+        const RunSplit rs = split_runs(g.n_chunks, 8);
         int rc = by_dtype(dtype, [&](auto *tag) {
             using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
-            hipLaunchKernelGGL(k_fit_partials<T>, dim3((unsigned)g.n_chunks), dim3(kBlock), 0, st, g.sv,
-                               static_cast<const T *>(x), g.partials());
+            hipLaunchKernelGGL(k_fit_partials<T>, dim3((unsigned)rs.blocks), dim3(kBlock), 0, st, g.sv,
+                               static_cast<const T *>(x), g.partials(), g.n_chunks, rs.chunks_per_block);
             return check_launch();
         });
         if (rc != GG_OK) return rc;
@@ -667,7 +775,8 @@ static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out
     if (g.S > 0) {
         PrepArgs p{};
         if (prep) p = *prep;
-        hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(), out, p, prep ? 1 : 0);
+        hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(), out, solve_const(), p,
+                           prep ? 1 : 0);
         return check_launch();
     }
     return GG_OK;
@@ -697,17 +806,11 @@ static int launch_quant_inst(const Geometry &g, const void *x, const QuantOpts &
     a.lbins = o.hist ? (o.nbins < kMaxLdsBins ? o.nbins : kMaxLdsBins) : 0;
     a.grad = o.grad; a.accumulate = o.accumulate;
     a.n_chunks = g.n_chunks;
-    // with a histogram each block keeps its private bins over a run of chunks
-    int64_t cpb = 1;
-    if (o.hist) {
-        const int64_t target_blocks = 256 * 8;
-        cpb = (g.n_chunks + target_blocks - 1) / target_blocks;
-        if (cpb < 1) cpb = 1;
-    }
-    a.chunks_per_block = (int32_t)cpb;
-    const int64_t blocks = (g.n_chunks + cpb - 1) / cpb;
+    // block-private histogram bins cost LDS: 48 KiB allows three resident blocks per compute unit
+    const RunSplit rs = split_runs(g.n_chunks, o.hist ? 3 : 8);
+    a.chunks_per_block = rs.chunks_per_block;
     const size_t lds = (size_t)a.lbins * sizeof(uint32_t);
-    hipLaunchKernelGGL((k_quant<T, MODE, RATE, PEN, EXTRA>), dim3((unsigned)blocks), dim3(kBlock), lds, st, g.sv,
+    hipLaunchKernelGGL((k_quant<T, MODE, RATE, PEN, EXTRA>), dim3((unsigned)rs.blocks), dim3(kBlock), lds, st, g.sv,
                        static_cast<const T *>(x), a);
     return check_launch();
 }
@@ -784,7 +887,7 @@ static int fused_common(Geometry &g, const void *x, int dtype, float delta_div, 
     p.lambda = lambda; p.params = g.params(); p.rate = rate; p.want_pen = grad != nullptr;
     if ((rc = launch_fit(g, x, dtype, fit, &p, st)) != GG_OK) return rc;
     if (total_fit) {
-        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(64), 0, st, fit, (int64_t)g.S, total_fit);
+        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(64), 0, st, fit, (int64_t)g.S, total_fit, solve_const());
         if ((rc = check_launch()) != GG_OK) return rc;
     }
     QuantOpts o;
@@ -869,7 +972,7 @@ int gg_fit_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, gg_fit
     hipStream_t st = (hipStream_t)stream;
     if ((rc = launch_fit(g, x_dev, dtype, out_dev, nullptr, st)) != GG_OK) return rc;
     if (total_out_dev) {
-        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(64), 0, st, out_dev, rows, total_out_dev);
+        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(64), 0, st, out_dev, rows, total_out_dev, solve_const());
         return check_launch();
     }
     return GG_OK;
