@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--extra", action="store_true", help="also time the penalty variant and the sampler")
     ap.add_argument("--cpu-sample-elems", type=int, default=380_000_000)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain device copy of known size (counter calibration under rocprofv3 --pmc)")
     return ap.parse_args()
 
 
@@ -127,6 +129,17 @@ def main():
                       + (" [1/64 scale]" if args.small else ""),
                       "elements": n, "segments": S, "input_generation_s": round(t_gen, 2)},
            "roofline": roofline}
+
+    if args.calibrate_copy:
+        # 2^28 fp32 = 1 GiB read + 1 GiB written by a plain copy kernel: what FETCH_SIZE / WRITE_SIZE
+        # report for it gives the scale of those counters on this machine
+        m = min(n, 1 << 28)
+        dst = torch.empty(m, dtype=torch.float32, device=dev)
+        for _ in range(3):
+            dst.copy_(flat[:m])
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes_each_way"] = 4 * m
+        del dst
 
     if args.extra:
         extra = {}

@@ -158,8 +158,8 @@ struct FitBody {
 
 // A block owns a run of consecutive chunks.  Lanes keep fp32 sums per chunk (<= 16 terms each) and
 // fold them into fp64 lane totals; lanes are combined only when the run leaves a unit or ends.
-// The combined value goes to the slot of the first chunk of that piece, every other slot of the
-// run gets zero, so the per-unit sum over chunk slots (k_fit_finalize) sees each element once.
+// The combined value of a (run, unit) piece goes to the slot of the piece's first chunk, which is
+// max(first chunk of the unit, first chunk of the run): k_fit_finalize visits exactly those slots.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void k_fit_partials(SegView sv, const T *__restrict__ x,
                                                          double2 *__restrict__ partials, int64_t n_chunks,
@@ -195,8 +195,6 @@ __global__ __launch_bounds__(kBlock) void k_fit_partials(SegView sv, const T *__
         if (cur.L.seg != piece_seg) {
             flush(piece_first);
             piece_first = cur.chunk; piece_seg = cur.L.seg;
-        } else if (cur.chunk != piece_first && tid == 0) {
-            partials[cur.chunk] = make_double2(0.0, 0.0);
         }
         FitBody body;
         process_chunk<T, 4>(x, cur.L.start, cur.L.len, body);
@@ -290,14 +288,19 @@ __device__ __forceinline__ void prepare_unit(const PrepArgs &a, int seg, int64_t
 }
 
 __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *__restrict__ partials,
-                                                     gg_fit_t *__restrict__ out, SolveConst sc, PrepArgs prep,
-                                                     int do_prep) {
+                                                     int32_t chunks_per_block, gg_fit_t *__restrict__ out,
+                                                     SolveConst sc, PrepArgs prep, int do_prep) {
     const int seg = blockIdx.x, lane = threadIdx.x;
     const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
     double s1 = 0.0, s2 = 0.0;
-    for (int64_t c = c0 + lane; c < c1; c += 64) {   // lane-strided, ascending: a fixed order
-        const double2 p = partials[c];
-        s1 += p.x; s2 += p.y;
+    if (c1 > c0) {
+        // one piece per run that overlaps the unit; lane-strided over runs, ascending: a fixed order
+        const int64_t r0 = c0 / chunks_per_block, r1 = (c1 - 1) / chunks_per_block;
+        for (int64_t r = r0 + lane; r <= r1; r += 64) {
+            const int64_t run_first = r * chunks_per_block;
+            const double2 p = partials[run_first > c0 ? run_first : c0];
+            s1 += p.x; s2 += p.y;
+        }
     }
     s1 = wave_reduce(s1, OpAdd());
     s2 = wave_reduce(s2, OpAdd());
@@ -761,9 +764,16 @@ static SolveConst solve_const() {
     return SolveConst{lrho(GG_BETA_MIN), lrho(GG_BETA_MAX)};
 }
 
+#ifndef GG_FIT_BLOCKS_PER_CU
+#define GG_FIT_BLOCKS_PER_CU 8
+#endif
+#ifndef GG_QUANT_BLOCKS_PER_CU
+#define GG_QUANT_BLOCKS_PER_CU 8
+#endif
+
 static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out, const PrepArgs *prep, hipStream_t st) {
+    const RunSplit rs = split_runs(g.n_chunks, GG_FIT_BLOCKS_PER_CU);
     if (g.n_chunks > 0) {
-        const RunSplit rs = split_runs(g.n_chunks, 8);
         int rc = by_dtype(dtype, [&](auto *tag) {
             using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
             hipLaunchKernelGGL(k_fit_partials<T>, dim3((unsigned)rs.blocks), dim3(kBlock), 0, st, g.sv,
@@ -775,8 +785,8 @@ static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out
     if (g.S > 0) {
         PrepArgs p{};
         if (prep) p = *prep;
-        hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(), out, solve_const(), p,
-                           prep ? 1 : 0);
+        hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(), rs.chunks_per_block,
+                           out, solve_const(), p, prep ? 1 : 0);
         return check_launch();
     }
     return GG_OK;
@@ -807,7 +817,7 @@ static int launch_quant_inst(const Geometry &g, const void *x, const QuantOpts &
     a.grad = o.grad; a.accumulate = o.accumulate;
     a.n_chunks = g.n_chunks;
     // block-private histogram bins cost LDS: 48 KiB allows three resident blocks per compute unit
-    const RunSplit rs = split_runs(g.n_chunks, o.hist ? 3 : 8);
+    const RunSplit rs = split_runs(g.n_chunks, o.hist ? 3 : GG_QUANT_BLOCKS_PER_CU);
     a.chunks_per_block = rs.chunks_per_block;
     const size_t lds = (size_t)a.lbins * sizeof(uint32_t);
     hipLaunchKernelGGL((k_quant<T, MODE, RATE, PEN, EXTRA>), dim3((unsigned)rs.blocks), dim3(kBlock), lds, st, g.sv,
