@@ -23,7 +23,9 @@ ALGO_BYTES_PER_ELEM = 8.0      # fp32 bucket: 4 B read by the moment sweep + 4 B
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this same command, scaled by a plain-copy calibration; the summaries live under profiles/.
 # None until measured for the kernel that currently ships.
-MEASURED_TRAFFIC_BYTES = None
+MEASURED_TRAFFIC_BYTES = {"fetch": 6174878720, "write": 144128,
+                          "note": "k_quant on the 1,543,655,424-element bucket: FETCH_SIZE 3015077.5 x 2 KiB "
+                                  "(factor from a 1 GiB copy), WRITE_SIZE 140.75 KiB; profiles/k_quant_c4_bucket.md"}
 
 
 def parse():
@@ -34,6 +36,7 @@ def parse():
     ap.add_argument("--small", action="store_true", help="1/64-scale bucket (quick functional run)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--extra", action="store_true", help="also time the penalty variant and the sampler")
+    ap.add_argument("--all", action="store_true", help="--extra plus the other BASELINE configurations (C1, C2, C3, C5)")
     ap.add_argument("--cpu-sample-elems", type=int, default=380_000_000)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of known size (counter calibration under rocprofv3 --pmc)")
@@ -52,6 +55,64 @@ def time_steps(fn, steps, torch):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     return wall_ms / steps, ev0.elapsed_time(ev1) / steps
+
+
+def other_configs(gg, gg_inputs, torch, dev, args):
+    """The remaining BASELINE configurations, each timed as one whole call (HIP events, 10 calls)."""
+    res = {}
+    reps = 10
+
+    def timed(fn):
+        fn()
+        return time_steps(fn, reps, torch)[1]
+
+    # C1: 1024x1024 fp32, fit + Delta=alpha/16 + histogram/entropy/EG bits + penalty written
+    n = 1 << 20
+    x = gg_inputs.make_tensor((n,), 0.02, 1.0, seed=0, device=dev)
+    ws = gg.Workspace(n, 1, device=dev)
+    grad = torch.empty(n, dtype=torch.float32, device=dev)
+    ms = timed(lambda: gg.gg_fused_segmented(x, [0, n], ws, delta_div=16.0, nbins=4096, lam=1e-4, grad=grad))
+    res["C1_1024x1024_f32_fit_hist_penalty"] = {"ms": round(ms, 4), "Gelem/s": round(n / ms / 1e6, 2),
+                                                "algorithmic_GB/s": round(12.0 * n / ms / 1e6, 1)}
+    # C2: 4096x11008 bf16 weight, fit + rate (Delta=alpha/32) + penalty -> fp32
+    n = 4096 * 11008
+    x = gg_inputs.make_tensor((n,), 0.015, 1.5, seed=1, device=dev, dtype=torch.bfloat16)
+    ws = gg.Workspace(n, 1, device=dev)
+    grad = torch.empty(n, dtype=torch.float32, device=dev)
+    ms = timed(lambda: gg.gg_fused_segmented(x, [0, n], ws, delta_div=32.0, lam=1e-4, grad=grad))
+    res["C2_4096x11008_bf16_fit_rate_penalty"] = {"ms": round(ms, 4), "Gelem/s": round(n / ms / 1e6, 2),
+                                                  "algorithmic_GB/s": round(8.0 * n / ms / 1e6, 1)}
+    # C3: [8*2048, 4096] bf16 activations with outliers: per-row + per-tensor fit, per-row rates, tensor histogram
+    rows, cols = 8 * 2048, 4096
+    n = rows * cols
+    x = gg_inputs.make_tensor((rows, cols), 0.5, 0.8, seed=2, device=dev, dtype=torch.bfloat16, outlier_frac=1e-3,
+                              outlier_scale=20.0).reshape(-1)
+    ws = gg.Workspace(n, rows, device=dev)
+    r0 = gg.gg_fused_rows(x, rows, cols, ws, delta_div=8.0, want_total=True)
+    tot_alpha = float(gg.fit_records(r0["total"])[0]["alpha"])
+    ms_rows = timed(lambda: gg.gg_fused_rows(x, rows, cols, ws, delta_div=8.0, want_total=True))
+    ms_hist = timed(lambda: gg.gg_quantize_rate(x, tot_alpha / 8.0, ws, nbins=32768))
+    res["C3_16384x4096_bf16_rows_fit_rate"] = {"ms": round(ms_rows, 4), "Gelem/s": round(n / ms_rows / 1e6, 2),
+                                               "algorithmic_GB/s": round(4.0 * n / ms_rows / 1e6, 1)}
+    res["C3_tensor_histogram_32768_bins"] = {"ms": round(ms_hist, 4), "Gelem/s": round(n / ms_hist / 1e6, 2),
+                                             "algorithmic_GB/s": round(2.0 * n / ms_hist / 1e6, 1)}
+    del x, grad
+    if not args.small:
+        # C5: 7B-shaped bf16 weight set, fused fit + penalty accumulated into fp32 (and write-only)
+        layout = gg_inputs.weights_7b()
+        flat, off, _, _ = gg_inputs.make_bucket(layout, seed=4, device=dev, dtype=torch.bfloat16,
+                                                alpha_range=(0.005, 0.03), beta_range=(0.6, 2.0), log_alpha=False)
+        n, S = int(off[-1]), len(layout)
+        ws = gg.Workspace(n, S, device=dev)
+        grad = torch.zeros(n, dtype=torch.float32, device=dev)
+        reps = 3
+        ms_acc = timed(lambda: gg.gg_fused_segmented(flat, off, ws, want_rate=False, lam=1e-4, grad=grad, accumulate=True))
+        ms_wr = timed(lambda: gg.gg_fused_segmented(flat, off, ws, want_rate=False, lam=1e-4, grad=grad, accumulate=False))
+        res["C5_7B_bf16_fit_penalty_accumulate"] = {"ms": round(ms_acc, 3), "Gelem/s": round(n / ms_acc / 1e6, 2),
+                                                    "algorithmic_GB/s": round(12.0 * n / ms_acc / 1e6, 1)}
+        res["C5_7B_bf16_fit_penalty_write"] = {"ms": round(ms_wr, 3), "Gelem/s": round(n / ms_wr / 1e6, 2),
+                                               "algorithmic_GB/s": round(8.0 * n / ms_wr / 1e6, 1)}
+    return res
 
 
 def main():
@@ -113,7 +174,7 @@ def main():
     algo_bytes_kernel = 4.0 * n
     achieved = algo_bytes_kernel / (ms_rate * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "k_quant (rate sweep)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None if args.small else MEASURED_TRAFFIC_BYTES,
                 "algorithmic_bytes_per_launch": algo_bytes_kernel, "avg_launch_ms": round(ms_rate, 4),
                 "fit_sweep_ms": round(ms_fit, 4),
                 "whole_pass": {"algorithmic_bytes": ALGO_BYTES_PER_ELEM * n, "ms": round(ms_ev, 4),
@@ -141,6 +202,8 @@ def main():
         out["calibration_copy_bytes_each_way"] = 4 * m
         del dst
 
+    if args.all:
+        args.extra = True
     if args.extra:
         extra = {}
         grad = torch.zeros(n, dtype=torch.float32, device=dev)
@@ -162,6 +225,9 @@ def main():
         step_sample()
         _, ms_s = time_steps(step_sample, 5, torch)
         extra["gg_sample_bf16"] = {"elements": ns, "ms": round(ms_s, 4), "Gsamples/s": round(ns / ms_s / 1e6, 2)}
+        if args.all:
+            del xs
+            extra.update(other_configs(gg, gg_inputs, torch, dev, args))
         out["extra"] = extra
 
     if not args.no_cpu:

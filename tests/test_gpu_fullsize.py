@@ -1,0 +1,161 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The 1.5-billion-element bucket is too large for the oracle to sweep whole within a test, so the
+oracle recomputes a sample of whole segments (every size class, first/last, the ones next to run
+boundaries) one by one, and properties that hold at any size cover the rest."""
+import numpy as np
+import pytest
+import torch
+
+import gg_inputs
+import oracle
+from parity import check_fit, check_penalty, check_rate, host_bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+@pytest.fixture(scope="module")
+def gg():
+    import paper_2506_00486_amd as m
+    m.lib()
+    return m
+
+
+def test_gradient_bucket_1p5b_fused_pass(gg):
+    layout = gg_inputs.gradient_bucket_1p5b()
+    assert len(layout) == 253
+    print("generating 1.5B-element bucket", flush=True)
+    flat, off, alpha, beta = gg_inputs.make_bucket(layout, seed=3, device=DEV)
+    n, S = int(off[-1]), len(layout)
+    assert n == 1_543_655_424
+    ws = gg.Workspace(n, S)
+    res = gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, eg_k=0)
+    torch.cuda.synchronize()
+    frec, rrec = gg.fit_records(res["fit"]), gg.rate_records(res["rate"])
+    print("pass done; checking properties", flush=True)
+
+    # properties at any size
+    sizes = np.diff(off)
+    assert np.array_equal(frec["n"], sizes.astype(np.uint64)) and np.array_equal(rrec["n"], sizes.astype(np.uint64))
+    assert not frec["flags"].any() and not rrec["flags"].any()
+    assert np.all(rrec["eg_bits"] >= rrec["n"]) and np.all(rrec["eg_bits"] <= 63 * rrec["n"])
+    assert np.array_equal(rrec["fl_bits"], np.array([max(1, int(u).bit_length()) for u in rrec["u_max"]], dtype=np.uint32))
+    assert np.array_equal(rrec["delta"], frec["alpha"] / np.float32(16.0))
+    big = sizes >= 100_000          # estimator noise is small there: the fit must recover the generating parameters
+    assert np.all(np.abs(frec["beta"][big] - beta[big]) < 0.03)
+    assert np.all(np.abs(frec["alpha"][big] / alpha[big] - 1.0) < 0.05)
+    # torch reductions as a second, independent look at the moments of every segment
+    for s in range(0, S, 11):
+        seg = flat[int(off[s]):int(off[s + 1])].double()
+        assert float(seg.abs().sum()) == pytest.approx(float(frec["sum_abs"][s]), rel=1e-6)
+        assert float((seg * seg).sum()) == pytest.approx(float(frec["sum_sq"][s]), rel=1e-6)
+
+    # oracle on sampled whole segments: every tensor kind of layers 0, 13, 27 (which straddle run boundaries
+    # differently), all 56 norm vectors, and the 233M-element embedding
+    sample = [s for s, seg in enumerate(layout) if seg.name.split(".")[0] in ("l0", "l13", "l27")]
+    sample += [s for s, seg in enumerate(layout) if "norm" in seg.name]
+    sample = sorted(set(sample)) + [S - 1]
+    for s in sample:
+        lo, hi = int(off[s]), int(off[s + 1])
+        print(f"oracle on {layout[s].name} ({hi - lo} elements)", flush=True)
+        hb = host_bits(flat[lo:hi])
+        check_fit(frec[s], oracle.fit(hb), layout[s].name)
+        r, _, _ = oracle.quantize_rate(hb, float(rrec[s]["delta"]))
+        check_rate(rrec[s], r, layout[s].name, entropy=False)
+
+    # same call again: bit-identical records (fixed reduction order, integer atomics)
+    res2 = gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, eg_k=0)
+    assert res2["fit"].cpu().numpy().tobytes() == res["fit"].cpu().numpy().tobytes()
+    assert res2["rate"].cpu().numpy().tobytes() == res["rate"].cpu().numpy().tobytes()
+
+
+def test_linear_weight_bf16_fit_rate_penalty(gg):
+    """4096 x 11008 bf16 weight: fit + rate with Delta = alpha/32 + penalty gradient written as fp32."""
+    n = 4096 * 11008
+    x = gg_inputs.make_tensor((n,), 0.015, 1.5, seed=1, device=DEV, dtype=torch.bfloat16)
+    ws = gg.Workspace(n, 1)
+    grad = torch.empty(n, dtype=torch.float32, device=DEV)
+    res = gg.gg_fused_segmented(x, [0, n], ws, delta_div=32.0, nbins=4096, lam=1e-4, grad=grad)
+    frec, rrec = gg.fit_records(res["fit"])[0], gg.rate_records(res["rate"])[0]
+    hb = host_bits(x)
+    check_fit(frec, oracle.fit(hb), "weight")
+    r, ohist, _ = oracle.quantize_rate(hb, float(rrec["delta"]), nbins=4096)
+    check_rate(rrec, r, "weight")
+    assert np.array_equal(res["hist"].cpu().numpy().view(np.uint64), ohist)
+    # penalty: oracle on three slices (start, an unaligned middle, the tail)
+    g = res["grad"]
+    for lo, hi in ((0, 200_000), (20_000_003, 20_300_001), (n - 150_001, n)):
+        og = oracle.penalty_grad(hb[lo:hi], frec["alpha"], frec["beta"], 1e-4)
+        check_penalty(g[lo:hi].cpu().numpy(), og, f"slice {lo}")
+    # odd symmetry and sign agreement everywhere
+    xf = x.float()
+    assert bool(((g > 0) == (xf > 0)).all()) and bool(((g < 0) == (xf < 0)).all())
+
+
+def test_activation_tensor_rows_and_histogram(gg):
+    """[8*2048, 4096] bf16 activations with x20 outliers: per-row and per-tensor fit in one sweep,
+    per-tensor histogram + entropy, per-row rates."""
+    rows, cols = 8 * 2048, 4096
+    x = gg_inputs.make_tensor((rows, cols), 0.5, 0.8, seed=2, device=DEV, dtype=torch.bfloat16, outlier_frac=1e-3,
+                              outlier_scale=20.0).reshape(-1)
+    ws = gg.Workspace(rows * cols, rows)
+    res = gg.gg_fused_rows(x, rows, cols, ws, delta_div=8.0, want_total=True)
+    frec, rrec, tot = gg.fit_records(res["fit"]), gg.rate_records(res["rate"]), gg.fit_records(res["total"])[0]
+    hb = host_bits(x)
+    check_fit(tot, oracle.fit(hb), "tensor")
+    for r_ in list(range(0, rows, 257)) + [rows - 1]:
+        xs = hb[r_ * cols:(r_ + 1) * cols]
+        check_fit(frec[r_], oracle.fit(xs), f"row {r_}")
+        r, _, _ = oracle.quantize_rate(xs, float(rrec[r_]["delta"]))
+        check_rate(rrec[r_], r, f"row {r_}", entropy=False)
+    assert int(frec["n"].sum()) == rows * cols and int(tot["n"]) == rows * cols
+    delta = float(np.float32(tot["alpha"]) / np.float32(8.0))
+    out, hist, _ = gg.gg_quantize_rate(x, delta, ws, nbins=32768)
+    r, ohist, _ = oracle.quantize_rate(hb, delta, nbins=32768)
+    check_rate(gg.rate_records(out)[0], r, "tensor")
+    assert np.array_equal(hist.cpu().numpy().view(np.uint64), ohist)
+
+
+def test_weights_7b_fit_penalty_accumulate_and_resample(gg):
+    """7B-shaped bf16 weight set (290 segments, 6.7B elements): fused fit + penalty accumulated into an
+    fp32 gradient buffer; one layer re-drawn with the GG sampler at the Eq. 5 scale."""
+    layout = gg_inputs.weights_7b()
+    assert len(layout) == 290
+    print("generating 6.7B-element bf16 weight set", flush=True)
+    flat, off, alpha, beta = gg_inputs.make_bucket(layout, seed=4, device=DEV, dtype=torch.bfloat16,
+                                                   alpha_range=(0.005, 0.03), beta_range=(0.6, 2.0), log_alpha=False)
+    n, S = int(off[-1]), len(layout)
+    assert n == 6_738_411_520
+    ws = gg.Workspace(n, S)
+    grad = torch.full((n,), 0.25, dtype=torch.float32, device=DEV)
+    res = gg.gg_fused_segmented(flat, off, ws, want_rate=False, lam=1e-4, grad=grad, accumulate=True)
+    torch.cuda.synchronize()
+    frec = gg.fit_records(res["fit"])
+    assert np.array_equal(frec["n"], np.diff(off).astype(np.uint64)) and not frec["flags"].any()
+    big = np.diff(off) >= 100_000
+    assert np.all(np.abs(frec["beta"][big] - beta[big]) < 0.03)
+    for s in (0, 1, 7, 8, 145, 288, 289):
+        lo, hi = int(off[s]), int(off[s + 1])
+        m = min(hi - lo, 3_000_000)
+        print(f"oracle on {layout[s].name} (first {m} of {hi - lo})", flush=True)
+        hb_full = host_bits(flat[lo:hi])
+        check_fit(frec[s], oracle.fit(hb_full), layout[s].name)
+        base = np.full(m, 0.25, dtype=np.float32)
+        pen = oracle.penalty_grad(hb_full[:m], frec[s]["alpha"], frec[s]["beta"], 1e-4)
+        og = oracle.penalty_grad(hb_full[:m], frec[s]["alpha"], frec[s]["beta"], 1e-4, grad=base, accumulate=True)
+        check_penalty(res["grad"][lo:lo + m].cpu().numpy(), og, layout[s].name, penalty=pen)
+    del grad, res
+    # re-sample layer 0 (9 tensors) at the GG-init scale of its fan-in, shape = the fitted one
+    fan_in = {"q": 4096, "k": 4096, "v": 4096, "o": 4096, "gate": 4096, "up": 4096, "down": 11008}
+    for s in range(7):
+        kind = layout[s].name.split(".")[1]
+        shape = float(frec[s]["beta"])
+        a = gg.gg_init_alpha(fan_in[kind], shape, 1.0)
+        lo, hi = int(off[s]), int(off[s + 1])
+        gg.gg_sample(hi - lo, a, shape, seed=4, stream_id=s, out=flat[lo:hi])
+    rec = gg.fit_records(gg.gg_fit_segmented(flat, off[:8], ws))
+    for s in range(7):
+        kind = layout[s].name.split(".")[1]
+        assert abs(float(rec[s]["beta"]) - float(frec[s]["beta"])) < 0.03
+        assert float(rec[s]["sum_sq"]) / float(rec[s]["n"]) == pytest.approx(1.0 / fan_in[kind], rel=0.03)   # Eq. 5
