@@ -84,11 +84,15 @@ struct bf16_t { uint16_t bits; };
 #endif
 typedef float gg_f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int gg_u4 __attribute__((ext_vector_type(4)));
+typedef int gg_i4 __attribute__((ext_vector_type(4)));
+
+typedef unsigned int gg_u2 __attribute__((ext_vector_type(2)));
 
 template <typename T> struct Elem;
 
 template <> struct Elem<float> {
     static constexpr int W = 4;
+    using type = float;
     using raw = gg_f4;
     static __device__ __forceinline__ raw loadv(const float *p) {
 #if GG_STREAM_LOADS
@@ -105,6 +109,7 @@ template <> struct Elem<float> {
 
 template <> struct Elem<bf16_t> {
     static constexpr int W = 8;
+    using type = bf16_t;
     using raw = gg_u4;
     static __device__ __forceinline__ raw loadv(const bf16_t *p) {
 #if GG_STREAM_LOADS
@@ -125,6 +130,28 @@ template <> struct Elem<bf16_t> {
     }
 };
 
+// bf16 with four elements (8 bytes) per lane: used where every element produces a 4-byte output,
+// so that a lane's outputs are one 16-byte store and a wave's store instruction covers whole lines.
+struct ElemBf16x4 {
+    static constexpr int W = 4;
+    using type = bf16_t;
+    using raw = gg_u2;
+    static __device__ __forceinline__ raw loadv(const bf16_t *p) {
+#if GG_STREAM_LOADS
+        return __builtin_nontemporal_load(reinterpret_cast<const gg_u2 *>(p));
+#else
+        return *reinterpret_cast<const gg_u2 *>(p);
+#endif
+    }
+    static __device__ __forceinline__ void unpack(const raw &r, float (&v)[W]) {
+        v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+    }
+    static __device__ __forceinline__ float load1(const bf16_t *p) {
+        return __uint_as_float((uint32_t)p->bits << 16);
+    }
+};
+
 // fp32 -> bf16, round to nearest even, NaN kept quiet
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     uint32_t b = __float_as_uint(f);
@@ -135,42 +162,45 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 
 // ---------------------------------------------------------------------------------------------
 // chunk walker.  Elements [start, start+len) of x are visited once each by the block:
-// a scalar head up to the first 16-byte boundary, 128-bit vectors (U loads in flight per
+// a scalar head up to the first vector boundary, W-element vectors (U loads in flight per
 // lane), and a scalar tail.  `x` itself must be 16-byte aligned, so the boundary is a
 // property of the element index.  body.vec(v, idx) gets W consecutive elements starting at
-// element index idx (a multiple of W); body.one(v, idx) gets one.
+// element index idx (a multiple of W); body.one(v, idx) gets one.  E is the element policy
+// (Elem<float>, Elem<bf16_t>, ElemBf16x4).
 // ---------------------------------------------------------------------------------------------
-template <typename T, int U, typename Body>
-__device__ __forceinline__ void process_chunk(const T *__restrict__ x, int64_t start, int len, Body &body) {
-    constexpr int W = Elem<T>::W;
+template <typename E, int U, typename Body>
+__device__ __forceinline__ void process_chunk(const typename E::type *__restrict__ x, int64_t start, int len,
+                                              Body &body) {
+    using T = typename E::type;
+    constexpr int W = E::W;
     const int tid = threadIdx.x;
     int head = (int)((W - (int)(start % W)) % W);
     if (head > len) head = len;
-    if (tid < head) body.one(Elem<T>::load1(x + start + tid), start + tid);
+    if (tid < head) body.one(E::load1(x + start + tid), start + tid);
 
     const int64_t vstart = start + head;
     const int nvec = (len - head) / W;
     const T *__restrict__ p = x + vstart;
     int i = tid;
     for (; i + (U - 1) * kBlock < nvec; i += U * kBlock) {
-        typename Elem<T>::raw r[U];
+        typename E::raw r[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) r[u] = Elem<T>::loadv(p + (int64_t)(i + u * kBlock) * W);
+        for (int u = 0; u < U; ++u) r[u] = E::loadv(p + (int64_t)(i + u * kBlock) * W);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float v[W];
-            Elem<T>::unpack(r[u], v);
+            E::unpack(r[u], v);
             body.vec(v, vstart + (int64_t)(i + u * kBlock) * W);
         }
     }
     for (; i < nvec; i += kBlock) {
-        typename Elem<T>::raw r = Elem<T>::loadv(p + (int64_t)i * W);
+        typename E::raw r = E::loadv(p + (int64_t)i * W);
         float v[W];
-        Elem<T>::unpack(r, v);
+        E::unpack(r, v);
         body.vec(v, vstart + (int64_t)i * W);
     }
     const int done = head + nvec * W;
-    if (tid < len - done) body.one(Elem<T>::load1(x + start + done + tid), start + done + tid);
+    if (tid < len - done) body.one(E::load1(x + start + done + tid), start + done + tid);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kBlock) void k_fit_partials(SegView sv, const T *__
             piece_first = cur.chunk; piece_seg = cur.L.seg;
         }
         FitBody body;
-        process_chunk<T, 4>(x, cur.L.start, cur.L.len, body);
+        process_chunk<Elem<T>, 4>(x, cur.L.start, cur.L.len, body);
         d1 += ((double)body.s1[0] + (double)body.s1[1]) + ((double)body.s1[2] + (double)body.s1[3]);
         d2 += ((double)body.s2[0] + (double)body.s2[1]) + ((double)body.s2[2] + (double)body.s2[3]);
     }
@@ -245,6 +245,39 @@ __device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, cons
     const double r = 1.0 / b;
     f.beta = (float)b;
     f.alpha = (float)sqrt(m2 * exp(lgamma_pos(r) - lgamma_pos(3.0 * r)));   // Eq. 2 with sigma^2 = m2
+}
+
+// One-lane fit from the moments, for buffers cut into thousands of units (rows of an activation
+// matrix), where total work matters more than the latency of a single solve: bracketed secant
+// steps (Illinois variant) on g(l) = log_rho(e^l) - target over l = ln b; 8-12 evaluations reach
+// 1e-9 where the 64-way bracketing spends 320.
+__device__ __forceinline__ void solve_fit_lane(double s1, double s2, uint64_t n, const SolveConst &sc, gg_fit_t &f) {
+    f.sum_abs = s1; f.sum_sq = s2; f.n = n; f.beta = 0.f; f.alpha = 0.f; f.flags = 0; f._pad = 0;
+    if (n == 0) { f.flags = GG_F_EMPTY; return; }
+    if (!isfinite(s1) || !isfinite(s2)) { f.flags = GG_F_NONFINITE; f.beta = 2.f; return; }
+    if (s2 == 0.0) { f.flags = GG_F_DEGENERATE; f.beta = 2.f; return; }
+    const double m1 = s1 / (double)n, m2 = s2 / (double)n;
+    const double target = log(m1 * m1 / m2);
+    double b;
+    if (!(target > sc.lrho_min)) {
+        b = GG_BETA_MIN; f.flags = GG_F_BETA_CLAMPED_LO;
+    } else if (!(target < sc.lrho_max)) {
+        b = GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI;
+    } else {
+        double la = log(GG_BETA_MIN), lb = log(GG_BETA_MAX);
+        double fa = sc.lrho_min - target, fb = sc.lrho_max - target;   // fa < 0 < fb
+        for (int it = 0; it < 64; ++it) {
+            const double lc = (fa * lb - fb * la) / (fa - fb);
+            const double fc = log_rho(exp(lc)) - target;
+            if ((fc < 0.0) != (fb < 0.0)) { la = lb; fa = fb; } else { fa *= 0.5; }
+            lb = lc; fb = fc;
+            if (fc == 0.0 || fabs(lb - la) < 2e-9) break;
+        }
+        b = exp(lb);
+    }
+    const double r = 1.0 / b;
+    f.beta = (float)b;
+    f.alpha = (float)sqrt(m2 * exp(lgamma_pos(r) - lgamma_pos(3.0 * r)));
 }
 
 // where the step and the penalty parameters of a unit come from
@@ -311,6 +344,29 @@ __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *
         out[seg] = f;
         if (do_prep) prepare_unit(prep, seg, n, f.alpha, f.beta);
     }
+}
+
+// the same finalisation with one lane per unit (many small units)
+__global__ __launch_bounds__(64) void k_fit_finalize_lanes(SegView sv, const double2 *__restrict__ partials,
+                                                           int32_t chunks_per_block, gg_fit_t *__restrict__ out,
+                                                           SolveConst sc, PrepArgs prep, int do_prep) {
+    const int seg = blockIdx.x * 64 + threadIdx.x;
+    if (seg >= sv.S) return;
+    const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
+    double s1 = 0.0, s2 = 0.0;
+    if (c1 > c0) {
+        const int64_t r0 = c0 / chunks_per_block, r1 = (c1 - 1) / chunks_per_block;
+        for (int64_t r = r0; r <= r1; ++r) {
+            const int64_t run_first = r * chunks_per_block;
+            const double2 p = partials[run_first > c0 ? run_first : c0];
+            s1 += p.x; s2 += p.y;
+        }
+    }
+    const int64_t n = unit_len(sv, seg);
+    gg_fit_t f;
+    solve_fit_lane(s1, s2, (uint64_t)n, sc, f);
+    out[seg] = f;
+    if (do_prep) prepare_unit(prep, seg, n, f.alpha, f.beta);
 }
 
 // fit of the whole matrix from the per-row sums (one wave, fixed order)
@@ -382,6 +438,21 @@ __device__ __forceinline__ float log2_full(float t) {
     return tiny ? l - 64.0f : l;
 }
 
+// Outputs are written once and not re-read by this library: streaming (non-temporal) stores.  Every
+// output-writing kernel handles four elements per lane, so a wave's store instruction covers 1 KiB
+// of whole cache lines; with eight per lane each instruction would cover only every other 16
+// bytes, and such partial-line streaming stores were measured to halve the write bandwidth.
+template <int W, typename V>
+__device__ __forceinline__ void stream_store(V v, V *p) {
+    static_assert(W == 4, "output-writing kernels use four elements per lane");
+    __builtin_nontemporal_store(v, p);
+}
+template <int W, typename V>
+__device__ __forceinline__ V stream_load(const V *p) {
+    static_assert(W == 4, "output-writing kernels use four elements per lane");
+    return __builtin_nontemporal_load(p);
+}
+
 template <int MODE, bool RATE, bool PEN, bool EXTRA>
 struct QuantBody {
     // unit parameters
@@ -435,21 +506,20 @@ struct QuantBody {
             if constexpr (EXTRA) {
                 if (symbols) {
 #pragma unroll
-                    for (int j = 0; j < W; j += 4)
-                        *reinterpret_cast<int4 *>(symbols + idx + j) = make_int4(q[j], q[j + 1], q[j + 2], q[j + 3]);
+                    for (int j = 0; j < W; j += 4) {
+                        gg_i4 qv = {q[j], q[j + 1], q[j + 2], q[j + 3]};
+                        stream_store<W>(qv, reinterpret_cast<gg_i4 *>(symbols + idx + j));
+                    }
                 }
             }
         }
         if constexpr (PEN) {
 #pragma unroll
             for (int j = 0; j < W; j += 4) {
-                float4 g = make_float4(penalty(v[j]), penalty(v[j + 1]), penalty(v[j + 2]), penalty(v[j + 3]));
-                float4 *dst = reinterpret_cast<float4 *>(grad + idx + j);
-                if (accumulate) {
-                    const float4 o = *dst;
-                    g.x += o.x; g.y += o.y; g.z += o.z; g.w += o.w;
-                }
-                *dst = g;
+                gg_f4 g = {penalty(v[j]), penalty(v[j + 1]), penalty(v[j + 2]), penalty(v[j + 3])};
+                gg_f4 *dst = reinterpret_cast<gg_f4 *>(grad + idx + j);
+                if (accumulate) g += stream_load<W>(dst);
+                stream_store<W>(g, dst);
             }
         }
     }
@@ -543,7 +613,11 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
             body.hist_live = want_hist && rate_live;
             body.ghist = want_hist ? a.hist + (int64_t)piece_seg * a.nbins : nullptr;
         }
-        process_chunk<T, 4>(x, cur.L.start, cur.L.len, body);
+        // kernels that write one 4-byte output per element read bf16 eight bytes per lane (see ElemBf16x4)
+        if constexpr (sizeof(T) == 2 && (PEN || EXTRA))
+            process_chunk<ElemBf16x4, 8>(x, cur.L.start, cur.L.len, body);
+        else
+            process_chunk<Elem<T>, 4>(x, cur.L.start, cur.L.len, body);
         piece_elems += cur.L.len;
         piece_chunks += 1;
     }
@@ -751,6 +825,7 @@ static int by_dtype(int dtype, F &&f) {
 // Static split of the chunk list into one run per block: `blocks_per_cu` resident blocks on each
 // of the 256 compute units, every block a contiguous range of chunks.
 constexpr int kComputeUnits = 256;
+constexpr int kManyUnits = 2048;   // from here on the finalisation uses one lane per unit instead of one wave
 struct RunSplit { int64_t blocks; int32_t chunks_per_block; };
 static RunSplit split_runs(int64_t n_chunks, int blocks_per_cu) {
     const int64_t target = (int64_t)kComputeUnits * blocks_per_cu;
@@ -785,8 +860,12 @@ static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out
     if (g.S > 0) {
         PrepArgs p{};
         if (prep) p = *prep;
-        hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(), rs.chunks_per_block,
-                           out, solve_const(), p, prep ? 1 : 0);
+        if (g.S >= kManyUnits)
+            hipLaunchKernelGGL(k_fit_finalize_lanes, dim3((unsigned)((g.S + 63) / 64)), dim3(64), 0, st, g.sv, g.partials(),
+                               rs.chunks_per_block, out, solve_const(), p, prep ? 1 : 0);
+        else
+            hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(),
+                               rs.chunks_per_block, out, solve_const(), p, prep ? 1 : 0);
         return check_launch();
     }
     return GG_OK;

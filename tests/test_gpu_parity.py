@@ -379,3 +379,36 @@ def test_fit_only_and_penalty_only_fused_modes(gg):
         lo, hi = int(off[s]), int(off[s + 1])
         check_fit(frec[s], oracle.fit(hb[lo:hi]), segs[s].name)
         check_penalty(g[lo:hi], oracle.penalty_grad(hb[lo:hi], frec[s]["alpha"], frec[s]["beta"], 1e-4), segs[s].name)
+
+
+def test_many_small_units_use_the_per_lane_solver(gg):
+    """More than 2048 units switch the finalisation to one lane per unit; results must not change."""
+    rng = np.random.default_rng(5)
+    sizes = rng.integers(0, 400, size=3000)
+    sizes[17] = 40_000                      # one unit spanning several chunks among the small ones
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(21)
+    x = torch.empty(n, device=DEV)
+    betas = rng.uniform(0.4, 3.0, size=sizes.size)
+    for s in range(0, sizes.size, 100):     # a shape per group of 100 units
+        lo, hi = int(off[s]), int(off[min(s + 100, sizes.size)])
+        x[lo:hi] = gg_inputs.gg_torch(hi - lo, 0.01, float(betas[s]), gen, DEV)
+    ws = gg.Workspace(n, sizes.size)
+    res = gg.gg_fused_segmented(x, off, ws, delta_div=16.0)
+    frec, rrec = gg.fit_records(res["fit"]), gg.rate_records(res["rate"])
+    hb = host_bits(x)
+    fits, rates = oracle.fused_segmented(hb, off, delta_div=0.0, delta=rrec["delta"].copy())
+    for s in range(sizes.size):
+        check_fit(frec[s], fits[s], f"unit {s}")
+        if frec[s]["alpha"] > 0:
+            check_rate(rrec[s], rates[s], f"unit {s}", entropy=False)
+    # rows path with the same switch
+    rows, cols = 2500, 96
+    xr = make(rows * cols, 0.5, 0.8, seed=3, dtype=torch.bfloat16)
+    wsr = gg.Workspace(rows * cols, rows)
+    rec = gg.fit_records(gg.gg_fit_rows(xr, rows, cols, wsr))
+    hbr = host_bits(xr)
+    for r_ in range(0, rows, 7):
+        check_fit(rec[r_], oracle.fit(hbr[r_ * cols:(r_ + 1) * cols]), f"row {r_}")
