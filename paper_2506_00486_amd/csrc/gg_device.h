@@ -13,7 +13,10 @@ namespace gg {
 
 constexpr int kBlock = 256;          // threads per workgroup: 4 wave64
 constexpr int kWaves = kBlock / 64;
-constexpr int kChunk = 16384;        // elements per work item (64 KiB of fp32, 32 KiB of bf16)
+#ifndef GG_CHUNK
+#define GG_CHUNK 16384
+#endif
+constexpr int kChunk = GG_CHUNK;     // elements per work item (64 KiB of fp32, 32 KiB of bf16)
 
 // ---------------------------------------------------------------------------------------------
 // lane exchange

@@ -25,6 +25,14 @@
 #include "../../include/gg.h"
 #include "gg_device.h"
 
+// 128-bit loads each lane keeps in flight in the two sweeps (tuned on MI355X)
+#ifndef GG_U_FIT
+#define GG_U_FIT 8
+#endif
+#ifndef GG_U_QUANT
+#define GG_U_QUANT 8
+#endif
+
 namespace gg {
 
 // ---------------------------------------------------------------------------------------------
@@ -197,7 +205,7 @@ __global__ __launch_bounds__(kBlock) void k_fit_partials(SegView sv, const T *__
             piece_first = cur.chunk; piece_seg = cur.L.seg;
         }
         FitBody body;
-        process_chunk<Elem<T>, 4>(x, cur.L.start, cur.L.len, body);
+        process_chunk<Elem<T>, GG_U_FIT>(x, cur.L.start, cur.L.len, body);
         d1 += ((double)body.s1[0] + (double)body.s1[1]) + ((double)body.s1[2] + (double)body.s1[3]);
         d2 += ((double)body.s2[0] + (double)body.s2[1]) + ((double)body.s2[2] + (double)body.s2[3]);
     }
@@ -617,7 +625,7 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
         if constexpr (sizeof(T) == 2 && (PEN || EXTRA))
             process_chunk<ElemBf16x4, 8>(x, cur.L.start, cur.L.len, body);
         else
-            process_chunk<Elem<T>, 4>(x, cur.L.start, cur.L.len, body);
+            process_chunk<Elem<T>, (sizeof(T) == 2 ? GG_U_QUANT / 2 : GG_U_QUANT)>(x, cur.L.start, cur.L.len, body);
         piece_elems += cur.L.len;
         piece_chunks += 1;
     }
@@ -834,6 +842,14 @@ static RunSplit split_runs(int64_t n_chunks, int blocks_per_cu) {
     return RunSplit{(n_chunks + cpb - 1) / cpb, (int32_t)cpb};
 }
 
+// resident blocks of `kernel` per compute unit, capped at `cap` (a pure function of the code object)
+template <typename K>
+static int resident_blocks(K kernel, size_t dyn_lds, int cap) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, dyn_lds) != hipSuccess || n < 1) n = 1;
+    return n < cap ? n : cap;
+}
+
 static SolveConst solve_const() {
     auto lrho = [](double b) { return 2.0 * lgamma(2.0 / b) - lgamma(1.0 / b) - lgamma(3.0 / b); };
     return SolveConst{lrho(GG_BETA_MIN), lrho(GG_BETA_MAX)};
@@ -847,7 +863,9 @@ static SolveConst solve_const() {
 #endif
 
 static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out, const PrepArgs *prep, hipStream_t st) {
-    const RunSplit rs = split_runs(g.n_chunks, GG_FIT_BLOCKS_PER_CU);
+    const int bpc = dtype == GG_BF16 ? resident_blocks(k_fit_partials<bf16_t>, 0, GG_FIT_BLOCKS_PER_CU)
+                                     : resident_blocks(k_fit_partials<float>, 0, GG_FIT_BLOCKS_PER_CU);
+    const RunSplit rs = split_runs(g.n_chunks, bpc);
     if (g.n_chunks > 0) {
         int rc = by_dtype(dtype, [&](auto *tag) {
             using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
@@ -895,10 +913,11 @@ static int launch_quant_inst(const Geometry &g, const void *x, const QuantOpts &
     a.lbins = o.hist ? (o.nbins < kMaxLdsBins ? o.nbins : kMaxLdsBins) : 0;
     a.grad = o.grad; a.accumulate = o.accumulate;
     a.n_chunks = g.n_chunks;
-    // block-private histogram bins cost LDS: 48 KiB allows three resident blocks per compute unit
-    const RunSplit rs = split_runs(g.n_chunks, o.hist ? 3 : GG_QUANT_BLOCKS_PER_CU);
-    a.chunks_per_block = rs.chunks_per_block;
+    // one run per block that can be resident at once (registers, and LDS when block-private histogram
+    // bins are in use), so the whole grid starts together and no block waits for a free slot
     const size_t lds = (size_t)a.lbins * sizeof(uint32_t);
+    const RunSplit rs = split_runs(g.n_chunks, resident_blocks(k_quant<T, MODE, RATE, PEN, EXTRA>, lds, GG_QUANT_BLOCKS_PER_CU));
+    a.chunks_per_block = rs.chunks_per_block;
     hipLaunchKernelGGL((k_quant<T, MODE, RATE, PEN, EXTRA>), dim3((unsigned)rs.blocks), dim3(kBlock), lds, st, g.sv,
                        static_cast<const T *>(x), a);
     return check_launch();
