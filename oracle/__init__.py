@@ -85,6 +85,8 @@ def lib():
         L.orc_eg_decode.argtypes = [vp, u64, C.c_int, vp, i64]
         L.orc_huffman_mean_bits.restype = f64
         L.orc_huffman_mean_bits.argtypes = [vp, i32]
+        L.orc_rate_grad.restype = None
+        L.orc_rate_grad.argtypes = [vp, C.c_int, i64, f32, C.c_int, i64, f32, vp, C.c_int]
         L.orc_compression_ratio.restype = f64
         L.orc_compression_ratio.argtypes = [f64, f64]
         _lib = L
@@ -254,3 +256,13 @@ def huffman_mean_bits(hist: np.ndarray) -> float:
 
 def compression_ratio(mean_bits: float, fl_bits: float) -> float:
     return lib().orc_compression_ratio(float(mean_bits), float(fl_bits))
+
+
+def rate_grad(x: np.ndarray, inv_delta: float, eg_k: int, n_rate: int, scale: float = 1.0,
+              grad: np.ndarray = None, accumulate: bool = False) -> np.ndarray:
+    x = _flat(x)
+    if grad is None:
+        grad = np.zeros(x.size, dtype=np.float32)
+    lib().orc_rate_grad(_ptr(x), _dtype_of(x), x.size, _f32(inv_delta), eg_k, int(n_rate), _f32(scale), _ptr(grad),
+                        int(bool(accumulate)))
+    return grad

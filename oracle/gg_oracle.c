@@ -428,6 +428,33 @@ void orc_gct_update(float *w, const float *g, float *g_hat_prev, int64_t n,
 }
 
 /* ------------------------------------------------------------------------- */
+/* Gradient of the rate R = (1/N) sum_i [2 log2(u_i + 2^k) - k + 1] through    */
+/* the straight-through quantiser (Sec. 4.2): d u/d x ~ 2 inv_delta sign(x),   */
+/* so dR/dx_i = 4 inv_delta / (N ln 2) * sign(x_i) / (u_i + 2^k)  -- the       */
+/* expression Sec. 4.3 prints as 2^(n+2)/(n ln 2) Sign(G)/Map(Quant(G)), with  */
+/* the 2^k of the code length kept so that u = 0 is finite.                    */
+/* ------------------------------------------------------------------------- */
+void orc_rate_grad(const void *x, int dtype, int64_t n, float inv_delta, int eg_k, int64_t n_rate,
+                   float scale, float *grad, int accumulate)
+{
+    const double ln2 = 0.69314718055994530942;
+    double coef = (double)scale * 4.0 * (double)inv_delta / ((double)n_rate * ln2);
+    for (int64_t i = 0; i < n; ++i) {
+        float v = load_elem(x, dtype, i);
+        uint32_t fl = 0;
+        uint32_t u = orc_map(orc_quantize_one(v, inv_delta, ORC_ROUND_FLOOR, &fl));
+        double s = v > 0.0f ? 1.0 : (v < 0.0f ? -1.0 : 0.0);
+        float d = (float)(coef * s / ((double)u + (double)((uint64_t)1 << eg_k)));
+        if (accumulate) {
+            volatile float sum = grad[i] + d;
+            grad[i] = sum;
+        } else {
+            grad[i] = d;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
 /* Exp-Golomb-k bit stream, MSB first: (L-1-k) zeros then the L bits of u+2^k */
 /* ------------------------------------------------------------------------- */
 uint64_t orc_eg_encode(const uint32_t *u, int64_t n, int eg_k, uint8_t *out, uint64_t out_bytes)

@@ -106,6 +106,11 @@ void orc_gct_update(float *w, const float *g, float *g_hat_prev, int64_t n,
                     float eta, float lambda, float eps, float inv_delta, int eg_k,
                     int64_t n_rate, int first_step);
 
+/* ---- gradient of the mean EG-k length w.r.t. the quantised tensor (ACT backward, Sec. 4.2/4.3) ----
+ * grad[i] (+)= scale * 4 inv_delta / (n_rate ln 2) * sign(x_i) / (u_i + 2^k) */
+void orc_rate_grad(const void *x, int dtype, int64_t n, float inv_delta, int eg_k, int64_t n_rate,
+                   float scale, float *grad, int accumulate);
+
 /* ---- Exp-Golomb bit stream (encoder / decoder) -------------------------- */
 /* returns number of bits written; out must hold (bits+7)/8 bytes, zero-initialised by callee */
 uint64_t orc_eg_encode(const uint32_t *u, int64_t n, int eg_k, uint8_t *out, uint64_t out_bytes);

@@ -113,3 +113,41 @@ def test_huffman_textbook_and_bounds():
         assert hm == pytest.approx(heap_huffman_mean(hist), rel=1e-12)
         assert r.entropy_bits <= hm < r.entropy_bits + 1          # Shannon bound for an optimal prefix code
         assert hm <= r.eg_bits / r.n + 1e-12                      # EG is one particular prefix code
+
+
+# ---- rate gradient (ACT backward) ---------------------------------------------------------------
+def test_rate_grad_is_slope_of_smoothed_mean_eg_length():
+    n_exp, k, N = 10, 0, 500
+    inv = 2.0 ** n_exp
+    x = np.array([0.37, -0.9, 0.051, -0.0042, 3.3], dtype=np.float32)
+    g = oracle.rate_grad(x, inv, k, N)
+    smooth = lambda v: 2.0 * math.log2(2.0 * abs(v) * inv + 2 ** k) / N     # u ~ 2|x| 2^n
+    for xi, gi in zip(x.astype(np.float64), g):
+        fd = (smooth(xi * 1.0001) - smooth(xi * 0.9999)) / (xi * 0.0002)
+        assert gi == pytest.approx(fd, rel=0.02 if abs(xi) * inv > 20 else 0.3)
+    # printed form of Sec. 4.3 at k = 0 for a positive symbol: 2^(n+2)/(N ln 2) / (u + 1)
+    q = math.floor(0.37 * inv)
+    assert g[0] == pytest.approx(2.0 ** (n_exp + 2) / (N * math.log(2)) / (2 * q - 1 + 1), rel=1e-6)
+
+
+def test_rate_grad_sign_zero_scale_accumulate_and_gct_consistency():
+    x = np.array([0.0, -0.0, 0.25, -0.25, 1e-9, -1e-9], dtype=np.float32)
+    g = oracle.rate_grad(x, 64.0, 1, 6)
+    assert g[0] == 0 and g[1] == 0 and g[2] > 0 and g[3] < 0
+    # floor puts -0.25*64 = -16 at u = 32 and +0.25*64 = 16 at u = 31: asymmetric by design
+    assert g[2] == pytest.approx(4 * 64 / (6 * math.log(2)) / (31 + 2), rel=1e-6)
+    assert g[3] == pytest.approx(-4 * 64 / (6 * math.log(2)) / (32 + 2), rel=1e-6)
+    assert g[4] == pytest.approx(4 * 64 / (6 * math.log(2)) / 2, rel=1e-6)        # u = 0
+    assert g[5] == pytest.approx(-4 * 64 / (6 * math.log(2)) / (2 + 2), rel=1e-6)  # q = -1 -> u = 2
+    g2 = oracle.rate_grad(x, 64.0, 1, 6, scale=0.5)
+    assert np.allclose(g2, 0.5 * g, rtol=1e-6)
+    base = np.ones(6, dtype=np.float32)
+    acc = oracle.rate_grad(x, 64.0, 1, 6, grad=base.copy(), accumulate=True)
+    assert np.array_equal(acc, (base + g).astype(np.float32))
+    # the GCT update uses the same rate gradient: with h = 1/(2 eta) (ghat_prev = 2g, eps = 0), ghat - g = lambda dR / (2 eta)
+    gvec = np.array([0.37, -0.2], dtype=np.float32)
+    w = np.zeros(2, dtype=np.float32)
+    gp = (2 * gvec).astype(np.float32)
+    oracle.gct_update(w, gvec, gp, eta=0.5, lam=1.0, eps=0.0, inv_delta=64.0, eg_k=1, n_rate=6, first_step=False)
+    dr = oracle.rate_grad(gvec, 64.0, 1, 6)
+    assert np.allclose(gp - gvec, dr, rtol=1e-5)
