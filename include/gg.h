@@ -177,6 +177,45 @@ int gg_fused_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols,
                   gg_fit_t *fit_dev, gg_fit_t *total_fit_dev, gg_rate_t *rate_dev,
                   void *ws_dev, size_t ws_bytes, void *stream);
 
+/* ---- companions of the pass inside the training algorithms ----------------------------------- */
+/* ACT backward (Sec. 4.2) / dR/dG of Sec. 4.3: gradient of the mean order-k Exp-Golomb length
+ * R = (1/n_rate) sum_i [2 log2(u_i + 2^k) - k + 1] through the straight-through quantiser,
+ *   grad[i] (=|+=) scale * 4 (1/delta) / (n_rate ln 2) * sign(x_i) / (u_i + 2^k),  u_i = Map(floor(x_i / delta)).
+ * For delta = 2^-n, k = 0 this is the paper's 2^(n+2)/(N ln 2) Sign/Map(Quant) with the 2^k of the code
+ * length kept (finite at u = 0).  n_rate is the N of the mean (normally n).  grad_dev fp32, 16-byte aligned. */
+int gg_rate_grad(const void *x_dev, int dtype, int64_t n, float delta, int eg_k, int64_t n_rate, float scale,
+                 float *grad_dev, int accumulate, void *stream);
+
+/* GCT element-wise update, Algorithm 2 (steps "approximate second-order derivatives", "equivalent
+ * gradient", "weight update"), fp32, in place on w_dev and ghat_prev_dev:
+ *   h = first_step ? 0 : (1/eta) (1 - g/(ghat_prev + eps));  ghat = g + lambda * dR/dg * h  (dR/dg as in
+ *   gg_rate_grad with scale 1);  ghat_prev <- ghat;  w <- w - eta * ghat.
+ * The per-epoch decay lambda <- alpha_decay * lambda is the caller's scalar.  eta > 0. */
+int gg_gct_update(float *w_dev, const float *g_dev, float *ghat_prev_dev, int64_t n, float eta, float lambda,
+                  float eps, float delta, int eg_k, int64_t n_rate, int first_step, void *stream);
+/* The same over a flat bucket with one step per unit (delta_dev[S], e.g. from gg_delta_from_fit) and
+ * n_rate = the unit's length.  A unit without a positive finite step gets no rate term (plain SGD). */
+int gg_gct_update_segmented(float *w_dev, const float *g_dev, float *ghat_prev_dev, const int64_t *offsets_host,
+                            int32_t S, const float *delta_dev, float eta, float lambda, float eps, int eg_k,
+                            int first_step, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Order-k Exp-Golomb bit stream of quantised symbols q (as written by the rate sweep): symbol i is
+ * (L-1-k) zero bits followed by the L bits of Map(q_i) + 2^k, most significant bit first, bytes filled from
+ * their most significant bit.  The stream's length in bits equals gg_rate_t.eg_bits of the same symbols.
+ * stream_dev: stream_bytes (a multiple of 4, 4-byte aligned) are cleared and filled; if the stream does not
+ * fit, blocks that would overflow are left out (compare *total_bits_dev with 8*stream_bytes).
+ * block_offsets_dev: gg_eg_workspace_bytes(n) bytes; on return entry b is the bit offset of symbol 2048*b
+ * (an index for parallel decoding), the last entry the total.  total_bits_dev may be NULL. */
+int gg_eg_workspace_bytes(int64_t n, size_t *bytes_out_host);
+int gg_eg_encode(const int32_t *symbols_dev, int64_t n, int eg_k, uint8_t *stream_dev, uint64_t stream_bytes,
+                 uint64_t *block_offsets_dev, uint64_t *total_bits_dev, void *stream);
+int gg_eg_decode(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, int64_t n, int eg_k,
+                 int32_t *symbols_dev, void *stream);
+
+/* Host helper: mean Huffman code length in bits/symbol of a histogram (the HM column of the paper's
+ * tables, Sec. 5.1); 0 for an empty histogram, 1 when a single symbol occurs. */
+int gg_huffman_mean_bits(const uint64_t *hist_host, int32_t nbins, double *mean_bits_out_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -69,6 +69,13 @@ def lib():
             "gg_compression_ratio": (f64, [f64, f64]),
             "gg_fused_segmented": (ci, [vp, ci, vp, i32, f32, vp, ci, ci, i32, vp, vp, f32, vp, ci, vp, vp, vp, sz, vp]),
             "gg_fused_rows": (ci, [vp, ci, i64, i64, f32, vp, ci, ci, vp, f32, vp, ci, vp, vp, vp, vp, sz, vp]),
+            "gg_rate_grad": (ci, [vp, ci, i64, f32, ci, i64, f32, vp, ci, vp]),
+            "gg_gct_update": (ci, [vp, vp, vp, i64, f32, f32, f32, f32, ci, i64, ci, vp]),
+            "gg_gct_update_segmented": (ci, [vp, vp, vp, vp, i32, vp, f32, f32, f32, ci, ci, vp, sz, vp]),
+            "gg_eg_workspace_bytes": (ci, [i64, C.POINTER(sz)]),
+            "gg_eg_encode": (ci, [vp, i64, ci, vp, u64, vp, vp, vp]),
+            "gg_eg_decode": (ci, [vp, vp, i64, ci, vp, vp]),
+            "gg_huffman_mean_bits": (ci, [vp, i32, C.POINTER(f64)]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -283,3 +290,65 @@ def gg_fused_rows(x: torch.Tensor, rows: int, cols: int, ws: Workspace, delta_di
                                _dev(sym), _f32(lam), _dev(grad), int(bool(accumulate)), _dev(fit), _dev(total),
                                _dev(rate), ws.ptr, ws.bytes, _stream()), "gg_fused_rows")
     return dict(fit=fit, total=total, rate=rate, symbols=sym, grad=grad)
+
+
+# ---- companions of the pass inside the training algorithms --------------------------------------
+def gg_rate_grad(x: torch.Tensor, delta: float, eg_k: int = 0, n_rate: Optional[int] = None, scale: float = 1.0,
+                 grad: Optional[torch.Tensor] = None, accumulate: bool = False) -> torch.Tensor:
+    if grad is None:
+        grad = torch.empty(x.numel(), dtype=torch.float32, device=x.device)
+    _check(lib().gg_rate_grad(_dev(x), _dtype_code(x), x.numel(), _f32(delta), eg_k,
+                              x.numel() if n_rate is None else int(n_rate), _f32(scale), _dev(grad),
+                              int(bool(accumulate)), _stream()), "gg_rate_grad")
+    return grad
+
+
+def gg_gct_update(w: torch.Tensor, g: torch.Tensor, ghat_prev: torch.Tensor, eta: float, lam: float, eps: float,
+                  delta: float, eg_k: int = 0, n_rate: Optional[int] = None, first_step: bool = False) -> None:
+    for t in (w, g, ghat_prev):
+        if t.dtype != torch.float32:
+            raise TypeError("gg_gct_update works on float32 tensors")
+    _check(lib().gg_gct_update(_dev(w), _dev(g), _dev(ghat_prev), w.numel(), _f32(eta), _f32(lam), _f32(eps),
+                               _f32(delta), eg_k, w.numel() if n_rate is None else int(n_rate), int(bool(first_step)),
+                               _stream()), "gg_gct_update")
+
+
+def gg_gct_update_segmented(w: torch.Tensor, g: torch.Tensor, ghat_prev: torch.Tensor, offsets, delta: torch.Tensor,
+                            eta: float, lam: float, eps: float, ws: Workspace, eg_k: int = 0,
+                            first_step: bool = False) -> None:
+    off = _offsets(offsets)
+    for t in (w, g, ghat_prev):
+        if t.dtype != torch.float32:
+            raise TypeError("gg_gct_update_segmented works on float32 tensors")
+    _check(lib().gg_gct_update_segmented(_dev(w), _dev(g), _dev(ghat_prev), off.ctypes.data, off.size - 1, _dev(delta),
+                                         _f32(eta), _f32(lam), _f32(eps), eg_k, int(bool(first_step)), ws.ptr, ws.bytes,
+                                         _stream()), "gg_gct_update_segmented")
+
+
+def gg_eg_encode(symbols: torch.Tensor, eg_k: int = 0, capacity_bytes: Optional[int] = None):
+    """Returns (stream uint8 tensor, block bit offsets int64 tensor, total_bits int).  Without a capacity the
+    stream is sized for the worst case of 8 bytes per symbol."""
+    n = symbols.numel()
+    out = C.c_size_t(0)
+    _check(lib().gg_eg_workspace_bytes(n, C.byref(out)), "gg_eg_workspace_bytes")
+    index = torch.empty(out.value // 8, dtype=torch.int64, device=symbols.device)
+    cap = (8 * n + 4) if capacity_bytes is None else int(capacity_bytes)
+    cap = (cap + 3) // 4 * 4
+    stream = torch.empty(cap, dtype=torch.uint8, device=symbols.device)
+    total = torch.zeros(1, dtype=torch.int64, device=symbols.device)
+    _check(lib().gg_eg_encode(_dev(symbols), n, eg_k, _dev(stream), cap, _dev(index), _dev(total), _stream()),
+           "gg_eg_encode")
+    return stream, index, int(total.item())
+
+
+def gg_eg_decode(stream: torch.Tensor, index: torch.Tensor, n: int, eg_k: int = 0) -> torch.Tensor:
+    out = torch.empty(n, dtype=torch.int32, device=stream.device)
+    _check(lib().gg_eg_decode(_dev(stream), _dev(index), n, eg_k, _dev(out), _stream()), "gg_eg_decode")
+    return out
+
+
+def gg_huffman_mean_bits(hist) -> float:
+    h = np.ascontiguousarray(np.asarray(hist.cpu() if isinstance(hist, torch.Tensor) else hist)).view(np.uint64)
+    out = C.c_double(0.0)
+    _check(lib().gg_huffman_mean_bits(h.ctypes.data, h.size, C.byref(out)), "gg_huffman_mean_bits")
+    return out.value

@@ -6,13 +6,13 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgg.so")
-SOURCES = ["gg_kernels.hip"]
+SOURCES = ["gg_kernels.hip", "gg_train.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                       # every fused multiply-add in the kernels is written explicitly
-    "-fno-fast-math", "-fgpu-flush-denormals-to-zero=0" if False else "-fno-gpu-flush-denormals-to-zero",
+    "-fno-fast-math", "-fno-gpu-flush-denormals-to-zero",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]

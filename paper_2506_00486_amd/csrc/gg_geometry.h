@@ -1,0 +1,269 @@
+// gg_geometry.h -- how a buffer is cut into units, chunks and runs, on the device (SegView,
+// locate, RunCursor) and on the host (argument validation, workspace layout, table upload,
+// occupancy-aware run split).  Shared by the translation units of libgg.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <type_traits>
+#include <vector>
+
+#include "../../include/gg.h"
+#include "gg_device.h"
+
+namespace gg {
+
+// ---------------------------------------------------------------------------------------------
+// unit geometry
+// ---------------------------------------------------------------------------------------------
+struct SegView {
+    const int64_t *off;    // device: S+1 element offsets, or nullptr for uniform rows
+    const int64_t *cpre;   // device: S+1 chunk prefix sums (with off)
+    int64_t cols;          // uniform: elements per row
+    int64_t cpr;           // uniform: chunks per row
+    int32_t S;
+};
+
+struct ChunkLoc {
+    int64_t start;   // first element
+    int64_t c;       // chunk index inside the unit
+    int32_t seg;
+    int32_t len;
+};
+
+__device__ __forceinline__ ChunkLoc locate(const SegView &sv, int64_t chunk) {
+    ChunkLoc L;
+    if (sv.off == nullptr) {
+        const int64_t seg = chunk / sv.cpr;
+        L.c = chunk - seg * sv.cpr;
+        L.seg = (int32_t)seg;
+        L.start = seg * sv.cols + L.c * kChunk;
+        const int64_t rest = sv.cols - L.c * kChunk;
+        L.len = (int32_t)(rest < kChunk ? rest : kChunk);
+    } else {
+        int lo = 0, hi = sv.S;  // largest s with cpre[s] <= chunk (skips empty units)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (sv.cpre[mid] <= chunk) lo = mid; else hi = mid;
+        }
+        L.seg = lo;
+        L.c = chunk - sv.cpre[lo];
+        L.start = sv.off[lo] + L.c * kChunk;
+        const int64_t rest = sv.off[lo + 1] - L.start;
+        L.len = (int32_t)(rest < kChunk ? rest : kChunk);
+    }
+    return L;
+}
+
+__device__ __forceinline__ int64_t unit_len(const SegView &sv, int seg) {
+    return sv.off ? sv.off[seg + 1] - sv.off[seg] : sv.cols;
+}
+__device__ __forceinline__ int64_t unit_chunk0(const SegView &sv, int seg) {
+    return sv.off ? sv.cpre[seg] : (int64_t)seg * sv.cpr;
+}
+__device__ __forceinline__ int64_t unit_chunk1(const SegView &sv, int seg) {
+    return sv.off ? sv.cpre[seg + 1] : (int64_t)(seg + 1) * sv.cpr;
+}
+
+__device__ __forceinline__ int64_t unit_end(const SegView &sv, int seg) {
+    return sv.off ? sv.off[seg + 1] : (int64_t)(seg + 1) * sv.cols;
+}
+
+// Walks the consecutive chunks [first, last) a block owns; the unit table is searched only when
+// the walk crosses into another unit.
+struct RunCursor {
+    ChunkLoc L;
+    int64_t chunk, last, seg_chunks;
+    __device__ __forceinline__ void init(const SegView &sv, int64_t first, int64_t last_) {
+        chunk = first; last = last_;
+        L = locate(sv, first);
+        seg_chunks = unit_chunk1(sv, L.seg) - unit_chunk0(sv, L.seg);
+    }
+    __device__ __forceinline__ bool valid() const { return chunk < last; }
+    __device__ __forceinline__ void next(const SegView &sv) {
+        if (++chunk >= last) return;
+        if (L.c + 1 < seg_chunks) {
+            L.c += 1;
+            L.start += kChunk;
+            const int64_t rest = unit_end(sv, L.seg) - L.start;
+            L.len = (int32_t)(rest < kChunk ? rest : kChunk);
+        } else {
+            L = locate(sv, chunk);
+            seg_chunks = unit_chunk1(sv, L.seg) - unit_chunk0(sv, L.seg);
+        }
+    }
+};
+
+// per-unit parameters of the second sweep
+constexpr uint32_t kSkipRate = 1u;   // no usable step: symbols 0, nothing accumulated
+constexpr uint32_t kPenZero = 2u;    // alpha == 0: penalty contributes 0
+struct SegParam {
+    float inv_delta;
+    float delta;
+    float pen_coef;    // lambda * beta / alpha
+    float inv_alpha;
+    float beta_m1;
+    uint32_t flags;
+    uint32_t _pad[2];
+};
+
+// ---------------------------------------------------------------------------------------------
+// small utility kernels
+// ---------------------------------------------------------------------------------------------
+constexpr int kPackI64 = 448;  // 3584 bytes of kernel arguments per launch
+struct PackI64 { int64_t v[kPackI64]; };
+
+static __global__ void k_upload_i64(PackI64 pack, int count, int64_t *dst) {
+    for (int i = threadIdx.x; i < count; i += blockDim.x) dst[i] = pack.v[i];
+}
+
+static __global__ void k_fill_u64(uint64_t *p, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = 0;
+}
+
+
+// =============================================================================================
+// host side
+// =============================================================================================
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct WsLayout {
+    size_t off_bytes, cpre_bytes, params_bytes, partials_bytes, total;
+    size_t off_at, cpre_at, params_at, partials_at;
+};
+
+static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
+    WsLayout w;
+    const size_t S = (size_t)n_units;
+    const size_t max_chunks = (size_t)(n_total / kChunk) + S + 1;
+    w.off_bytes = align_up((S + 1) * sizeof(int64_t), 256);
+    w.cpre_bytes = w.off_bytes;
+    w.params_bytes = align_up(S * sizeof(SegParam), 256);
+    w.partials_bytes = align_up(max_chunks * sizeof(double2), 256);
+    w.off_at = 256;
+    w.cpre_at = w.off_at + w.off_bytes;
+    w.params_at = w.cpre_at + w.cpre_bytes;
+    w.partials_at = w.params_at + w.params_bytes;
+    w.total = w.partials_at + w.partials_bytes;
+    return w;
+}
+
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline bool aligned8(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; }
+
+constexpr int64_t kMaxUnits = 1 << 24;
+constexpr int64_t kMaxChunks = 2147483647LL;
+
+// A validated description of how a buffer is cut into units, plus where its tables live.
+struct Geometry {
+    SegView sv{};
+    int64_t n_total = 0, n_chunks = 0;
+    int32_t S = 0;
+    WsLayout wl{};
+    char *ws = nullptr;
+    std::vector<int64_t> off, cpre;   // host copies (segmented only)
+    SegParam *params() const { return reinterpret_cast<SegParam *>(ws + wl.params_at); }
+    double2 *partials() const { return reinterpret_cast<double2 *>(ws + wl.partials_at); }
+};
+
+static int geometry_uniform(int64_t rows, int64_t cols, void *ws, size_t ws_bytes, bool need_ws, Geometry &g) {
+    if (rows < 0 || cols < 0 || rows > kMaxUnits) return GG_ERR_INVALID_ARG;
+    if (rows > 0 && cols > INT64_MAX / rows) return GG_ERR_INVALID_ARG;
+    g.S = (int32_t)rows;
+    g.n_total = rows * cols;
+    const int64_t cpr = (cols + kChunk - 1) / kChunk;
+    if (cpr > 0 && rows > kMaxChunks / cpr) return GG_ERR_INVALID_ARG;
+    g.n_chunks = rows * cpr;
+    g.sv.off = nullptr; g.sv.cpre = nullptr; g.sv.cols = cols; g.sv.cpr = cpr; g.sv.S = g.S;
+    g.wl = ws_layout(g.n_total, rows > 0 ? rows : 1);
+    if (need_ws) {
+        if (!ws || ws_bytes < g.wl.total || !aligned16(ws)) return GG_ERR_WORKSPACE;
+        g.ws = static_cast<char *>(ws);
+    }
+    return GG_OK;
+}
+
+static int geometry_segmented(const int64_t *offsets, int32_t S, void *ws, size_t ws_bytes, Geometry &g) {
+    if (!offsets || S < 0 || S > kMaxUnits) return S < 0 || !offsets ? GG_ERR_INVALID_ARG : GG_ERR_BAD_SEGMENTS;
+    if (offsets[0] < 0) return GG_ERR_BAD_SEGMENTS;
+    g.S = S;
+    g.off.assign(offsets, offsets + S + 1);
+    g.cpre.resize((size_t)S + 1);
+    int64_t chunks = 0;
+    for (int32_t s = 0; s < S; ++s) {
+        if (offsets[s + 1] < offsets[s]) return GG_ERR_BAD_SEGMENTS;
+        g.cpre[s] = chunks;
+        chunks += (offsets[s + 1] - offsets[s] + kChunk - 1) / kChunk;
+        if (chunks > kMaxChunks) return GG_ERR_BAD_SEGMENTS;
+    }
+    g.cpre[S] = chunks;
+    g.n_chunks = chunks;
+    g.n_total = offsets[S];   // elements of the buffer the units index into
+    g.wl = ws_layout(g.n_total, S > 0 ? S : 1);
+    if (!ws || ws_bytes < g.wl.total || !aligned16(ws)) return GG_ERR_WORKSPACE;
+    g.ws = static_cast<char *>(ws);
+    g.sv.off = reinterpret_cast<const int64_t *>(g.ws + g.wl.off_at);
+    g.sv.cpre = reinterpret_cast<const int64_t *>(g.ws + g.wl.cpre_at);
+    g.sv.cols = 0; g.sv.cpr = 1; g.sv.S = S;
+    return GG_OK;
+}
+
+static int check_launch() { return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP; }
+
+// tables travel as kernel arguments: asynchronous, no pinned staging, no allocation
+static int upload_i64(const std::vector<int64_t> &v, int64_t *dst, hipStream_t st) {
+    for (size_t base = 0; base < v.size(); base += kPackI64) {
+        PackI64 pack;
+        const int count = (int)((v.size() - base) < (size_t)kPackI64 ? v.size() - base : kPackI64);
+        memcpy(pack.v, v.data() + base, (size_t)count * sizeof(int64_t));
+        hipLaunchKernelGGL(k_upload_i64, dim3(1), dim3(256), 0, st, pack, count, dst + base);
+    }
+    return check_launch();
+}
+
+static int upload_geometry(const Geometry &g, hipStream_t st) {
+    if (g.sv.off == nullptr) return GG_OK;
+    int rc = upload_i64(g.off, const_cast<int64_t *>(g.sv.off), st);
+    if (rc != GG_OK) return rc;
+    return upload_i64(g.cpre, const_cast<int64_t *>(g.sv.cpre), st);
+}
+
+template <typename F>
+static int by_dtype(int dtype, F &&f) {
+    if (dtype == GG_F32) return f(static_cast<const float *>(nullptr));
+    if (dtype == GG_BF16) return f(static_cast<const bf16_t *>(nullptr));
+    return GG_ERR_BAD_DTYPE;
+}
+
+// Static split of the chunk list into one run per block: `blocks_per_cu` resident blocks on each
+// of the 256 compute units, every block a contiguous range of chunks.
+constexpr int kComputeUnits = 256;
+constexpr int kManyUnits = 2048;   // from here on the finalisation uses one lane per unit instead of one wave
+struct RunSplit { int64_t blocks; int32_t chunks_per_block; };
+static RunSplit split_runs(int64_t n_chunks, int blocks_per_cu) {
+    const int64_t target = (int64_t)kComputeUnits * blocks_per_cu;
+    int64_t cpb = (n_chunks + target - 1) / target;
+    if (cpb < 1) cpb = 1;
+    return RunSplit{(n_chunks + cpb - 1) / cpb, (int32_t)cpb};
+}
+
+// resident blocks of `kernel` per compute unit, capped at `cap` (a pure function of the code object)
+template <typename K>
+static int resident_blocks(K kernel, size_t dyn_lds, int cap) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, dyn_lds) != hipSuccess || n < 1) n = 1;
+    return n < cap ? n : cap;
+}
+
+static int launch_fill_u64(uint64_t *p, int64_t n, hipStream_t st) {
+    if (n <= 0) return GG_OK;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)blocks), dim3(256), 0, st, p, n);
+    return check_launch();
+}
+
+}  // namespace gg

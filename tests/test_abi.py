@@ -32,7 +32,7 @@ def test_header_symbols_are_exported():
         assert hasattr(gg.lib(), n), n
     # and the binding offers the same names
     for n in names:
-        if n in ("gg_strerror", "gg_workspace_bytes"):
+        if n in ("gg_strerror", "gg_workspace_bytes", "gg_eg_workspace_bytes"):
             continue
         assert hasattr(gg, n), n
 
@@ -105,6 +105,18 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.gg_fused_segmented(P, 0, ok_off.ctypes.data, 3, 16.0, None, 0, 0, 0, None, None, 0.0, None, 0, None, P, P,
                                 ws_bytes, None) == -1                                              # no fit output
     assert L.gg_delta_from_fit(P, 3, 0.0, P, None) == -1
+    # companions
+    assert L.gg_rate_grad(P, 0, 100, 0.0, 0, 100, 1.0, P, 0, None) == -1                           # step 0
+    assert L.gg_rate_grad(P, 0, 100, 0.1, 0, 0, 1.0, P, 0, None) == -1                             # n_rate 0
+    assert L.gg_rate_grad(P, 5, 100, 0.1, 0, 100, 1.0, P, 0, None) == -2
+    assert L.gg_gct_update(P, P, P, 100, 0.0, 1.0, 1e-8, 0.1, 0, 100, 0, None) == -1               # eta 0
+    assert L.gg_gct_update(P, None, P, 100, 0.1, 1.0, 1e-8, 0.1, 0, 100, 0, None) == -1
+    assert L.gg_gct_update_segmented(P, P, P, off.ctypes.data, 3, P, 0.1, 1.0, 1e-8, 0, 0, P, ws_bytes, None) == -3
+    assert L.gg_eg_encode(P, 100, 16, P, 1024, P, None, None) == -1                                # k > 15
+    assert L.gg_eg_encode(P, 100, 0, P, 1022, P, None, None) == -1                                 # size not a multiple of 4
+    assert L.gg_eg_encode(P, 100, 0, P, 1024, None, None, None) == -4                              # no index buffer
+    out = C.c_double(0)
+    assert L.gg_huffman_mean_bits(None, 4, C.byref(out)) == -1
 
 
 def test_host_helpers_match_paper_special_cases():
@@ -114,6 +126,20 @@ def test_host_helpers_match_paper_special_cases():
     assert np.isnan(gg.gg_init_alpha(0, 2.0, 1.0))
     # a row of the paper's result table: EG 1.59 bits at FL 12 -> 86.75 %
     assert 100 * gg.gg_compression_ratio(1.59, 12.0) == pytest.approx(86.75, abs=0.005)
+
+
+def test_huffman_mean_bits_host_helper():
+    gg = _lib()
+    assert gg.gg_huffman_mean_bits(np.array([1, 1, 2, 4], dtype=np.uint64)) == pytest.approx(14 / 8)   # lengths 3,3,2,1
+    assert gg.gg_huffman_mean_bits(np.array([5, 5, 5, 5], dtype=np.uint64)) == 2.0
+    assert gg.gg_huffman_mean_bits(np.array([0, 9, 0], dtype=np.uint64)) == 1.0
+    assert gg.gg_huffman_mean_bits(np.zeros(8, dtype=np.uint64)) == 0.0
+    import oracle
+    rng = np.random.default_rng(0)
+    h = rng.integers(0, 1000, size=5000).astype(np.uint64)
+    assert gg.gg_huffman_mean_bits(h) == pytest.approx(oracle.huffman_mean_bits(h), rel=1e-12)
+    out = C.c_size_t(0)
+    assert gg.lib().gg_eg_workspace_bytes(4097, C.byref(out)) == 0 and out.value == (3 + 1) * 8
 
 
 def test_empty_calls_are_ok_without_gpu_work():

@@ -1,0 +1,176 @@
+"""GPU parity of the pass's companions in the training algorithms (rate gradient, GCT update,
+Exp-Golomb bit stream) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import gg_inputs
+import oracle
+from parity import host_bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+@pytest.fixture(scope="module")
+def gg():
+    import paper_2506_00486_amd as m
+    m.lib()
+    return m
+
+
+def make(n, alpha, beta, seed, dtype=torch.float32):
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    return gg_inputs.gg_torch(n, alpha, beta, gen, DEV, dtype)
+
+
+def inv32(delta):
+    return float(np.float32(1.0) / np.float32(delta))
+
+
+# ---- rate gradient ------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,k", [(1, 0), (4099, 0), (100_003, 2), (16384 * 3 + 5, 1)])
+def test_rate_grad(gg, n, k, dtype):
+    x = make(n, 0.5, 0.8, seed=n, dtype=dtype)
+    x[::97] = 0.0
+    delta = 2.0 ** -6
+    g = gg.gg_rate_grad(x, delta, eg_k=k, scale=0.37).cpu().numpy()
+    o = oracle.rate_grad(host_bits(x), inv32(delta), k, n, scale=0.37)
+    # fp32 coefficient and one fp32 division against the oracle's fp64: a few 1e-7 relative
+    assert np.allclose(g, o, rtol=1e-5, atol=1e-30)
+    assert not g[::97].any()
+    base = torch.randn(n, device=DEV)
+    acc = gg.gg_rate_grad(x, delta, eg_k=k, scale=0.37, grad=base.clone(), accumulate=True).cpu().numpy()
+    assert np.allclose(acc, base.cpu().numpy() + o, rtol=1e-6, atol=1e-5 * np.abs(o).max())
+
+
+def test_rate_grad_matches_gct_rate_term(gg):
+    # with ghat_prev = 2g and eps = 0, h = 1/(2 eta): ghat - g = lambda * dR/dg / (2 eta)
+    n = 50_000
+    g = make(n, 1e-3, 1.0, seed=3)
+    g[g == 0] = 1e-3
+    w = torch.zeros(n, device=DEV)
+    gp = (2 * g).clone()
+    delta = 2.0 ** -14
+    gg.gg_gct_update(w, g, gp, eta=0.5, lam=1.0, eps=0.0, delta=delta, eg_k=0)
+    dr = gg.gg_rate_grad(g, delta, eg_k=0)
+    assert torch.allclose(gp - g, dr, rtol=1e-4, atol=1e-7 * float(dr.abs().max()))
+
+
+# ---- GCT update ---------------------------------------------------------------------------------
+def gct_case(n, seed):
+    g = make(n, 1e-3, 0.9, seed=seed)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed + 100)
+    gp = g * (1.0 + 0.5 * torch.randn(n, device=DEV, generator=gen))   # previous equivalent gradient near g
+    w = torch.randn(n, device=DEV, generator=gen)
+    return w, g, gp
+
+
+def check_gct(w_gpu, gp_gpu, w0, g, gp0, eta, lam, eps, delta, k, n_rate, first):
+    wo, go, gpo = w0.copy(), g.copy(), gp0.copy()
+    oracle.gct_update(wo, go, gpo, eta, lam, eps, inv32(delta), k, n_rate, first)
+    # conditioning: the secant term (1 - g/(ghat_prev+eps))/eta carries an absolute fp32 error of
+    # ~2^-23 max(1, |g/(ghat_prev+eps)|)/eta, multiplied by lambda*|dR/dg| in the equivalent gradient
+    dr = np.abs(oracle.rate_grad(g, inv32(delta), k, n_rate).astype(np.float64))
+    ratio = np.abs(g.astype(np.float64) / (gp0.astype(np.float64) + eps))
+    tol_g = 1e-6 * np.abs(gpo) + (0 if first else 4e-7 * abs(lam) * dr / eta * np.maximum(1.0, ratio)) + 1e-30
+    assert np.all(np.abs(gp_gpu.astype(np.float64) - gpo) <= tol_g), float(np.max(np.abs(gp_gpu - gpo) / tol_g))
+    tol_w = 2.0 ** -23 * np.abs(wo) + eta * tol_g
+    assert np.all(np.abs(w_gpu.astype(np.float64) - wo) <= tol_w)
+
+
+@pytest.mark.parametrize("n", [1, 5, 4099, 16384 * 2 + 3, 300_001])
+@pytest.mark.parametrize("first", [True, False])
+def test_gct_update_single(gg, n, first):
+    w, g, gp = gct_case(n, seed=n)
+    w0, g0, gp0 = w.cpu().numpy(), g.cpu().numpy(), gp.cpu().numpy()
+    eta, lam, eps, delta, k = 1e-2, 0.3, 1e-8, 2.0 ** -16, 0
+    gg.gg_gct_update(w, g, gp, eta, lam, eps, delta, eg_k=k, first_step=first)
+    check_gct(w.cpu().numpy(), gp.cpu().numpy(), w0, g0, gp0, eta, lam, eps, delta, k, n, first)
+    if first:   # t = 1: plain SGD, the equivalent gradient is the gradient itself
+        assert np.array_equal(gp.cpu().numpy(), g0)
+
+
+def test_gct_zero_lambda_is_sgd(gg):
+    w, g, gp = gct_case(100_000, seed=9)
+    w0, g0 = w.cpu().numpy(), g.cpu().numpy()
+    gg.gg_gct_update(w, g, gp, 1e-2, 0.0, 1e-8, 2.0 ** -16)
+    assert np.array_equal(gp.cpu().numpy(), g0)
+    expect = (w0.astype(np.float64) - float(np.float32(1e-2)) * g0.astype(np.float64))
+    assert np.all(np.abs(w.cpu().numpy() - expect) <= 2.0 ** -23 * np.abs(expect))
+
+
+def test_gct_update_segmented_with_fitted_steps(gg):
+    layout = gg_inputs.gradient_bucket_1p5b()
+    segs = gg_inputs.scaled_layout(layout[:18], 499)
+    segs.insert(4, gg_inputs.Segment("empty", 0))
+    segs.insert(9, gg_inputs.Segment("zeros", 40))
+    g, off, _, _ = gg_inputs.make_bucket(segs, seed=3, device=DEV)
+    g[int(off[9]):int(off[10])] = 0
+    n, S = g.numel(), len(segs)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(1)
+    gp = g * (1.0 + 0.5 * torch.randn(n, device=DEV, generator=gen))
+    gp[int(off[9]):int(off[10])] = 1e-3
+    w = torch.randn(n, device=DEV, generator=gen)
+    ws = gg.Workspace(n, S)
+    res = gg.gg_fused_segmented(g, off, ws, delta_div=16.0)           # the pass gives each tensor's step
+    rrec = gg.rate_records(res["rate"])
+    delta = torch.tensor(rrec["delta"].copy(), device=DEV)
+    w0, g0, gp0 = w.cpu().numpy(), g.cpu().numpy(), gp.cpu().numpy()
+    eta, lam, eps = 1e-2, 0.2, 1e-8
+    gg.gg_gct_update_segmented(w, g, gp, off, delta, eta, lam, eps, ws)
+    wg, gpg = w.cpu().numpy(), gp.cpu().numpy()
+    for s in range(S):
+        lo, hi = int(off[s]), int(off[s + 1])
+        if hi == lo:
+            continue
+        d = float(rrec["delta"][s])
+        if not d > 0:     # no usable step: plain SGD
+            assert np.array_equal(gpg[lo:hi], g0[lo:hi])
+            continue
+        check_gct(wg[lo:hi], gpg[lo:hi], w0[lo:hi], g0[lo:hi], gp0[lo:hi], eta, lam, eps, d, 0, hi - lo, False)
+
+
+# ---- Exp-Golomb bit stream ----------------------------------------------------------------------
+@pytest.mark.parametrize("n", [0, 1, 7, 2047, 2048, 2049, 100_003])
+@pytest.mark.parametrize("k", [0, 3])
+def test_eg_stream_equals_oracle_stream(gg, n, k):
+    x = make(max(n, 1), 0.02, 0.7, seed=n + k)[:n].contiguous()
+    ws = gg.Workspace(max(n, 1), 1)
+    delta = float(np.float32(0.02) / np.float32(16))
+    out, _, sym = gg.gg_quantize_rate(x, delta, ws, eg_k=k, want_symbols=True) if n else (None, None,
+                                                                                         torch.empty(0, dtype=torch.int32, device=DEV))
+    stream, index, total = gg.gg_eg_encode(sym, eg_k=k)
+    q = sym.cpu().numpy()
+    u = np.where(q > 0, 2 * q.astype(np.int64) - 1, -2 * q.astype(np.int64)).astype(np.uint32)
+    obuf, obits = oracle.eg_encode(u, k)
+    assert total == obits
+    if n:
+        assert total == int(gg.rate_records(out)[0]["eg_bits"])       # the rate estimate is the stream size
+    sb = stream.cpu().numpy()
+    assert np.array_equal(sb[: obuf.size], obuf) and not sb[obuf.size:].any()
+    idx = index.cpu().numpy()
+    assert idx[0] == 0 and idx[-1] == total and np.all(np.diff(idx) >= 0)
+    back = gg.gg_eg_decode(stream, index, n, eg_k=k)
+    assert np.array_equal(back.cpu().numpy(), q)
+    # the oracle decodes the GPU stream too
+    assert np.array_equal(oracle.eg_decode(sb, total, k, n), u)
+
+
+def test_eg_stream_extreme_symbols_and_tight_capacity(gg):
+    q = torch.tensor([0, 1, -1, 2 ** 30, -(2 ** 30), 5, -7, 0, 0, 123456, -654321] * 400, dtype=torch.int32, device=DEV)
+    for k in (0, 15):
+        u = np.array([oracle.map_symbol(int(v)) for v in q.cpu().numpy()], dtype=np.uint32)
+        obuf, obits = oracle.eg_encode(u, k)
+        stream, index, total = gg.gg_eg_encode(q, eg_k=k, capacity_bytes=(obits + 7) // 8)
+        assert total == obits
+        assert np.array_equal(stream.cpu().numpy()[: obuf.size], obuf)
+        assert np.array_equal(gg.gg_eg_decode(stream, index, q.numel(), eg_k=k).cpu().numpy(), q.cpu().numpy())
+    # a stream that is too small: the total still reports the need, nothing is written past the end
+    stream, index, total = gg.gg_eg_encode(q, eg_k=0, capacity_bytes=64)
+    assert total == oracle.eg_encode(np.array([oracle.map_symbol(int(v)) for v in q.cpu().numpy()], dtype=np.uint32), 0)[1]
+    assert total > 64 * 8 and stream.numel() == 64
