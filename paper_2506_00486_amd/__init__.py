@@ -13,3 +13,4 @@ from .binding import (  # noqa: F401
     gg_compression_ratio, gg_fused_segmented, gg_fused_rows, fit_records, rate_records,
     gg_rate_grad, gg_gct_update, gg_gct_update_segmented, gg_eg_encode, gg_eg_decode, gg_huffman_mean_bits,
 )
+from .train import gg_init_, eg_rate, EGRate, GCTState  # noqa: F401,E402

@@ -174,3 +174,53 @@ def test_eg_stream_extreme_symbols_and_tight_capacity(gg):
     stream, index, total = gg.gg_eg_encode(q, eg_k=0, capacity_bytes=64)
     assert total == oracle.eg_encode(np.array([oracle.map_symbol(int(v)) for v in q.cpu().numpy()], dtype=np.uint32), 0)[1]
     assert total > 64 * 8 and stream.numel() == 64
+
+
+# ---- torch glue: GG init driver, differentiable rate, GCT state ---------------------------------
+def test_gg_init_driver(gg):
+    w1 = torch.empty(512, 1024, device=DEV)                       # fan-in 1024
+    w2 = torch.empty(2048, 256, device=DEV, dtype=torch.bfloat16)  # fan-in 256
+    gg.gg_init_([(w1, 1024), (w2, 256)], shape=0.5, xi=2.0, seed=7)
+    assert float(w1.double().var()) == pytest.approx(2.0 / 1024, rel=0.05)   # Eq. 5: variance xi / fan_in
+    assert float(w2.double().var()) == pytest.approx(2.0 / 256, rel=0.05)
+    rec = gg.fit_records(gg.gg_fit(w1.view(-1), gg.Workspace(w1.numel(), 1)))[0]
+    assert abs(float(rec["beta"]) - 0.5) < 0.02
+    a1 = gg.gg_init_alpha(1024, 0.5, 2.0)
+    ref = gg.gg_sample(w1.numel(), a1, 0.5, 7, stream_id=0)
+    assert torch.equal(ref, w1.view(-1))                           # tensor i = generator stream i
+
+
+def test_differentiable_eg_rate(gg):
+    a = make(40_000, 0.5, 0.8, seed=1).reshape(100, 400).requires_grad_(True)
+    delta = 2.0 ** -5
+    r = gg.eg_rate(a, delta, 0)
+    ws = gg.Workspace(a.numel(), 1)
+    rec = gg.rate_records(gg.gg_quantize_rate(a.detach().view(-1), delta, ws)[0])[0]
+    assert float(r) == pytest.approx(float(rec["eg_bits"]) / a.numel(), rel=1e-6)
+    (3.0 * r).backward()
+    o = oracle.rate_grad(host_bits(a.detach().view(-1)), inv32(delta), 0, a.numel(), scale=3.0)
+    assert np.allclose(a.grad.view(-1).cpu().numpy(), o, rtol=1e-5, atol=1e-30)
+
+
+def test_gct_state_runs_algorithm_2_steps(gg):
+    segs = gg_inputs.scaled_layout(gg_inputs.gradient_bucket_1p5b()[:9], 997)
+    off = gg_inputs.offsets_of(segs)
+    n = int(off[-1])
+    st = gg.GCTState(n, off, eta=1e-2, lam=0.1, decay=0.8)
+    w = torch.randn(n, device=DEV)
+    w_ref = w.cpu().numpy().copy()
+    ghat = np.zeros(n, dtype=np.float32)
+    for t in range(3):
+        g, _, _, _ = gg_inputs.make_bucket(segs, seed=50 + t, device=DEV)
+        res = st.step(w, g)
+        rrec = gg.rate_records(res["rate"])
+        g_h = g.cpu().numpy()
+        for s in range(len(segs)):            # oracle: the same update per tensor with the GPU's step
+            lo, hi = int(off[s]), int(off[s + 1])
+            ws_, gs_, gp_ = w_ref[lo:hi].copy(), g_h[lo:hi].copy(), ghat[lo:hi].copy()
+            oracle.gct_update(ws_, gs_, gp_, 1e-2, st.lam, 1e-8, inv32(rrec["delta"][s]), 0, hi - lo, t == 0)
+            w_ref[lo:hi], ghat[lo:hi] = ws_, gp_
+        # loose, drift-tolerant comparison over three chained steps
+        assert np.allclose(w.cpu().numpy(), w_ref, rtol=1e-4, atol=1e-5)
+    st.end_epoch()
+    assert st.lam == pytest.approx(0.08) and st.t == 4
