@@ -225,8 +225,43 @@ def main():
         step_sample()
         _, ms_s = time_steps(step_sample, 5, torch)
         extra["gg_sample_bf16"] = {"elements": ns, "ms": round(ms_s, 4), "Gsamples/s": round(ns / ms_s / 1e6, 2)}
+        del xs
+        # companions: GCT update over the same bucket (reads g, ghat_prev, w; writes ghat, w = 20 B/elem),
+        # rate gradient (4 B read + 4 B written), Exp-Golomb bit-stream encoder on a 64M-symbol slice
+        delta = gg.gg_delta_from_fit(fit, S, 16.0)
+        wbuf = torch.zeros(n, dtype=torch.float32, device=dev)
+        gprev = flat.clone()
+
+        def step_gct():
+            gg.gg_gct_update_segmented(wbuf, flat, gprev, off, delta, 1e-3, 0.1, 1e-8, ws)
+
+        step_gct()
+        _, ms_g = time_steps(step_gct, 5, torch)
+        extra["gct_update_segmented"] = {"ms": round(ms_g, 4), "Gelem/s": round(n / ms_g / 1e6, 2),
+                                         "algorithmic_GB/s": round(20.0 * n / ms_g / 1e6, 1)}
+        del gprev
+
+        def step_rg():
+            gg.gg_rate_grad(flat, 2.0 ** -16, grad=wbuf)
+
+        step_rg()
+        _, ms_r = time_steps(step_rg, 5, torch)
+        extra["rate_grad"] = {"ms": round(ms_r, 4), "Gelem/s": round(n / ms_r / 1e6, 2),
+                              "algorithmic_GB/s": round(8.0 * n / ms_r / 1e6, 1)}
+        del wbuf
+        m = min(n, 1 << 26)
+        wsq = gg.Workspace(m, 1, device=dev)
+        rec, _, sym = gg.gg_quantize_rate(flat[:m], float(frec["alpha"][0]) / 16.0, wsq, want_symbols=True)
+        bits = int(gg.rate_records(rec)[0]["eg_bits"])
+
+        def step_enc():
+            gg.gg_eg_encode(sym, 0, capacity_bytes=(bits + 7) // 8)
+
+        step_enc()
+        _, ms_e = time_steps(step_enc, 5, torch)
+        extra["eg_encode"] = {"symbols": m, "stream_bits": bits, "ms": round(ms_e, 4), "Gsymbols/s": round(m / ms_e / 1e6, 2)}
+        del sym
         if args.all:
-            del xs
             extra.update(other_configs(gg, gg_inputs, torch, dev, args))
         out["extra"] = extra
 
