@@ -91,18 +91,24 @@ typedef int gg_i4 __attribute__((ext_vector_type(4)));
 
 typedef unsigned int gg_u2 __attribute__((ext_vector_type(2)));
 
-template <typename T> struct Elem;
+// NT = true: streaming load (data read once per sweep); NT = false: ordinary cached load (data that
+// the same compute unit re-reads shortly, as in the wave-per-row kernels).
+template <typename V, bool NT>
+__device__ __forceinline__ V load_vec(const V *p) {
+#if GG_STREAM_LOADS
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+#endif
+    return *p;
+}
 
-template <> struct Elem<float> {
+template <typename T, bool NT = true> struct Elem;
+
+template <bool NT> struct Elem<float, NT> {
     static constexpr int W = 4;
     using type = float;
     using raw = gg_f4;
     static __device__ __forceinline__ raw loadv(const float *p) {
-#if GG_STREAM_LOADS
-        return __builtin_nontemporal_load(reinterpret_cast<const gg_f4 *>(p));
-#else
-        return *reinterpret_cast<const gg_f4 *>(p);
-#endif
+        return load_vec<gg_f4, NT>(reinterpret_cast<const gg_f4 *>(p));
     }
     static __device__ __forceinline__ void unpack(const raw &r, float (&v)[W]) {
         v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
@@ -110,16 +116,12 @@ template <> struct Elem<float> {
     static __device__ __forceinline__ float load1(const float *p) { return *p; }
 };
 
-template <> struct Elem<bf16_t> {
+template <bool NT> struct Elem<bf16_t, NT> {
     static constexpr int W = 8;
     using type = bf16_t;
     using raw = gg_u4;
     static __device__ __forceinline__ raw loadv(const bf16_t *p) {
-#if GG_STREAM_LOADS
-        return __builtin_nontemporal_load(reinterpret_cast<const gg_u4 *>(p));
-#else
-        return *reinterpret_cast<const gg_u4 *>(p);
-#endif
+        return load_vec<gg_u4, NT>(reinterpret_cast<const gg_u4 *>(p));
     }
     static __device__ __forceinline__ void unpack(const raw &r, float (&v)[W]) {
         // bf16 is the high half of an fp32: widening is a shift (even element) or a mask (odd)
@@ -135,16 +137,12 @@ template <> struct Elem<bf16_t> {
 
 // bf16 with four elements (8 bytes) per lane: used where every element produces a 4-byte output,
 // so that a lane's outputs are one 16-byte store and a wave's store instruction covers whole lines.
-struct ElemBf16x4 {
+template <bool NT = true> struct ElemBf16x4T {
     static constexpr int W = 4;
     using type = bf16_t;
     using raw = gg_u2;
     static __device__ __forceinline__ raw loadv(const bf16_t *p) {
-#if GG_STREAM_LOADS
-        return __builtin_nontemporal_load(reinterpret_cast<const gg_u2 *>(p));
-#else
-        return *reinterpret_cast<const gg_u2 *>(p);
-#endif
+        return load_vec<gg_u2, NT>(reinterpret_cast<const gg_u2 *>(p));
     }
     static __device__ __forceinline__ void unpack(const raw &r, float (&v)[W]) {
         v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
@@ -154,6 +152,8 @@ struct ElemBf16x4 {
         return __uint_as_float((uint32_t)p->bits << 16);
     }
 };
+
+using ElemBf16x4 = ElemBf16x4T<true>;
 
 // fp32 -> bf16, round to nearest even, NaN kept quiet
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
@@ -171,12 +171,13 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 // element index idx (a multiple of W); body.one(v, idx) gets one.  E is the element policy
 // (Elem<float>, Elem<bf16_t>, ElemBf16x4).
 // ---------------------------------------------------------------------------------------------
-template <typename E, int U, typename Body>
+// GROUP threads cooperate (the whole block, or one wave with GROUP = 64).
+template <typename E, int U, typename Body, int GROUP = kBlock>
 __device__ __forceinline__ void process_chunk(const typename E::type *__restrict__ x, int64_t start, int len,
                                               Body &body) {
     using T = typename E::type;
     constexpr int W = E::W;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & (GROUP - 1);
     int head = (int)((W - (int)(start % W)) % W);
     if (head > len) head = len;
     if (tid < head) body.one(E::load1(x + start + tid), start + tid);
@@ -185,18 +186,18 @@ __device__ __forceinline__ void process_chunk(const typename E::type *__restrict
     const int nvec = (len - head) / W;
     const T *__restrict__ p = x + vstart;
     int i = tid;
-    for (; i + (U - 1) * kBlock < nvec; i += U * kBlock) {
+    for (; i + (U - 1) * GROUP < nvec; i += U * GROUP) {
         typename E::raw r[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) r[u] = E::loadv(p + (int64_t)(i + u * kBlock) * W);
+        for (int u = 0; u < U; ++u) r[u] = E::loadv(p + (int64_t)(i + u * GROUP) * W);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float v[W];
             E::unpack(r[u], v);
-            body.vec(v, vstart + (int64_t)(i + u * kBlock) * W);
+            body.vec(v, vstart + (int64_t)(i + u * GROUP) * W);
         }
     }
-    for (; i < nvec; i += kBlock) {
+    for (; i < nvec; i += GROUP) {
         typename E::raw r = E::loadv(p + (int64_t)i * W);
         float v[W];
         E::unpack(r, v);
@@ -214,8 +215,10 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
                                               uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        // one 32x32->64 multiply per product (v_mad_u64_u32) instead of separate high and low halves
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
         c0 = hi1 ^ c1 ^ k0;
         c1 = lo1;
         c2 = hi0 ^ c3 ^ k1;

@@ -115,6 +115,7 @@ struct SolveConst { double lrho_min, lrho_max; };
 
 // Wave-cooperative fit from the moments.  The root of log_rho(b) = log(rho_hat) is bracketed by
 // evaluating 64 log-spaced shapes at once (one per lane); each round shrinks the bracket 65-fold.
+// Must be called by all 64 lanes of a wave with identical arguments.
 __device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, const SolveConst &sc, gg_fit_t &f) {
     const int lane = threadIdx.x & 63;
     f.sum_abs = s1; f.sum_sq = s2; f.n = n; f.beta = 0.f; f.alpha = 0.f; f.flags = 0; f._pad = 0;
@@ -129,18 +130,22 @@ __device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, cons
     } else if (!(target < sc.lrho_max)) {
         b = GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI;
     } else {
+        // Three rounds of 64 log-spaced candidates shrink the bracket in ln b to ln(400)/65^3 = 2e-5;
+        // the residuals at its two ends are known from the last round, and one secant step between
+        // them lands within 1e-10 (relative) of the root.
         double llo = log(GG_BETA_MIN), lhi = log(GG_BETA_MAX);
-        // five rounds: ln(400) / 65^5 = 5e-9 relative width, below fp32 resolution of the result
-        for (int round = 0; round < 5; ++round) {
+        double flo = sc.lrho_min - target, fhi = sc.lrho_max - target;
+        for (int round = 0; round < 3; ++round) {
             const double step = (lhi - llo) * (1.0 / 65.0);
-            const double cand = exp(llo + step * (double)(lane + 1));
-            const bool below = log_rho(cand) < target;   // rho increases with b
-            const int cnt = __popcll(__ballot(below));
-            const double nlo = llo + step * (double)cnt;
-            lhi = cnt == 64 ? lhi : llo + step * (double)(cnt + 1);
-            llo = nlo;
+            const double cand = llo + step * (double)(lane + 1);
+            const double fv = log_rho(exp(cand)) - target;     // rho increases with b
+            const int cnt = __popcll(__ballot(fv < 0.0));      // candidates below the root: lanes 0..cnt-1
+            const double c_lo = __shfl(cand, cnt > 0 ? cnt - 1 : 0, 64), f_lo = __shfl(fv, cnt > 0 ? cnt - 1 : 0, 64);
+            const double c_hi = __shfl(cand, cnt < 64 ? cnt : 63, 64), f_hi = __shfl(fv, cnt < 64 ? cnt : 63, 64);
+            if (cnt > 0) { llo = c_lo; flo = f_lo; }
+            if (cnt < 64) { lhi = c_hi; fhi = f_hi; }
         }
-        b = exp(0.5 * (llo + lhi));
+        b = exp(fhi > flo ? llo - flo * (lhi - llo) / (fhi - flo) : 0.5 * (llo + lhi));
     }
     const double r = 1.0 / b;
     f.beta = (float)b;
@@ -269,19 +274,29 @@ __global__ __launch_bounds__(64) void k_fit_finalize_lanes(SegView sv, const dou
     if (do_prep) prepare_unit(prep, seg, n, f.alpha, f.beta);
 }
 
-// fit of the whole matrix from the per-row sums (one wave, fixed order)
-__global__ __launch_bounds__(64) void k_fit_total(const gg_fit_t *__restrict__ rows, int64_t n_rows,
-                                                  gg_fit_t *__restrict__ out, SolveConst sc) {
-    const int lane = threadIdx.x;
+// fit of the whole matrix from the per-row sums: thread-strided ascending sums, fixed tree across the
+// block, solve by the first wave
+constexpr int kTotalThreads = 1024;
+__global__ __launch_bounds__(kTotalThreads) void k_fit_total(const gg_fit_t *__restrict__ rows, int64_t n_rows,
+                                                             gg_fit_t *__restrict__ out, SolveConst sc) {
+    __shared__ double red1[kTotalThreads / 64], red2[kTotalThreads / 64];
+    __shared__ uint64_t redn[kTotalThreads / 64];
+    const int tid = threadIdx.x;
     double s1 = 0.0, s2 = 0.0;
     uint64_t n = 0;
-    for (int64_t r = lane; r < n_rows; r += 64) { s1 += rows[r].sum_abs; s2 += rows[r].sum_sq; n += rows[r].n; }
+    for (int64_t r = tid; r < n_rows; r += kTotalThreads) { s1 += rows[r].sum_abs; s2 += rows[r].sum_sq; n += rows[r].n; }
     s1 = wave_reduce(s1, OpAdd());
     s2 = wave_reduce(s2, OpAdd());
     n = wave_reduce(n, OpAdd());
-    gg_fit_t f;
-    solve_fit(s1, s2, n, sc, f);
-    if (lane == 0) out[0] = f;
+    if ((tid & 63) == 0) { red1[tid >> 6] = s1; red2[tid >> 6] = s2; redn[tid >> 6] = n; }
+    __syncthreads();
+    if (tid < 64) {
+        s1 = 0.0; s2 = 0.0; n = 0;
+        for (int w = 0; w < kTotalThreads / 64; ++w) { s1 += red1[w]; s2 += red2[w]; n += redn[w]; }
+        gg_fit_t f;
+        solve_fit(s1, s2, n, sc, f);
+        if (tid == 0) out[0] = f;
+    }
 }
 
 // parameters for calls that do not fit first (one thread per unit)
@@ -524,6 +539,86 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
     flush();
 }
 
+// ---------------------------------------------------------------------------------------------
+// wave-per-row pass.  For matrices whose rows fit a few cache lines per lane (activations: one row
+// per token) a wave owns a row outright: it sums the moments, solves the fit with its 64 lanes,
+// derives the row's step and immediately quantises the row again while it is still in cache.  No
+// workspace, no atomics, no second kernel; HBM sees each element once.
+// ---------------------------------------------------------------------------------------------
+constexpr int64_t kRowWaveMax = 16384;   // elements per row this path takes
+
+struct RowsArgs {
+    int64_t rows, cols;
+    gg_fit_t *fit;            // per-row fits (written when do_fit)
+    gg_rate_t *rate;          // per-row rate records (RATE)
+    const float *delta_dev;   // per-row steps when delta_div <= 0
+    float delta_div, lambda;
+    uint32_t eg_add, eg_const;
+    int32_t *symbols; float *grad; int accumulate;
+    int do_fit;
+    SolveConst sc;
+};
+
+template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
+__global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t n_waves = (int64_t)gridDim.x * kWaves;
+    const int len = (int)a.cols;
+    for (int64_t row = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6); row < a.rows; row += n_waves) {
+        const int64_t start = row * a.cols;
+        float alpha = 0.f, beta = 0.f;
+        if (a.do_fit) {
+            FitBody fb;
+            // cached loads: the row is read again a few microseconds later by this same wave
+            process_chunk<Elem<T, !(RATE || PEN)>, 4, FitBody, 64>(x, start, len, fb);
+            double s1 = ((double)fb.s1[0] + (double)fb.s1[1]) + ((double)fb.s1[2] + (double)fb.s1[3]);
+            double s2 = ((double)fb.s2[0] + (double)fb.s2[1]) + ((double)fb.s2[2] + (double)fb.s2[3]);
+            s1 = wave_reduce(s1, OpAdd());
+            s2 = wave_reduce(s2, OpAdd());
+            gg_fit_t f;
+            solve_fit(s1, s2, (uint64_t)len, a.sc, f);
+            if (lane == 0) a.fit[row] = f;
+            alpha = f.alpha; beta = f.beta;
+        }
+        if constexpr (RATE || PEN) {
+            float delta = 0.f;
+            if constexpr (RATE) delta = a.delta_div > 0.f ? (float)((double)alpha / (double)a.delta_div) : a.delta_dev[row];
+            const bool ok = delta > 0.f && isfinite(delta);
+            QuantBody<MODE, RATE, PEN, EXTRA> body;
+            body.eg_add = a.eg_add;
+            body.symbols = a.symbols; body.grad = a.grad; body.accumulate = a.accumulate;
+            body.lds_hist = nullptr; body.ghist = nullptr; body.last_bin = 0; body.lbins = 0; body.hist_live = false;
+            body.inv_delta = ok ? (float)(1.0 / (double)delta) : 0.f;
+            body.pen_live = PEN && alpha > 0.f && isfinite(alpha) && isfinite(beta);
+            body.inv_alpha = body.pen_live ? (float)(1.0 / (double)alpha) : 0.f;
+            body.pen_coef = body.pen_live ? (float)((double)a.lambda * (double)beta / (double)alpha) : 0.f;
+            body.beta_m1 = body.pen_live ? beta - 1.0f : 0.f;
+            if constexpr (sizeof(T) == 2 && (PEN || EXTRA))
+                process_chunk<ElemBf16x4, 8, decltype(body), 64>(x, start, len, body);
+            else
+                process_chunk<Elem<T>, 4, decltype(body), 64>(x, start, len, body);
+            if constexpr (RATE) {
+                const uint64_t clz = wave_reduce((uint64_t)body.clz_sum, OpAdd());
+                const uint32_t um = wave_reduce(body.u_max, OpMax());
+                const uint32_t nan = wave_reduce((uint32_t)body.nan_seen, OpOr());
+                if (lane == 0) {
+                    gg_rate_t r;
+                    r.n = (uint64_t)len; r.n_clamped = 0; r.entropy_bits = 0.0; r.delta = delta;
+                    if (ok) {
+                        r.eg_bits = (uint64_t)len * a.eg_const - 2ull * clz;
+                        r.u_max = um;
+                        r.fl_bits = um ? 32u - (uint32_t)__builtin_clz(um) : 1u;
+                        r.flags = (nan ? GG_F_NONFINITE : 0u) | (um >= 2147483647u ? GG_F_SATURATED : 0u);
+                    } else {
+                        r.eg_bits = 0; r.u_max = 0; r.fl_bits = 0; r.flags = GG_F_DEGENERATE;
+                    }
+                    a.rate[row] = r;
+                }
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void k_rate_finalize(gg_rate_t *__restrict__ rate, const uint64_t *__restrict__ hist,
                                                           int32_t nbins) {
     __shared__ double red[kWaves];
@@ -718,6 +813,41 @@ static int launch_seg_prepare(const Geometry &g, const PrepArgs &p, hipStream_t 
     return check_launch();
 }
 
+// wave-per-row launch: enough blocks to fill the machine, each wave strides over rows
+template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
+static int launch_rows_inst(const void *x, const RowsArgs &a, hipStream_t st) {
+    const int bpc = resident_blocks(k_rows<T, MODE, RATE, PEN, EXTRA>, 0, 8);
+    int64_t blocks = (a.rows + kWaves - 1) / kWaves;
+    const int64_t cap = (int64_t)kComputeUnits * bpc;
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL((k_rows<T, MODE, RATE, PEN, EXTRA>), dim3((unsigned)blocks), dim3(kBlock), 0, st,
+                       static_cast<const T *>(x), a);
+    return check_launch();
+}
+
+template <typename T, int MODE>
+static int launch_rows_mode(const void *x, const RowsArgs &a, bool rate, bool pen, bool extra, hipStream_t st) {
+    if (rate && !pen && !extra) return launch_rows_inst<T, MODE, true, false, false>(x, a, st);
+    if (rate && pen && !extra) return launch_rows_inst<T, MODE, true, true, false>(x, a, st);
+    if (rate && !pen && extra) return launch_rows_inst<T, MODE, true, false, true>(x, a, st);
+    if (rate && pen && extra) return launch_rows_inst<T, MODE, true, true, true>(x, a, st);
+    return GG_ERR_INVALID_ARG;
+}
+
+static bool rows_take_wave_path(int64_t rows, int64_t cols) { return rows > 0 && cols > 0 && cols <= kRowWaveMax; }
+
+static int launch_rows(const void *x, int dtype, RowsArgs a, int eg_k, int round_mode, bool rate, bool pen, hipStream_t st) {
+    a.eg_add = 1u << eg_k; a.eg_const = 63u - (uint32_t)eg_k; a.sc = solve_const();
+    const bool extra = a.symbols != nullptr;
+    return by_dtype(dtype, [&](auto *tag) {
+        using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
+        if (!rate && !pen) return launch_rows_inst<T, GG_FLOOR, false, false, false>(x, a, st);
+        if (!rate) return launch_rows_inst<T, GG_FLOOR, false, true, false>(x, a, st);
+        if (round_mode == GG_FLOOR) return launch_rows_mode<T, GG_FLOOR>(x, a, rate, pen, extra, st);
+        return launch_rows_mode<T, GG_NEAREST_EVEN>(x, a, rate, pen, extra, st);
+    });
+}
+
 static int check_rate_args(int eg_k, int round_mode, int32_t nbins, const uint64_t *hist, const int32_t *symbols) {
     if (eg_k < 0 || eg_k > GG_MAX_EG_K) return GG_ERR_INVALID_ARG;
     if (round_mode != GG_FLOOR && round_mode != GG_NEAREST_EVEN) return GG_ERR_INVALID_ARG;
@@ -750,7 +880,7 @@ static int fused_common(Geometry &g, const void *x, int dtype, float delta_div, 
     p.lambda = lambda; p.params = g.params(); p.rate = rate; p.want_pen = grad != nullptr;
     if ((rc = launch_fit(g, x, dtype, fit, &p, st)) != GG_OK) return rc;
     if (total_fit) {
-        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(64), 0, st, fit, (int64_t)g.S, total_fit, solve_const());
+        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit, (int64_t)g.S, total_fit, solve_const());
         if ((rc = check_launch()) != GG_OK) return rc;
     }
     QuantOpts o;
@@ -833,9 +963,16 @@ int gg_fit_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, gg_fit
     if (rows > 0 && (!out_dev || !aligned8(out_dev))) return GG_ERR_INVALID_ARG;
     if (total_out_dev && !aligned8(total_out_dev)) return GG_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = launch_fit(g, x_dev, dtype, out_dev, nullptr, st)) != GG_OK) return rc;
+    if (rows_take_wave_path(rows, cols)) {
+        RowsArgs a{};
+        a.rows = rows; a.cols = cols; a.fit = out_dev; a.do_fit = 1;
+        rc = launch_rows(x_dev, dtype, a, 0, GG_FLOOR, false, false, st);
+    } else {
+        rc = launch_fit(g, x_dev, dtype, out_dev, nullptr, st);
+    }
+    if (rc != GG_OK) return rc;
     if (total_out_dev) {
-        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(64), 0, st, out_dev, rows, total_out_dev, solve_const());
+        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, out_dev, rows, total_out_dev, solve_const());
         return check_launch();
     }
     return GG_OK;
@@ -893,6 +1030,12 @@ int gg_quantize_rate_rows(const void *x_dev, int dtype, int64_t rows, int64_t co
     if ((rc = check_rate_args(eg_k, round_mode, 0, nullptr, symbols_dev)) != GG_OK) return rc;
     if (rows > 0 && (!delta_dev || !out_dev || !aligned8(out_dev))) return GG_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
+    if (rows_take_wave_path(rows, cols)) {
+        RowsArgs a{};
+        a.rows = rows; a.cols = cols; a.rate = out_dev; a.delta_dev = delta_dev; a.delta_div = 0.f;
+        a.symbols = symbols_dev; a.do_fit = 0;
+        return launch_rows(x_dev, dtype, a, eg_k, round_mode, true, false, st);
+    }
     PrepArgs p{};
     p.delta_dev = delta_dev; p.delta_div = 0.f; p.params = g.params(); p.rate = out_dev; p.want_pen = 0;
     if ((rc = launch_seg_prepare(g, p, st)) != GG_OK) return rc;
@@ -1029,6 +1172,19 @@ int gg_fused_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, floa
                           rate_dev, g.S, g.n_total)) != GG_OK)
         return rc;
     if (total_fit_dev && !aligned8(total_fit_dev)) return GG_ERR_INVALID_ARG;
+    if (rows_take_wave_path(rows, cols)) {
+        hipStream_t st = (hipStream_t)stream;
+        RowsArgs a{};
+        a.rows = rows; a.cols = cols; a.fit = fit_dev; a.rate = rate_dev; a.delta_dev = delta_dev; a.delta_div = delta_div;
+        a.lambda = lambda; a.symbols = rate_dev ? symbols_dev : nullptr; a.grad = grad_dev; a.accumulate = accumulate ? 1 : 0;
+        a.do_fit = 1;
+        if ((rc = launch_rows(x_dev, dtype, a, eg_k, round_mode, rate_dev != nullptr, grad_dev != nullptr, st)) != GG_OK) return rc;
+        if (total_fit_dev) {
+            hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit_dev, rows, total_fit_dev, solve_const());
+            return check_launch();
+        }
+        return GG_OK;
+    }
     return fused_common(g, x_dev, dtype, delta_div, delta_dev, eg_k, round_mode, 0, nullptr, symbols_dev, lambda, grad_dev,
                         accumulate ? 1 : 0, fit_dev, total_fit_dev, rate_dev, (hipStream_t)stream);
 }
