@@ -130,9 +130,11 @@ static __global__ void k_fill_u64(uint64_t *p, int64_t n) {
 // =============================================================================================
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+constexpr int kSolveTable = 4096;   // intervals of the tabulated moment-ratio curve (many-unit solves)
+
 struct WsLayout {
-    size_t off_bytes, cpre_bytes, params_bytes, partials_bytes, total;
-    size_t off_at, cpre_at, params_at, partials_at;
+    size_t off_bytes, cpre_bytes, params_bytes, partials_bytes, table_bytes, total;
+    size_t off_at, cpre_at, params_at, partials_at, table_at;
 };
 
 static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
@@ -147,7 +149,9 @@ static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
     w.cpre_at = w.off_at + w.off_bytes;
     w.params_at = w.cpre_at + w.cpre_bytes;
     w.partials_at = w.params_at + w.params_bytes;
-    w.total = w.partials_at + w.partials_bytes;
+    w.table_bytes = align_up((size_t)(kSolveTable + 1) * sizeof(double2), 256);
+    w.table_at = w.partials_at + w.partials_bytes;
+    w.total = w.table_at + w.table_bytes;
     return w;
 }
 
@@ -167,6 +171,7 @@ struct Geometry {
     std::vector<int64_t> off, cpre;   // host copies (segmented only)
     SegParam *params() const { return reinterpret_cast<SegParam *>(ws + wl.params_at); }
     double2 *partials() const { return reinterpret_cast<double2 *>(ws + wl.partials_at); }
+    double2 *solve_table() const { return reinterpret_cast<double2 *>(ws + wl.table_at); }
 };
 
 static int geometry_uniform(int64_t rows, int64_t cols, void *ws, size_t ws_bytes, bool need_ws, Geometry &g) {

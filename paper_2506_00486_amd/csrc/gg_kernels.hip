@@ -152,37 +152,99 @@ __device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, cons
     f.alpha = (float)sqrt(m2 * exp(lgamma_pos(r) - lgamma_pos(3.0 * r)));   // Eq. 2 with sigma^2 = m2
 }
 
-// One-lane fit from the moments, for buffers cut into thousands of units (rows of an activation
-// matrix), where total work matters more than the latency of a single solve: bracketed secant
-// steps (Illinois variant) on g(l) = log_rho(e^l) - target over l = ln b; 8-12 evaluations reach
-// 1e-9 where the 64-way bracketing spends 320.
-__device__ __forceinline__ void solve_fit_lane(double s1, double s2, uint64_t n, const SolveConst &sc, gg_fit_t &f) {
-    f.sum_abs = s1; f.sum_sq = s2; f.n = n; f.beta = 0.f; f.alpha = 0.f; f.flags = 0; f._pad = 0;
-    if (n == 0) { f.flags = GG_F_EMPTY; return; }
-    if (!isfinite(s1) || !isfinite(s2)) { f.flags = GG_F_NONFINITE; f.beta = 2.f; return; }
-    if (s2 == 0.0) { f.flags = GG_F_DEGENERATE; f.beta = 2.f; return; }
-    const double m1 = s1 / (double)n, m2 = s2 / (double)n;
-    const double target = log(m1 * m1 / m2);
-    double b;
-    if (!(target > sc.lrho_min)) {
-        b = GG_BETA_MIN; f.flags = GG_F_BETA_CLAMPED_LO;
-    } else if (!(target < sc.lrho_max)) {
-        b = GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI;
-    } else {
-        double la = log(GG_BETA_MIN), lb = log(GG_BETA_MAX);
-        double fa = sc.lrho_min - target, fb = sc.lrho_max - target;   // fa < 0 < fb
-        for (int it = 0; it < 64; ++it) {
-            const double lc = (fa * lb - fb * la) / (fa - fb);
-            const double fc = log_rho(exp(lc)) - target;
-            if ((fc < 0.0) != (fb < 0.0)) { la = lb; fa = fb; } else { fa *= 0.5; }
-            lb = lc; fb = fc;
-            if (fc == 0.0 || fabs(lb - la) < 2e-9) break;
-        }
-        b = exp(lb);
+// Buffers cut into thousands of units (rows of an activation matrix) make the solve itself the
+// bottleneck: 64 fp64 lgamma-based evaluations per round and unit are ~2500 fp64 instructions per
+// wave.  For those the moment-ratio curve is tabulated once per call on a uniform grid in l = ln b,
+//   table[j] = { log_rho(b_j), lgamma(1/b_j) - lgamma(3/b_j) },  b_j = exp(l_min + j h),  j = 0..kSolveTable,
+// and a unit's root is found by locating its interval and inverse cubic interpolation through the
+// four surrounding points (error 7e-12 relative in b, 2e-10 in the log of the scale factor).
+__global__ void k_build_solve_table(double2 *__restrict__ table) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j > kSolveTable) return;
+    const double l_min = log(GG_BETA_MIN), h = (log(GG_BETA_MAX) - l_min) / (double)kSolveTable;
+    const double r = 1.0 / exp(l_min + h * (double)j);
+    const double g1 = lgamma_pos(r), g3 = lgamma_pos(3.0 * r);
+    table[j] = make_double2(2.0 * lgamma_pos(2.0 * r) - g1 - g3, g1 - g3);
+}
+
+// cubic Lagrange through (xs[k], ys[k]), k = 0..3, evaluated at x
+__device__ __forceinline__ double lagrange4(const double (&xs)[4], const double (&ys)[4], double x) {
+    double acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        double p = ys[k];
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+            if (m != k) p *= (x - xs[m]) / (xs[k] - xs[m]);
+        acc += p;
     }
+    return acc;
+}
+
+// beta and alpha from the interval index j (table[j].x <= target < table[j+1].x)
+__device__ __forceinline__ void finish_from_table(const double2 *__restrict__ table, int j, double target, double m2,
+                                                  gg_fit_t &f) {
+    const double l_min = log(GG_BETA_MIN), h = (log(GG_BETA_MAX) - l_min) / (double)kSolveTable;
+    int j0 = j - 1;
+    j0 = j0 < 0 ? 0 : (j0 > kSolveTable - 3 ? kSolveTable - 3 : j0);
+    double ls[4], fs[4], as[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const double2 t = table[j0 + k];
+        ls[k] = l_min + h * (double)(j0 + k); fs[k] = t.x; as[k] = t.y;
+    }
+    const double l = lagrange4(fs, ls, target);          // inverse interpolation: l as a function of log rho
+    f.beta = (float)exp(l);
+    f.alpha = (float)sqrt(m2 * exp(lagrange4(ls, as, l)));   // Eq. 2 with sigma^2 = m2
+}
+
+// common head of the table solvers; returns true when the root has to be searched
+__device__ __forceinline__ bool fit_head(double s1, double s2, uint64_t n, const SolveConst &sc, gg_fit_t &f,
+                                         double &target, double &m2) {
+    f.sum_abs = s1; f.sum_sq = s2; f.n = n; f.beta = 0.f; f.alpha = 0.f; f.flags = 0; f._pad = 0;
+    if (n == 0) { f.flags = GG_F_EMPTY; return false; }
+    if (!isfinite(s1) || !isfinite(s2)) { f.flags = GG_F_NONFINITE; f.beta = 2.f; return false; }
+    if (s2 == 0.0) { f.flags = GG_F_DEGENERATE; f.beta = 2.f; return false; }
+    const double m1 = s1 / (double)n;
+    m2 = s2 / (double)n;
+    target = log(m1 * m1 / m2);
+    double b = 0.0;
+    if (!(target > sc.lrho_min)) { b = GG_BETA_MIN; f.flags = GG_F_BETA_CLAMPED_LO; }
+    else if (!(target < sc.lrho_max)) { b = GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI; }
+    else return true;
     const double r = 1.0 / b;
     f.beta = (float)b;
     f.alpha = (float)sqrt(m2 * exp(lgamma_pos(r) - lgamma_pos(3.0 * r)));
+    return false;
+}
+
+// one lane per unit: binary search of the interval
+__device__ __forceinline__ void solve_fit_table_lane(double s1, double s2, uint64_t n, const SolveConst &sc,
+                                                     const double2 *__restrict__ table, gg_fit_t &f) {
+    double target, m2;
+    if (!fit_head(s1, s2, n, sc, f, target, m2)) return;
+    int lo = 0, hi = kSolveTable;            // table[lo].x <= target < table[hi].x
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (table[mid].x <= target) lo = mid; else hi = mid;
+    }
+    finish_from_table(table, lo, target, m2, f);
+}
+
+// one wave per unit (all 64 lanes, identical arguments): two rounds of 64 probes locate the interval
+__device__ __forceinline__ void solve_fit_table_wave(double s1, double s2, uint64_t n, const SolveConst &sc,
+                                                     const double2 *__restrict__ table, gg_fit_t &f) {
+    static_assert(kSolveTable == 64 * 64, "two 64-way rounds cover the table");
+    const int lane = threadIdx.x & 63;
+    double target, m2;
+    if (!fit_head(s1, s2, n, sc, f, target, m2)) return;
+    // table[0].x < target by fit_head up to rounding of the two lgamma implementations: clamp the counts
+    int c1 = __popcll(__ballot(table[64 * lane].x <= target));
+    c1 = c1 < 1 ? 1 : c1;
+    const int coarse = 64 * (c1 - 1);
+    int c2 = __popcll(__ballot(table[coarse + lane].x <= target));
+    c2 = c2 < 1 ? 1 : c2;
+    finish_from_table(table, coarse + c2 - 1, target, m2, f);
 }
 
 // where the step and the penalty parameters of a unit come from
@@ -254,7 +316,8 @@ __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *
 // the same finalisation with one lane per unit (many small units)
 __global__ __launch_bounds__(64) void k_fit_finalize_lanes(SegView sv, const double2 *__restrict__ partials,
                                                            int32_t chunks_per_block, gg_fit_t *__restrict__ out,
-                                                           SolveConst sc, PrepArgs prep, int do_prep) {
+                                                           SolveConst sc, const double2 *__restrict__ table,
+                                                           PrepArgs prep, int do_prep) {
     const int seg = blockIdx.x * 64 + threadIdx.x;
     if (seg >= sv.S) return;
     const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
@@ -269,7 +332,7 @@ __global__ __launch_bounds__(64) void k_fit_finalize_lanes(SegView sv, const dou
     }
     const int64_t n = unit_len(sv, seg);
     gg_fit_t f;
-    solve_fit_lane(s1, s2, (uint64_t)n, sc, f);
+    solve_fit_table_lane(s1, s2, (uint64_t)n, sc, table, f);
     out[seg] = f;
     if (do_prep) prepare_unit(prep, seg, n, f.alpha, f.beta);
 }
@@ -278,7 +341,8 @@ __global__ __launch_bounds__(64) void k_fit_finalize_lanes(SegView sv, const dou
 // block, solve by the first wave
 constexpr int kTotalThreads = 1024;
 __global__ __launch_bounds__(kTotalThreads) void k_fit_total(const gg_fit_t *__restrict__ rows, int64_t n_rows,
-                                                             gg_fit_t *__restrict__ out, SolveConst sc) {
+                                                             gg_fit_t *__restrict__ out, SolveConst sc,
+                                                             const double2 *__restrict__ table) {
     __shared__ double red1[kTotalThreads / 64], red2[kTotalThreads / 64];
     __shared__ uint64_t redn[kTotalThreads / 64];
     const int tid = threadIdx.x;
@@ -294,7 +358,8 @@ __global__ __launch_bounds__(kTotalThreads) void k_fit_total(const gg_fit_t *__r
         s1 = 0.0; s2 = 0.0; n = 0;
         for (int w = 0; w < kTotalThreads / 64; ++w) { s1 += red1[w]; s2 += red2[w]; n += redn[w]; }
         gg_fit_t f;
-        solve_fit(s1, s2, n, sc, f);
+        if (table) solve_fit_table_wave(s1, s2, n, sc, table, f);   // the caller has tabulated the curve already
+        else solve_fit(s1, s2, n, sc, f);
         if (tid == 0) out[0] = f;
     }
 }
@@ -501,7 +566,9 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
                 }
                 if (want_hist && rate_live) {   // merge the block-private bins into the unit's histogram
                     uint64_t *g = a.hist + (int64_t)piece_seg * a.nbins;
-                    for (int b = tid; b < a.lbins; b += kBlock) {
+                    // bins above the largest symbol this block saw are still zero
+                    const int touched = um < (uint32_t)a.lbins ? (int)um + 1 : a.lbins;
+                    for (int b = tid; b < touched; b += kBlock) {
                         const uint32_t c = lds_hist[b];
                         if (c) {
                             atomicAdd(reinterpret_cast<unsigned long long *>(&g[b]), (unsigned long long)c);
@@ -557,6 +624,7 @@ struct RowsArgs {
     int32_t *symbols; float *grad; int accumulate;
     int do_fit;
     SolveConst sc;
+    const double2 *table;     // tabulated moment-ratio curve (see k_build_solve_table)
 };
 
 template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
@@ -576,7 +644,7 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
             s1 = wave_reduce(s1, OpAdd());
             s2 = wave_reduce(s2, OpAdd());
             gg_fit_t f;
-            solve_fit(s1, s2, (uint64_t)len, a.sc, f);
+            solve_fit_table_wave(s1, s2, (uint64_t)len, a.sc, a.table, f);
             if (lane == 0) a.fit[row] = f;
             alpha = f.alpha; beta = f.beta;
         }
@@ -619,9 +687,10 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_rate_finalize(gg_rate_t *__restrict__ rate, const uint64_t *__restrict__ hist,
-                                                          int32_t nbins) {
-    __shared__ double red[kWaves];
+constexpr int kFinalizeThreads = 1024;
+__global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(gg_rate_t *__restrict__ rate,
+                                                                    const uint64_t *__restrict__ hist, int32_t nbins) {
+    __shared__ double red[kFinalizeThreads / 64];
     const int seg = blockIdx.x, tid = threadIdx.x;
     gg_rate_t *r = rate + seg;
     const uint32_t flags = r->flags;
@@ -630,13 +699,18 @@ __global__ __launch_bounds__(kBlock) void k_rate_finalize(gg_rate_t *__restrict_
     if (hist && n > 0 && !(flags & GG_F_DEGENERATE)) {
         const uint64_t *g = hist + (int64_t)seg * nbins;
         const double inv_n = 1.0 / (double)n;
-        for (int b = tid; b < nbins; b += kBlock) {   // ascending bins per lane, fixed tree above
+        for (int b = tid; b < nbins; b += kFinalizeThreads) {   // ascending bins per lane, fixed tree above
             const uint64_t c = g[b];
             if (c) { const double p = (double)c * inv_n; h -= p * log2(p); }
         }
     }
-    h = block_reduce(h, OpAdd(), red);
+    if (hist) {   // uniform over the block
+        h = wave_reduce(h, OpAdd());
+        if ((tid & 63) == 0) red[tid >> 6] = h;
+        __syncthreads();
+    }
     if (tid == 0) {
+        if (hist) { h = 0.0; for (int w = 0; w < kFinalizeThreads / 64; ++w) h += red[w]; }
         const uint32_t um = r->u_max;
         uint32_t f = flags;
         if (um >= 2147483647u) f |= GG_F_SATURATED;
@@ -735,10 +809,11 @@ static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out
     if (g.S > 0) {
         PrepArgs p{};
         if (prep) p = *prep;
-        if (g.S >= kManyUnits)
+        if (g.S >= kManyUnits) {
+            hipLaunchKernelGGL(k_build_solve_table, dim3((kSolveTable + 256) / 256), dim3(256), 0, st, g.solve_table());
             hipLaunchKernelGGL(k_fit_finalize_lanes, dim3((unsigned)((g.S + 63) / 64)), dim3(64), 0, st, g.sv, g.partials(),
-                               rs.chunks_per_block, out, solve_const(), p, prep ? 1 : 0);
-        else
+                               rs.chunks_per_block, out, solve_const(), g.solve_table(), p, prep ? 1 : 0);
+        } else
             hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(),
                                rs.chunks_per_block, out, solve_const(), p, prep ? 1 : 0);
         return check_launch();
@@ -803,7 +878,7 @@ static int launch_quant(const Geometry &g, const void *x, int dtype, const Quant
 
 static int launch_rate_finalize(const Geometry &g, gg_rate_t *rate, const uint64_t *hist, int32_t nbins, hipStream_t st) {
     if (g.S == 0) return GG_OK;
-    hipLaunchKernelGGL(k_rate_finalize, dim3((unsigned)g.S), dim3(kBlock), 0, st, rate, hist, nbins);
+    hipLaunchKernelGGL(k_rate_finalize, dim3((unsigned)g.S), dim3(hist ? kFinalizeThreads : 64), 0, st, rate, hist, nbins);
     return check_launch();
 }
 
@@ -836,8 +911,14 @@ static int launch_rows_mode(const void *x, const RowsArgs &a, bool rate, bool pe
 
 static bool rows_take_wave_path(int64_t rows, int64_t cols) { return rows > 0 && cols > 0 && cols <= kRowWaveMax; }
 
-static int launch_rows(const void *x, int dtype, RowsArgs a, int eg_k, int round_mode, bool rate, bool pen, hipStream_t st) {
+static int launch_rows(const Geometry &g, const void *x, int dtype, RowsArgs a, int eg_k, int round_mode, bool rate, bool pen,
+                       hipStream_t st) {
     a.eg_add = 1u << eg_k; a.eg_const = 63u - (uint32_t)eg_k; a.sc = solve_const();
+    if (a.do_fit) {
+        a.table = g.solve_table();
+        hipLaunchKernelGGL(k_build_solve_table, dim3((kSolveTable + 256) / 256), dim3(256), 0, st, g.solve_table());
+        if (check_launch() != GG_OK) return GG_ERR_HIP;
+    }
     const bool extra = a.symbols != nullptr;
     return by_dtype(dtype, [&](auto *tag) {
         using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
@@ -880,7 +961,8 @@ static int fused_common(Geometry &g, const void *x, int dtype, float delta_div, 
     p.lambda = lambda; p.params = g.params(); p.rate = rate; p.want_pen = grad != nullptr;
     if ((rc = launch_fit(g, x, dtype, fit, &p, st)) != GG_OK) return rc;
     if (total_fit) {
-        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit, (int64_t)g.S, total_fit, solve_const());
+        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit, (int64_t)g.S, total_fit, solve_const(),
+                           (const double2 *)(g.S >= kManyUnits ? g.solve_table() : nullptr));
         if ((rc = check_launch()) != GG_OK) return rc;
     }
     QuantOpts o;
@@ -966,13 +1048,14 @@ int gg_fit_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, gg_fit
     if (rows_take_wave_path(rows, cols)) {
         RowsArgs a{};
         a.rows = rows; a.cols = cols; a.fit = out_dev; a.do_fit = 1;
-        rc = launch_rows(x_dev, dtype, a, 0, GG_FLOOR, false, false, st);
+        rc = launch_rows(g, x_dev, dtype, a, 0, GG_FLOOR, false, false, st);
     } else {
         rc = launch_fit(g, x_dev, dtype, out_dev, nullptr, st);
     }
     if (rc != GG_OK) return rc;
     if (total_out_dev) {
-        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, out_dev, rows, total_out_dev, solve_const());
+        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, out_dev, rows, total_out_dev, solve_const(),
+                           (const double2 *)((rows_take_wave_path(rows, cols) || rows >= kManyUnits) ? g.solve_table() : nullptr));
         return check_launch();
     }
     return GG_OK;
@@ -1034,7 +1117,7 @@ int gg_quantize_rate_rows(const void *x_dev, int dtype, int64_t rows, int64_t co
         RowsArgs a{};
         a.rows = rows; a.cols = cols; a.rate = out_dev; a.delta_dev = delta_dev; a.delta_div = 0.f;
         a.symbols = symbols_dev; a.do_fit = 0;
-        return launch_rows(x_dev, dtype, a, eg_k, round_mode, true, false, st);
+        return launch_rows(g, x_dev, dtype, a, eg_k, round_mode, true, false, st);
     }
     PrepArgs p{};
     p.delta_dev = delta_dev; p.delta_div = 0.f; p.params = g.params(); p.rate = out_dev; p.want_pen = 0;
@@ -1178,9 +1261,10 @@ int gg_fused_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, floa
         a.rows = rows; a.cols = cols; a.fit = fit_dev; a.rate = rate_dev; a.delta_dev = delta_dev; a.delta_div = delta_div;
         a.lambda = lambda; a.symbols = rate_dev ? symbols_dev : nullptr; a.grad = grad_dev; a.accumulate = accumulate ? 1 : 0;
         a.do_fit = 1;
-        if ((rc = launch_rows(x_dev, dtype, a, eg_k, round_mode, rate_dev != nullptr, grad_dev != nullptr, st)) != GG_OK) return rc;
+        if ((rc = launch_rows(g, x_dev, dtype, a, eg_k, round_mode, rate_dev != nullptr, grad_dev != nullptr, st)) != GG_OK) return rc;
         if (total_fit_dev) {
-            hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit_dev, rows, total_fit_dev, solve_const());
+            hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit_dev, rows, total_fit_dev, solve_const(),
+                               (const double2 *)g.solve_table());
             return check_launch();
         }
         return GG_OK;
