@@ -412,3 +412,35 @@ def test_many_small_units_use_the_per_lane_solver(gg):
     hbr = host_bits(xr)
     for r_ in range(0, rows, 7):
         check_fit(rec[r_], oracle.fit(hbr[r_ * cols:(r_ + 1) * cols]), f"row {r_}")
+
+
+def test_fused_pass_is_graph_capturable(gg):
+    """The library enqueues kernels only (tables travel as kernel arguments; no allocation, memset,
+    copy or synchronisation), so a whole pass can be captured into a HIP graph and replayed."""
+    segs = gg_inputs.scaled_layout(gg_inputs.gradient_bucket_1p5b()[:27], 211)
+    flat, off, _, _ = gg_inputs.make_bucket(segs, seed=17, device=DEV)
+    S = len(segs)
+    ws = gg.Workspace(flat.numel(), S)
+    fit = torch.empty(S * 40, dtype=torch.uint8, device=DEV)
+    rate = torch.empty(S * 48, dtype=torch.uint8, device=DEV)
+    grad = torch.empty(flat.numel(), device=DEV)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, lam=1e-4, grad=grad, fit=fit, rate=rate)   # warm-up
+    torch.cuda.current_stream().wait_stream(stream)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, lam=1e-4, grad=grad, fit=fit, rate=rate)
+    for rep in range(3):
+        flat.mul_(1.0 + 0.25 * rep)              # eager work between replays, new input values
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (fit.cpu().numpy().tobytes(), rate.cpu().numpy().tobytes(), grad.cpu().numpy().tobytes())
+        e_fit = torch.empty_like(fit)
+        e_rate = torch.empty_like(rate)
+        e_grad = torch.empty_like(grad)
+        gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, lam=1e-4, grad=e_grad, fit=e_fit, rate=e_rate)
+        torch.cuda.synchronize()
+        assert got == (e_fit.cpu().numpy().tobytes(), e_rate.cpu().numpy().tobytes(), e_grad.cpu().numpy().tobytes()), rep
