@@ -216,6 +216,16 @@ def main():
         extra["with_penalty_written"] = {"ms": round(ms_pen, 4), "Gelem/s": round(n / ms_pen / 1e6, 2),
                                          "algorithmic_GB/s": round(12.0 * n / ms_pen / 1e6, 1)}
         del grad
+        # one-sweep mode: steps given up front (e.g. from the previous training step): x is read once
+        delta1 = gg.gg_delta_from_fit(fit, S, 16.0)
+
+        def step_one_sweep():
+            gg.gg_fused_segmented(flat, off, ws, delta_div=0.0, delta=delta1, eg_k=0, fit=fit, rate=rate)
+
+        step_one_sweep()
+        _, ms_1 = time_steps(step_one_sweep, max(3, args.steps // 2), torch)
+        extra["one_sweep_given_steps"] = {"ms": round(ms_1, 4), "Gelem/s": round(n / ms_1 / 1e6, 2),
+                                          "algorithmic_GB/s": round(4.0 * n / ms_1 / 1e6, 1)}
         ns = 202_383_360 if not args.small else 202_383_360 // 64
         xs = torch.empty(ns, dtype=torch.bfloat16, device=dev)
 

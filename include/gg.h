@@ -163,7 +163,10 @@ double gg_compression_ratio(double mean_bits, double fl_bits);
 /* Per unit s: fit -> fit_dev[s]; step Delta_s = fit alpha_s / delta_div (delta_div > 0) or
  * delta_dev[s] (delta_div <= 0); rate -> rate_dev[s] (skipped entirely when rate_dev is NULL);
  * optional histogram (hist_dev, S*nbins) and symbols; optional penalty gradient with the fitted
- * (alpha_s, beta_s) into grad_dev (NULL = none).  Everything stays on the device. */
+ * (alpha_s, beta_s) into grad_dev (NULL = none).  Everything stays on the device.
+ * When the steps are given (delta_div <= 0, delta_dev != NULL) and no penalty is asked for, nothing
+ * depends on this call's own fit and x is read ONCE: moments and rate come from the same sweep
+ * (e.g. GCT monitoring with the steps of the previous training step). */
 int gg_fused_segmented(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S,
                        float delta_div, const float *delta_dev, int eg_k, int round_mode,
                        int32_t nbins, uint64_t *hist_dev, int32_t *symbols_dev,

@@ -396,6 +396,8 @@ struct QuantArgs {
     // PEN
     float *grad;
     int accumulate;
+    // FIT
+    double2 *partials;
     // work split
     int64_t n_chunks;
     int32_t chunks_per_block;
@@ -433,8 +435,11 @@ __device__ __forceinline__ V stream_load(const V *p) {
     return __builtin_nontemporal_load(p);
 }
 
-template <int MODE, bool RATE, bool PEN, bool EXTRA>
+template <int MODE, bool RATE, bool PEN, bool EXTRA, bool FIT = false>
 struct QuantBody {
+    // moment sums of the current chunk when the sweep also fits (FIT): the one-sweep mode
+    float s1[4] = {0.f, 0.f, 0.f, 0.f};
+    float s2[4] = {0.f, 0.f, 0.f, 0.f};
     // unit parameters
     float inv_delta, inv_alpha, beta_m1, pen_coef;
     bool pen_live, hist_live;
@@ -479,6 +484,13 @@ struct QuantBody {
 
     template <int W>
     __device__ __forceinline__ void vec(const float (&v)[W], int64_t idx) {
+        if constexpr (FIT) {
+#pragma unroll
+            for (int j = 0; j < W; ++j) {
+                s1[j & 3] += fabsf(v[j]);
+                s2[j & 3] = __builtin_fmaf(v[j], v[j], s2[j & 3]);
+            }
+        }
         if constexpr (RATE) {
             int32_t q[W];
 #pragma unroll
@@ -505,6 +517,10 @@ struct QuantBody {
     }
 
     __device__ __forceinline__ void one(float v, int64_t idx) {
+        if constexpr (FIT) {
+            s1[0] += fabsf(v);
+            s2[0] = __builtin_fmaf(v, v, s2[0]);
+        }
         if constexpr (RATE) {
             const int32_t q = quant(v);
             if constexpr (EXTRA) { if (symbols) symbols[idx] = q; }
@@ -519,11 +535,14 @@ struct QuantBody {
 // A block owns a run of consecutive chunks.  Lane accumulators (bit-length sum, u_max, NaN seen,
 // clamped count) live across chunks and are combined, then added to the unit's rate record with
 // integer atomics, only when the run leaves a unit or ends.
-template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
+// With FIT the same sweep also accumulates the moments exactly as k_fit_partials does (one-sweep mode:
+// the steps are given up front, so nothing has to wait for the fit).
+template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA, bool FIT = false>
 __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restrict__ x, QuantArgs a) {
     extern __shared__ uint32_t lds_hist[];
     __shared__ uint64_t red64[kWaves];
     __shared__ uint32_t red[3][kWaves];
+    __shared__ double redd[2][kWaves];
     const int tid = threadIdx.x;
     const int64_t first = (int64_t)blockIdx.x * a.chunks_per_block;
     int64_t last = first + a.chunks_per_block;
@@ -536,7 +555,7 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
         __syncthreads();
     }
 
-    QuantBody<MODE, RATE, PEN, EXTRA> body;
+    QuantBody<MODE, RATE, PEN, EXTRA, FIT> body;
     body.eg_add = a.eg_add;
     body.symbols = a.symbols; body.grad = a.grad; body.accumulate = a.accumulate;
     body.lds_hist = lds_hist;
@@ -545,10 +564,27 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
 
     int piece_seg = -1;
     bool rate_live = false;
-    int64_t piece_elems = 0;
+    int64_t piece_elems = 0, piece_first = first;
     int32_t piece_chunks = 0;
+    double d1 = 0.0, d2 = 0.0;     // FIT: fp64 lane totals of the (run, unit) piece
 
-    auto flush = [&]() {   // fold the lanes of this piece into the unit's record
+    auto flush = [&](bool piece_ends) {   // fold the lanes of this piece into the unit's record
+        if constexpr (FIT) {
+            if (piece_seg >= 0 && piece_ends) {   // same slot convention as k_fit_partials
+                const double sa = wave_reduce(d1, OpAdd());
+                const double sb = wave_reduce(d2, OpAdd());
+                if ((tid & 63) == 0) { redd[0][tid >> 6] = sa; redd[1][tid >> 6] = sb; }
+                __syncthreads();
+                if (tid == 0) {
+                    double2 r;
+                    r.x = (redd[0][0] + redd[0][1]) + (redd[0][2] + redd[0][3]);
+                    r.y = (redd[1][0] + redd[1][1]) + (redd[1][2] + redd[1][3]);
+                    a.partials[piece_first] = r;
+                }
+                __syncthreads();
+                d1 = 0.0; d2 = 0.0;
+            }
+        }
         if constexpr (RATE) {
             if (piece_seg >= 0) {
                 const uint64_t clz = block_reduce((uint64_t)body.clz_sum, OpAdd(), red64);
@@ -586,7 +622,8 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
     RunCursor cur;
     for (cur.init(sv, first, last); cur.valid(); cur.next(sv)) {
         if (cur.L.seg != piece_seg || piece_chunks >= 32768) {
-            flush();
+            flush(cur.L.seg != piece_seg);
+            if (cur.L.seg != piece_seg) piece_first = cur.chunk;
             piece_seg = cur.L.seg;
             const SegParam P = a.params ? a.params[piece_seg] : a.single;
             rate_live = RATE && !(P.flags & kSkipRate);
@@ -600,10 +637,16 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
             process_chunk<ElemBf16x4, 8>(x, cur.L.start, cur.L.len, body);
         else
             process_chunk<Elem<T>, (sizeof(T) == 2 ? GG_U_QUANT / 2 : GG_U_QUANT)>(x, cur.L.start, cur.L.len, body);
+        if constexpr (FIT) {   // per chunk: <= 16-term fp32 lane sums into the fp64 lane totals
+            d1 += ((double)body.s1[0] + (double)body.s1[1]) + ((double)body.s1[2] + (double)body.s1[3]);
+            d2 += ((double)body.s2[0] + (double)body.s2[1]) + ((double)body.s2[2] + (double)body.s2[3]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { body.s1[j] = 0.f; body.s2[j] = 0.f; }
+        }
         piece_elems += cur.L.len;
         piece_chunks += 1;
     }
-    flush();
+    flush(true);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -793,6 +836,23 @@ static SolveConst solve_const() {
 #define GG_QUANT_BLOCKS_PER_CU 8
 #endif
 
+// per-unit sums of the pieces written by a sweep that used `chunks_per_block`, and the solve
+static int launch_fit_finalize(const Geometry &g, int32_t chunks_per_block, gg_fit_t *out, const PrepArgs *prep,
+                               hipStream_t st) {
+    if (g.S == 0) return GG_OK;
+    PrepArgs p{};
+    if (prep) p = *prep;
+    if (g.S >= kManyUnits) {
+        hipLaunchKernelGGL(k_build_solve_table, dim3((kSolveTable + 256) / 256), dim3(256), 0, st, g.solve_table());
+        hipLaunchKernelGGL(k_fit_finalize_lanes, dim3((unsigned)((g.S + 63) / 64)), dim3(64), 0, st, g.sv, g.partials(),
+                           chunks_per_block, out, solve_const(), g.solve_table(), p, prep ? 1 : 0);
+    } else {
+        hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(), chunks_per_block, out,
+                           solve_const(), p, prep ? 1 : 0);
+    }
+    return check_launch();
+}
+
 static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out, const PrepArgs *prep, hipStream_t st) {
     const int bpc = dtype == GG_BF16 ? resident_blocks(k_fit_partials<bf16_t>, 0, GG_FIT_BLOCKS_PER_CU)
                                      : resident_blocks(k_fit_partials<float>, 0, GG_FIT_BLOCKS_PER_CU);
@@ -806,19 +866,7 @@ static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out
         });
         if (rc != GG_OK) return rc;
     }
-    if (g.S > 0) {
-        PrepArgs p{};
-        if (prep) p = *prep;
-        if (g.S >= kManyUnits) {
-            hipLaunchKernelGGL(k_build_solve_table, dim3((kSolveTable + 256) / 256), dim3(256), 0, st, g.solve_table());
-            hipLaunchKernelGGL(k_fit_finalize_lanes, dim3((unsigned)((g.S + 63) / 64)), dim3(64), 0, st, g.sv, g.partials(),
-                               rs.chunks_per_block, out, solve_const(), g.solve_table(), p, prep ? 1 : 0);
-        } else
-            hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(),
-                               rs.chunks_per_block, out, solve_const(), p, prep ? 1 : 0);
-        return check_launch();
-    }
-    return GG_OK;
+    return launch_fit_finalize(g, rs.chunks_per_block, out, prep, st);
 }
 
 struct QuantOpts {
@@ -832,13 +880,16 @@ struct QuantOpts {
     gg_rate_t *rate_out = nullptr;
     const SegParam *params = nullptr;
     SegParam single{};
+    bool fit_too = false;              // one-sweep mode: the rate sweep also writes moment partials
+    int32_t chunks_per_block_out = 1;  // the run length the sweep used (the fit finalisation needs it)
 };
 
 constexpr int kMaxLdsBins = 12288;   // 48 KiB of block-private bins; higher symbols go to L2 atomics
 
-template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
-static int launch_quant_inst(const Geometry &g, const void *x, const QuantOpts &o, hipStream_t st) {
+template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA, bool FIT = false>
+static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hipStream_t st) {
     QuantArgs a{};
+    a.partials = g.ws ? g.partials() : nullptr;
     a.params = o.params; a.single = o.single; a.rate = o.rate_out;
     a.eg_add = 1u << o.eg_k; a.eg_const = 63u - (uint32_t)o.eg_k;
     a.symbols = o.symbols; a.hist = o.hist; a.nbins = o.nbins;
@@ -848,16 +899,20 @@ static int launch_quant_inst(const Geometry &g, const void *x, const QuantOpts &
     // one run per block that can be resident at once (registers, and LDS when block-private histogram
     // bins are in use), so the whole grid starts together and no block waits for a free slot
     const size_t lds = (size_t)a.lbins * sizeof(uint32_t);
-    const RunSplit rs = split_runs(g.n_chunks, resident_blocks(k_quant<T, MODE, RATE, PEN, EXTRA>, lds, GG_QUANT_BLOCKS_PER_CU));
+    const RunSplit rs = split_runs(g.n_chunks, resident_blocks(k_quant<T, MODE, RATE, PEN, EXTRA, FIT>, lds, GG_QUANT_BLOCKS_PER_CU));
     a.chunks_per_block = rs.chunks_per_block;
-    hipLaunchKernelGGL((k_quant<T, MODE, RATE, PEN, EXTRA>), dim3((unsigned)rs.blocks), dim3(kBlock), lds, st, g.sv,
+    o.chunks_per_block_out = rs.chunks_per_block;
+    hipLaunchKernelGGL((k_quant<T, MODE, RATE, PEN, EXTRA, FIT>), dim3((unsigned)rs.blocks), dim3(kBlock), lds, st, g.sv,
                        static_cast<const T *>(x), a);
     return check_launch();
 }
 
 template <typename T, int MODE>
-static int launch_quant_mode(const Geometry &g, const void *x, const QuantOpts &o, hipStream_t st) {
+static int launch_quant_mode(const Geometry &g, const void *x, QuantOpts &o, hipStream_t st) {
     const bool extra = o.hist || o.symbols;
+    if (o.fit_too && o.rate && !o.pen)
+        return extra ? launch_quant_inst<T, MODE, true, false, true, true>(g, x, o, st)
+                     : launch_quant_inst<T, MODE, true, false, false, true>(g, x, o, st);
     if (o.rate && !o.pen && !extra) return launch_quant_inst<T, MODE, true, false, false>(g, x, o, st);
     if (o.rate && o.pen && !extra) return launch_quant_inst<T, MODE, true, true, false>(g, x, o, st);
     if (o.rate && !o.pen && extra) return launch_quant_inst<T, MODE, true, false, true>(g, x, o, st);
@@ -865,7 +920,7 @@ static int launch_quant_mode(const Geometry &g, const void *x, const QuantOpts &
     return GG_ERR_INVALID_ARG;
 }
 
-static int launch_quant(const Geometry &g, const void *x, int dtype, const QuantOpts &o, hipStream_t st) {
+static int launch_quant(const Geometry &g, const void *x, int dtype, QuantOpts &o, hipStream_t st) {
     if (g.n_chunks == 0) return GG_OK;
     return by_dtype(dtype, [&](auto *tag) {
         using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
@@ -959,6 +1014,22 @@ static int fused_common(Geometry &g, const void *x, int dtype, float delta_div, 
     PrepArgs p{};
     p.fit = nullptr; p.delta_dev = delta_dev; p.delta_div = delta_div; p.delta_scalar = 0.f;
     p.lambda = lambda; p.params = g.params(); p.rate = rate; p.want_pen = grad != nullptr;
+    if (rate && !grad && !(delta_div > 0.f) && delta_dev) {
+        // One-sweep mode: the steps do not depend on this call's fit (e.g. they come from the previous
+        // training step), so moments and rate are taken from a single read of x: 4 B/elem instead of 8.
+        if ((rc = launch_seg_prepare(g, p, st)) != GG_OK) return rc;
+        QuantOpts o;
+        o.rate = true; o.eg_k = eg_k; o.round_mode = round_mode; o.nbins = nbins; o.hist = hist; o.symbols = symbols;
+        o.rate_out = rate; o.params = g.params(); o.fit_too = true;
+        if ((rc = run_second_sweep(g, x, dtype, o, st)) != GG_OK) return rc;
+        if ((rc = launch_fit_finalize(g, o.chunks_per_block_out, fit, nullptr, st)) != GG_OK) return rc;
+        if (total_fit) {
+            hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit, (int64_t)g.S, total_fit, solve_const(),
+                               (const double2 *)(g.S >= kManyUnits ? g.solve_table() : nullptr));
+            return check_launch();
+        }
+        return GG_OK;
+    }
     if ((rc = launch_fit(g, x, dtype, fit, &p, st)) != GG_OK) return rc;
     if (total_fit) {
         hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit, (int64_t)g.S, total_fit, solve_const(),

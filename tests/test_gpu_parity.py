@@ -444,3 +444,41 @@ def test_fused_pass_is_graph_capturable(gg):
         gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, lam=1e-4, grad=e_grad, fit=e_fit, rate=e_rate)
         torch.cuda.synchronize()
         assert got == (e_fit.cpu().numpy().tobytes(), e_rate.cpu().numpy().tobytes(), e_grad.cpu().numpy().tobytes()), rep
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_fused_one_sweep_mode_with_given_steps(gg, dtype):
+    """Steps handed in (no dependence on this call's fit): moments and rate from one read of x."""
+    layout = gg_inputs.gradient_bucket_1p5b()
+    segs = gg_inputs.scaled_layout(layout[:18] + layout[-1:], 311)
+    segs.insert(3, gg_inputs.Segment("empty", 0))
+    flat, off, alpha, _ = gg_inputs.make_bucket(segs, seed=23, device=DEV, dtype=dtype)
+    S = len(segs)
+    ws = gg.Workspace(flat.numel(), S)
+    dh = (np.insert(alpha, 3, 1e-4) / 16.0).astype(np.float32)          # "previous step's" steps
+    dh[5] = 0.0                                                          # one unit without a usable step
+    delta = torch.tensor(dh, device=DEV)
+    res = gg.gg_fused_segmented(flat, off, ws, delta_div=0.0, delta=delta, nbins=1024, want_symbols=True)
+    frec, rrec = gg.fit_records(res["fit"]), gg.rate_records(res["rate"])
+    hist = res["hist"].cpu().numpy().view(np.uint64).reshape(S, 1024)
+    sym = res["symbols"].cpu().numpy()
+    hb = host_bits(flat)
+    for s in range(S):
+        lo, hi = int(off[s]), int(off[s + 1])
+        check_fit(frec[s], oracle.fit(hb[lo:hi]), segs[s].name)
+        assert np.float32(rrec[s]["delta"]) == dh[s]
+        if hi == lo:
+            assert rrec[s]["flags"] == gg.GG_F_EMPTY
+            continue
+        if not dh[s] > 0:
+            assert rrec[s]["flags"] == gg.GG_F_DEGENERATE and rrec[s]["eg_bits"] == 0
+            continue
+        r, ohist, osym = oracle.quantize_rate(hb[lo:hi], float(dh[s]), nbins=1024, want_symbols=True)
+        check_rate(rrec[s], r, segs[s].name)
+        assert np.array_equal(hist[s], ohist) and np.array_equal(sym[lo:hi], osym)
+    # without histogram / symbols (the lean kernel) the integers are the same
+    res2 = gg.gg_fused_segmented(flat, off, ws, delta_div=0.0, delta=delta)
+    r2 = gg.rate_records(res2["rate"])
+    assert np.array_equal(r2["eg_bits"], rrec["eg_bits"]) and np.array_equal(r2["u_max"], rrec["u_max"])
+    f2 = gg.fit_records(res2["fit"])
+    assert np.allclose(f2["sum_sq"], frec["sum_sq"], rtol=1e-12) and np.allclose(f2["beta"], frec["beta"], rtol=1e-6)
