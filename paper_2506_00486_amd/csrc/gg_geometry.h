@@ -20,7 +20,7 @@ namespace gg {
 // ---------------------------------------------------------------------------------------------
 struct SegView {
     const int64_t *off;    // device: S+1 element offsets, or nullptr for uniform rows
-    const int64_t *cpre;   // device: S+1 chunk prefix sums (with off)
+    const int32_t *cpre;   // device: S+1 chunk prefix sums (with off)
     int64_t cols;          // uniform: elements per row
     int64_t cpr;           // uniform: chunks per row
     int32_t S;
@@ -133,21 +133,19 @@ static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
 constexpr int kSolveTable = 4096;   // intervals of the tabulated moment-ratio curve (many-unit solves)
 
 struct WsLayout {
-    size_t off_bytes, cpre_bytes, params_bytes, partials_bytes, table_bytes, total;
-    size_t off_at, cpre_at, params_at, partials_at, table_at;
+    size_t off_bytes, params_bytes, partials_bytes, table_bytes, total;   // off_bytes: offsets + chunk prefix
+    size_t off_at, params_at, partials_at, table_at;
 };
 
 static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
     WsLayout w;
     const size_t S = (size_t)n_units;
     const size_t max_chunks = (size_t)(n_total / kChunk) + S + 1;
-    w.off_bytes = align_up((S + 1) * sizeof(int64_t), 256);
-    w.cpre_bytes = w.off_bytes;
+    w.off_bytes = align_up((S + 1) * sizeof(int64_t) + ((S + 2) / 2) * sizeof(int64_t), 256);
     w.params_bytes = align_up(S * sizeof(SegParam), 256);
     w.partials_bytes = align_up(max_chunks * sizeof(double2), 256);
     w.off_at = 256;
-    w.cpre_at = w.off_at + w.off_bytes;
-    w.params_at = w.cpre_at + w.cpre_bytes;
+    w.params_at = w.off_at + w.off_bytes;
     w.partials_at = w.params_at + w.params_bytes;
     w.table_bytes = align_up((size_t)(kSolveTable + 1) * sizeof(double2), 256);
     w.table_at = w.partials_at + w.partials_bytes;
@@ -168,7 +166,8 @@ struct Geometry {
     int32_t S = 0;
     WsLayout wl{};
     char *ws = nullptr;
-    std::vector<int64_t> off, cpre;   // host copies (segmented only)
+    std::vector<int64_t> table;       // host copy of the unit table (segmented only): S+1 int64 element offsets
+                                      // followed by S+1 int32 chunk prefix sums, as it lies in the workspace
     SegParam *params() const { return reinterpret_cast<SegParam *>(ws + wl.params_at); }
     double2 *partials() const { return reinterpret_cast<double2 *>(ws + wl.partials_at); }
     double2 *solve_table() const { return reinterpret_cast<double2 *>(ws + wl.table_at); }
@@ -195,23 +194,25 @@ static int geometry_segmented(const int64_t *offsets, int32_t S, void *ws, size_
     if (!offsets || S < 0 || S > kMaxUnits) return S < 0 || !offsets ? GG_ERR_INVALID_ARG : GG_ERR_BAD_SEGMENTS;
     if (offsets[0] < 0) return GG_ERR_BAD_SEGMENTS;
     g.S = S;
-    g.off.assign(offsets, offsets + S + 1);
-    g.cpre.resize((size_t)S + 1);
+    const size_t n_off = (size_t)S + 1;
+    g.table.assign(n_off + (n_off + 1) / 2, 0);
+    memcpy(g.table.data(), offsets, n_off * sizeof(int64_t));
+    int32_t *cpre = reinterpret_cast<int32_t *>(g.table.data() + n_off);
     int64_t chunks = 0;
     for (int32_t s = 0; s < S; ++s) {
         if (offsets[s + 1] < offsets[s]) return GG_ERR_BAD_SEGMENTS;
-        g.cpre[s] = chunks;
+        cpre[s] = (int32_t)chunks;
         chunks += (offsets[s + 1] - offsets[s] + kChunk - 1) / kChunk;
         if (chunks > kMaxChunks) return GG_ERR_BAD_SEGMENTS;
     }
-    g.cpre[S] = chunks;
+    cpre[S] = (int32_t)chunks;
     g.n_chunks = chunks;
     g.n_total = offsets[S];   // elements of the buffer the units index into
     g.wl = ws_layout(g.n_total, S > 0 ? S : 1);
     if (!ws || ws_bytes < g.wl.total || !aligned16(ws)) return GG_ERR_WORKSPACE;
     g.ws = static_cast<char *>(ws);
     g.sv.off = reinterpret_cast<const int64_t *>(g.ws + g.wl.off_at);
-    g.sv.cpre = reinterpret_cast<const int64_t *>(g.ws + g.wl.cpre_at);
+    g.sv.cpre = reinterpret_cast<const int32_t *>(g.ws + g.wl.off_at + n_off * sizeof(int64_t));
     g.sv.cols = 0; g.sv.cpr = 1; g.sv.S = S;
     return GG_OK;
 }
@@ -231,9 +232,7 @@ static int upload_i64(const std::vector<int64_t> &v, int64_t *dst, hipStream_t s
 
 static int upload_geometry(const Geometry &g, hipStream_t st) {
     if (g.sv.off == nullptr) return GG_OK;
-    int rc = upload_i64(g.off, const_cast<int64_t *>(g.sv.off), st);
-    if (rc != GG_OK) return rc;
-    return upload_i64(g.cpre, const_cast<int64_t *>(g.sv.cpre), st);
+    return upload_i64(g.table, const_cast<int64_t *>(g.sv.off), st);   // offsets and chunk prefix in one go
 }
 
 template <typename F>

@@ -10,7 +10,7 @@
 //                     unit's quantiser / penalty parameters and clears its rate record
 //   k_quant           re-reads x: quantise, Map, Exp-Golomb bits, u_max, optional LDS-privatised
 //                     histogram, symbols, penalty gradient; integer atomics into the rate record
-//   k_rate_finalize   fixed-length bits, flags, histogram entropy in fp64
+//   k_rate_finalize   histogram entropy in fp64 (only when a histogram was asked for)
 // All reductions are order-fixed (floating point) or integer, so results are reproducible.
 
 #include <hip/hip_runtime.h>
@@ -281,8 +281,9 @@ __device__ __forceinline__ void prepare_unit(const PrepArgs &a, int seg, int64_t
     if (a.rate) {
         gg_rate_t r;
         r.eg_bits = 0; r.n = (uint64_t)n; r.n_clamped = 0; r.entropy_bits = 0.0;
-        r.u_max = 0; r.fl_bits = 0; r.delta = delta;
+        r.u_max = 0; r.delta = delta;
         r.flags = n == 0 ? GG_F_EMPTY : (ok ? 0u : GG_F_DEGENERATE);
+        r.fl_bits = (r.flags & GG_F_DEGENERATE) ? 0u : 1u;   // max(1, bit_length(u_max)); the sweep raises it
         a.rate[seg] = r;
     }
 }
@@ -597,8 +598,10 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
                     const uint64_t bits = (uint64_t)piece_elems * a.eg_const - 2ull * clz;
                     atomicAdd(reinterpret_cast<unsigned long long *>(&r->eg_bits), (unsigned long long)bits);
                     atomicMax(&r->u_max, um);
+                    if (um) atomicMax(&r->fl_bits, 32u - (uint32_t)__builtin_clz(um));   // bit length is monotone in u
                     if (ncl) atomicAdd(reinterpret_cast<unsigned long long *>(&r->n_clamped), (unsigned long long)ncl);
-                    if (nan) atomicOr(&r->flags, GG_F_NONFINITE);
+                    const uint32_t fl = (nan ? GG_F_NONFINITE : 0u) | (um >= 2147483647u ? GG_F_SATURATED : 0u);
+                    if (fl) atomicOr(&r->flags, fl);
                 }
                 if (want_hist && rate_live) {   // merge the block-private bins into the unit's histogram
                     uint64_t *g = a.hist + (int64_t)piece_seg * a.nbins;
@@ -1002,7 +1005,8 @@ static int run_second_sweep(const Geometry &g, const void *x, int dtype, QuantOp
     if (o.rate || o.pen) {
         if ((rc = launch_quant(g, x, dtype, o, st)) != GG_OK) return rc;
     }
-    if (o.rate) return launch_rate_finalize(g, o.rate_out, o.hist, o.nbins, st);
+    // without a histogram the sweep's integer atomics leave the rate records final; the entropy needs a pass over the bins
+    if (o.rate && o.hist) return launch_rate_finalize(g, o.rate_out, o.hist, o.nbins, st);
     return GG_OK;
 }
 
