@@ -257,6 +257,10 @@ static RunSplit split_runs(int64_t n_chunks, int blocks_per_cu) {
 // resident blocks of `kernel` per compute unit, capped at `cap` (a pure function of the code object)
 template <typename K>
 static int resident_blocks(K kernel, size_t dyn_lds, int cap) {
+#ifdef GG_RUNS_PER_CU   // tuning builds: a fixed number of runs per compute unit, resident or not
+    (void)kernel; (void)dyn_lds; (void)cap;
+    return GG_RUNS_PER_CU;
+#endif
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, dyn_lds) != hipSuccess || n < 1) n = 1;
     return n < cap ? n : cap;
