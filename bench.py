@@ -285,8 +285,23 @@ def main():
         t0 = time.perf_counter()
         ofits, orates = oracle.fused_segmented(host, off[:k + 1], delta_div=16.0)
         dt = time.perf_counter() - t0
+        # per-step cost of the oracle on a 16M-element slice (context for the individual rows of the pass)
+        sl = host[: min(m, 1 << 24)]
+        steps_ns = {}
+        t0 = time.perf_counter(); f0 = oracle.fit(sl); steps_ns["fit"] = (time.perf_counter() - t0) / sl.size * 1e9
+        t0 = time.perf_counter(); oracle.quantize_rate(sl, f0.alpha / 16.0); steps_ns["quantize_rate"] = (time.perf_counter() - t0) / sl.size * 1e9
+        t0 = time.perf_counter(); oracle.penalty_grad(sl, f0.alpha, f0.beta, 1e-4); steps_ns["penalty_grad"] = (time.perf_counter() - t0) / sl.size * 1e9
+        t0 = time.perf_counter(); oracle.sample(1 << 22, 0.02, 0.9, 1); steps_ns["sample"] = (time.perf_counter() - t0) / (1 << 22) * 1e9
+        cpu_model = ""
+        try:
+            with open("/proc/cpuinfo") as fh:
+                cpu_model = next((l.split(":", 1)[1].strip() for l in fh if l.startswith("model name")), "")
+        except OSError:
+            pass
         out["cpu_baseline"] = {"value": round(m / dt / 1e9, 4), "unit": "Gelem/s", "cores": 1, "kind": "oracle",
-                               "sample": "first %d segments (%d elements) of the same bucket, %.1f s" % (k, m, dt)}
+                               "sample": "first %d segments (%d elements) of the same bucket, %.1f s" % (k, m, dt),
+                               "ns_per_elem": {k_: round(v, 2) for k_, v in steps_ns.items()},
+                               "host": {"cpu": cpu_model, "nproc": os.cpu_count()}}
         # the sample doubles as a last sanity check of the timed configuration
         rrec = gg.rate_records(rate)
         for s in range(k):

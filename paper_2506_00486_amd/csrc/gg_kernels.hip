@@ -451,13 +451,48 @@ struct QuantBody {
     // per-lane accumulators
     uint32_t clz_sum = 0, u_max = 0, n_clamped = 0;
     bool nan_seen = false;
+    // MODE bit 0: 0 = floor, 1 = nearest-even.  MODE bit 1 (only with k = 0 and neither histogram nor
+    // symbols): the code length is read off the float exponent of |q| instead of the integer symbol:
+    //   q > 0: u + 1 = 2q;  q < 0: u + 1 = 2|q| + 1;  both have floor(log2(u + 1)) = 1 + floor(log2 |q|),
+    // and floor(log2 |q|) is the biased exponent of the integer-valued float |q| minus 127.  With 0.5
+    // standing in for q = 0 (exponent 126), len(u) = 2 floor(log2(u+1)) + 1 = 2 e - 251 for every element.
+    // u_max follows from the extremes of r = -q, since Map grows with |q| on either side of zero.
+    static constexpr bool kNearest = (MODE & 1) != 0;
+    static constexpr bool kExp0 = (MODE & 2) != 0;
+    static_assert(!kExp0 || (RATE && !EXTRA), "the exponent path serves the lean rate kernels only");
+    uint32_t exp_sum = 0;
+    float r_max = 0.f, r_min = 0.f;      // 0 is neutral: Map(0) = 0
+
+    __device__ __forceinline__ void quant_exp0(float x) {
+        const float t = x * inv_delta;                 // the one fp32 rounding of the quantiser
+        nan_seen |= (t != t);
+        const float r = kNearest ? rintf(-t) : ceilf(-t);                       // -q, not yet clamped; NaN stays NaN
+        const float a = __builtin_amdgcn_fmed3f(fabsf(r), 0.5f, 1073741824.0f);  // |q| in [1, 2^30], 0.5 for q = 0 and NaN
+        exp_sum += __float_as_uint(a) >> 23;
+        r_max = fmaxf(r_max, r);                       // NaN operands are ignored by v_max / v_min
+        r_min = fminf(r_min, r);
+    }
+
+    // largest symbol seen by this lane on the exponent path
+    __device__ __forceinline__ uint32_t exp0_u_max() const {
+        uint32_t best = 0;
+        const float ends[2] = {r_max, r_min};
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            int32_t m = cvt_i32_sat(ends[e]);
+            m = m < -kQLimI ? -kQLimI : (m > kQLimI ? kQLimI : m);
+            const uint32_t u = ((uint32_t)m << 1) ^ (uint32_t)(m >> 31);
+            best = u > best ? u : best;
+        }
+        return best;
+    }
 
     __device__ __forceinline__ int32_t quant(float x) {
         const float t = x * inv_delta;                 // the one fp32 rounding of the quantiser
         nan_seen |= (t != t);
         // m = -q: floor(t) = -ceil(-t), rint is odd-symmetric.  The conversion maps NaN to 0 and
         // saturates, so clamping the integer to +-2^30 equals clamping t before rounding.
-        const float r = MODE == GG_FLOOR ? ceilf(-t) : rintf(-t);
+        const float r = kNearest ? rintf(-t) : ceilf(-t);
         int32_t m = cvt_i32_sat(r);
         m = m < -kQLimI ? -kQLimI : (m > kQLimI ? kQLimI : m);
         // Map(q) = q > 0 ? 2q-1 : -2q  is the zig-zag code of m = -q
@@ -492,7 +527,10 @@ struct QuantBody {
                 s2[j & 3] = __builtin_fmaf(v[j], v[j], s2[j & 3]);
             }
         }
-        if constexpr (RATE) {
+        if constexpr (RATE && kExp0) {
+#pragma unroll
+            for (int j = 0; j < W; ++j) quant_exp0(v[j]);
+        } else if constexpr (RATE) {
             int32_t q[W];
 #pragma unroll
             for (int j = 0; j < W; ++j) q[j] = quant(v[j]);
@@ -522,7 +560,9 @@ struct QuantBody {
             s1[0] += fabsf(v);
             s2[0] = __builtin_fmaf(v, v, s2[0]);
         }
-        if constexpr (RATE) {
+        if constexpr (RATE && kExp0) {
+            quant_exp0(v);
+        } else if constexpr (RATE) {
             const int32_t q = quant(v);
             if constexpr (EXTRA) { if (symbols) symbols[idx] = q; }
         }
@@ -588,14 +628,17 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
         }
         if constexpr (RATE) {
             if (piece_seg >= 0) {
-                const uint64_t clz = block_reduce((uint64_t)body.clz_sum, OpAdd(), red64);
-                const uint32_t um = block_reduce(body.u_max, OpMax(), red[0]);
+                constexpr bool kExp0 = decltype(body)::kExp0;
+                const uint64_t lsum = block_reduce((uint64_t)(kExp0 ? body.exp_sum : body.clz_sum), OpAdd(), red64);
+                const uint32_t um = block_reduce(kExp0 ? body.exp0_u_max() : body.u_max, OpMax(), red[0]);
                 const uint32_t nan = block_reduce((uint32_t)body.nan_seen, OpOr(), red[1]);
                 uint32_t ncl = 0;
                 if constexpr (EXTRA) ncl = block_reduce(body.n_clamped, OpAdd(), red[2]);
                 if (tid == 0 && rate_live) {
                     gg_rate_t *r = a.rate + piece_seg;
-                    const uint64_t bits = (uint64_t)piece_elems * a.eg_const - 2ull * clz;
+                    // sum of 63-k-2 clz(u+2^k), or with k = 0 on the exponent path of 2e-251
+                    const uint64_t bits = kExp0 ? 2ull * lsum - 251ull * (uint64_t)piece_elems
+                                                : (uint64_t)piece_elems * a.eg_const - 2ull * lsum;
                     atomicAdd(reinterpret_cast<unsigned long long *>(&r->eg_bits), (unsigned long long)bits);
                     atomicMax(&r->u_max, um);
                     if (um) atomicMax(&r->fl_bits, 32u - (uint32_t)__builtin_clz(um));   // bit length is monotone in u
@@ -619,6 +662,7 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
             }
         }
         body.clz_sum = 0; body.u_max = 0; body.n_clamped = 0; body.nan_seen = false;
+        body.exp_sum = 0; body.r_max = 0.f; body.r_min = 0.f;
         piece_elems = 0; piece_chunks = 0;
     };
 
@@ -712,14 +756,15 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
             else
                 process_chunk<Elem<T>, 4, decltype(body), 64>(x, start, len, body);
             if constexpr (RATE) {
-                const uint64_t clz = wave_reduce((uint64_t)body.clz_sum, OpAdd());
-                const uint32_t um = wave_reduce(body.u_max, OpMax());
+                constexpr bool kExp0 = decltype(body)::kExp0;
+                const uint64_t lsum = wave_reduce((uint64_t)(kExp0 ? body.exp_sum : body.clz_sum), OpAdd());
+                const uint32_t um = wave_reduce(kExp0 ? body.exp0_u_max() : body.u_max, OpMax());
                 const uint32_t nan = wave_reduce((uint32_t)body.nan_seen, OpOr());
                 if (lane == 0) {
                     gg_rate_t r;
                     r.n = (uint64_t)len; r.n_clamped = 0; r.entropy_bits = 0.0; r.delta = delta;
                     if (ok) {
-                        r.eg_bits = (uint64_t)len * a.eg_const - 2ull * clz;
+                        r.eg_bits = kExp0 ? 2ull * lsum - 251ull * (uint64_t)len : (uint64_t)len * a.eg_const - 2ull * lsum;
                         r.u_max = um;
                         r.fl_bits = um ? 32u - (uint32_t)__builtin_clz(um) : 1u;
                         r.flags = (nan ? GG_F_NONFINITE : 0u) | (um >= 2147483647u ? GG_F_SATURATED : 0u);
@@ -913,14 +958,20 @@ static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hip
 template <typename T, int MODE>
 static int launch_quant_mode(const Geometry &g, const void *x, QuantOpts &o, hipStream_t st) {
     const bool extra = o.hist || o.symbols;
-    if (o.fit_too && o.rate && !o.pen)
-        return extra ? launch_quant_inst<T, MODE, true, false, true, true>(g, x, o, st)
-                     : launch_quant_inst<T, MODE, true, false, false, true>(g, x, o, st);
-    if (o.rate && !o.pen && !extra) return launch_quant_inst<T, MODE, true, false, false>(g, x, o, st);
-    if (o.rate && o.pen && !extra) return launch_quant_inst<T, MODE, true, true, false>(g, x, o, st);
-    if (o.rate && !o.pen && extra) return launch_quant_inst<T, MODE, true, false, true>(g, x, o, st);
-    if (o.rate && o.pen && extra) return launch_quant_inst<T, MODE, true, true, true>(g, x, o, st);
-    return GG_ERR_INVALID_ARG;
+    if constexpr ((MODE & 2) != 0) {   // exponent path: lean kernels only
+        if (o.fit_too && !o.pen) return launch_quant_inst<T, MODE, true, false, false, true>(g, x, o, st);
+        if (!o.pen) return launch_quant_inst<T, MODE, true, false, false>(g, x, o, st);
+        return launch_quant_inst<T, MODE, true, true, false>(g, x, o, st);
+    } else {
+        if (o.fit_too && o.rate && !o.pen)
+            return extra ? launch_quant_inst<T, MODE, true, false, true, true>(g, x, o, st)
+                         : launch_quant_inst<T, MODE, true, false, false, true>(g, x, o, st);
+        if (o.rate && !o.pen && !extra) return launch_quant_inst<T, MODE, true, false, false>(g, x, o, st);
+        if (o.rate && o.pen && !extra) return launch_quant_inst<T, MODE, true, true, false>(g, x, o, st);
+        if (o.rate && !o.pen && extra) return launch_quant_inst<T, MODE, true, false, true>(g, x, o, st);
+        if (o.rate && o.pen && extra) return launch_quant_inst<T, MODE, true, true, true>(g, x, o, st);
+        return GG_ERR_INVALID_ARG;
+    }
 }
 
 static int launch_quant(const Geometry &g, const void *x, int dtype, QuantOpts &o, hipStream_t st) {
@@ -928,8 +979,10 @@ static int launch_quant(const Geometry &g, const void *x, int dtype, QuantOpts &
     return by_dtype(dtype, [&](auto *tag) {
         using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
         if (!o.rate) return launch_quant_inst<T, GG_FLOOR, false, true, false>(g, x, o, st);
-        if (o.round_mode == GG_FLOOR) return launch_quant_mode<T, GG_FLOOR>(g, x, o, st);
-        return launch_quant_mode<T, GG_NEAREST_EVEN>(g, x, o, st);
+        // kernel MODE: bit 0 = rounding, bit 1 = exponent-based lengths (k = 0, no histogram, no symbols)
+        const bool exp0 = o.eg_k == 0 && !o.hist && !o.symbols;
+        if (o.round_mode == GG_FLOOR) return exp0 ? launch_quant_mode<T, 2>(g, x, o, st) : launch_quant_mode<T, 0>(g, x, o, st);
+        return exp0 ? launch_quant_mode<T, 3>(g, x, o, st) : launch_quant_mode<T, 1>(g, x, o, st);
     });
 }
 
@@ -960,11 +1013,15 @@ static int launch_rows_inst(const void *x, const RowsArgs &a, hipStream_t st) {
 
 template <typename T, int MODE>
 static int launch_rows_mode(const void *x, const RowsArgs &a, bool rate, bool pen, bool extra, hipStream_t st) {
-    if (rate && !pen && !extra) return launch_rows_inst<T, MODE, true, false, false>(x, a, st);
-    if (rate && pen && !extra) return launch_rows_inst<T, MODE, true, true, false>(x, a, st);
-    if (rate && !pen && extra) return launch_rows_inst<T, MODE, true, false, true>(x, a, st);
-    if (rate && pen && extra) return launch_rows_inst<T, MODE, true, true, true>(x, a, st);
-    return GG_ERR_INVALID_ARG;
+    if constexpr ((MODE & 2) != 0) {
+        return pen ? launch_rows_inst<T, MODE, true, true, false>(x, a, st) : launch_rows_inst<T, MODE, true, false, false>(x, a, st);
+    } else {
+        if (rate && !pen && !extra) return launch_rows_inst<T, MODE, true, false, false>(x, a, st);
+        if (rate && pen && !extra) return launch_rows_inst<T, MODE, true, true, false>(x, a, st);
+        if (rate && !pen && extra) return launch_rows_inst<T, MODE, true, false, true>(x, a, st);
+        if (rate && pen && extra) return launch_rows_inst<T, MODE, true, true, true>(x, a, st);
+        return GG_ERR_INVALID_ARG;
+    }
 }
 
 static bool rows_take_wave_path(int64_t rows, int64_t cols) { return rows > 0 && cols > 0 && cols <= kRowWaveMax; }
@@ -982,8 +1039,10 @@ static int launch_rows(const Geometry &g, const void *x, int dtype, RowsArgs a, 
         using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
         if (!rate && !pen) return launch_rows_inst<T, GG_FLOOR, false, false, false>(x, a, st);
         if (!rate) return launch_rows_inst<T, GG_FLOOR, false, true, false>(x, a, st);
-        if (round_mode == GG_FLOOR) return launch_rows_mode<T, GG_FLOOR>(x, a, rate, pen, extra, st);
-        return launch_rows_mode<T, GG_NEAREST_EVEN>(x, a, rate, pen, extra, st);
+        const bool exp0 = eg_k == 0 && !extra;
+        if (round_mode == GG_FLOOR)
+            return exp0 ? launch_rows_mode<T, 2>(x, a, rate, pen, extra, st) : launch_rows_mode<T, 0>(x, a, rate, pen, extra, st);
+        return exp0 ? launch_rows_mode<T, 3>(x, a, rate, pen, extra, st) : launch_rows_mode<T, 1>(x, a, rate, pen, extra, st);
     });
 }
 

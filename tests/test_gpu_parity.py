@@ -139,6 +139,32 @@ def test_quantize_special_values(gg):
             assert np.array_equal(sym.cpu().numpy(), osym), (delta, mode)
             check_rate(gg.rate_records(out)[0], r, f"delta={delta} mode={mode}")
             assert np.array_equal(hist.cpu().numpy().view(np.uint64), ohist)
+            # the lean kernels (k = 0, no histogram, no symbols) take the code length from the float exponent
+            out0, _, _ = gg.gg_quantize_rate(x, delta, ws, eg_k=0, round_mode=mode)
+            r0, _, _ = oracle.quantize_rate(host_bits(x), delta, eg_k=0, round_mode=mode)
+            check_rate(gg.rate_records(out0)[0], r0, f"lean delta={delta} mode={mode}", entropy=False)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_lean_rate_kernel_matches_integer_path(gg, dtype, mode):
+    """k = 0 without histogram/symbols uses exponent-derived lengths; every power-of-two boundary of |q| and
+    both signs must give the same bit count and u_max as the integer path and the oracle."""
+    edges = []
+    for e in range(0, 31):
+        for d in (-1.0, -0.5, 0.0, 0.5, 1.0):
+            edges += [2.0 ** e + d, -(2.0 ** e) + d]
+    base = torch.tensor(edges, dtype=torch.float32, device=DEV).to(dtype)
+    rnd = make(200_000, 40.0, 0.6, seed=31, dtype=dtype)             # symbols spread over ~2^20
+    x = torch.cat([base, rnd, torch.zeros(777, device=DEV, dtype=dtype), base * 0.001]).contiguous()
+    ws = gg.Workspace(x.numel(), 1)
+    for delta in (1.0, 0.37, 2.0 ** -9):
+        lean, _, _ = gg.gg_quantize_rate(x, delta, ws, eg_k=0, round_mode=mode)
+        full, _, _ = gg.gg_quantize_rate(x, delta, ws, eg_k=0, round_mode=mode, want_symbols=True)
+        a, b = gg.rate_records(lean)[0], gg.rate_records(full)[0]
+        r, _, _ = oracle.quantize_rate(host_bits(x), delta, eg_k=0, round_mode=mode)
+        check_rate(a, r, f"lean delta={delta}", entropy=False)
+        check_rate(b, r, f"full delta={delta}", entropy=False)
 
 
 def test_histogram_beyond_lds_bins_and_overflow_bin(gg):
