@@ -101,7 +101,7 @@ int gg_workspace_bytes(int64_t n_total, int32_t n_units, int32_t nbins, size_t *
 int gg_fit(const void *x_dev, int dtype, int64_t n, gg_fit_t *out_dev,
            void *ws_dev, size_t ws_bytes, void *stream);
 /* Flat bucket: unit s is x[offsets_host[s] .. offsets_host[s+1]) (element offsets, S+1 entries,
- * non-decreasing, offsets_host[0] >= 0; zero-length units are legal).  -> out_dev[S]. */
+ * non-decreasing, offsets_host[0] >= 0; zero-length units are legal; S <= 2^20).  -> out_dev[S]. */
 int gg_fit_segmented(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S,
                      gg_fit_t *out_dev, void *ws_dev, size_t ws_bytes, void *stream);
 /* Row-major rows x cols matrix: one fit per row -> out_dev[rows]; if total_out_dev is not NULL it

@@ -156,7 +156,8 @@ static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline bool aligned8(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; }
 
-constexpr int64_t kMaxUnits = 1 << 24;
+constexpr int64_t kMaxUnits = 1 << 24;      // rows of a matrix
+constexpr int64_t kMaxSegments = 1 << 20;   // units of a flat bucket
 constexpr int64_t kMaxChunks = 2147483647LL;
 
 // A validated description of how a buffer is cut into units, plus where its tables live.
@@ -191,7 +192,8 @@ static int geometry_uniform(int64_t rows, int64_t cols, void *ws, size_t ws_byte
 }
 
 static int geometry_segmented(const int64_t *offsets, int32_t S, void *ws, size_t ws_bytes, Geometry &g) {
-    if (!offsets || S < 0 || S > kMaxUnits) return S < 0 || !offsets ? GG_ERR_INVALID_ARG : GG_ERR_BAD_SEGMENTS;
+    // the unit table travels through kernel arguments (448 words per launch): keep it to a few thousand launches
+    if (!offsets || S < 0 || S > kMaxSegments) return S < 0 || !offsets ? GG_ERR_INVALID_ARG : GG_ERR_BAD_SEGMENTS;
     if (offsets[0] < 0) return GG_ERR_BAD_SEGMENTS;
     g.S = S;
     const size_t n_off = (size_t)S + 1;

@@ -79,6 +79,7 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.gg_fit_segmented(P, 0, None, 3, P, P, ws_bytes, None) == -1
     neg = np.array([-1, 10], dtype=np.int64)
     assert L.gg_fit_segmented(P, 0, neg.ctypes.data, 1, P, P, ws_bytes, None) == -3
+    assert L.gg_fit_segmented(P, 0, ok_off.ctypes.data, (1 << 20) + 1, P, P, ws_bytes, None) == -3   # too many units
     assert L.gg_fit_rows(P, 0, -1, 10, P, None, P, ws_bytes, None) == -1
     for delta in (0.0, -1.0, float("inf"), float("nan")):
         assert L.gg_quantize_rate(P, 0, 100, delta, 0, 0, 0, None, None, P, P, ws_bytes, None) == -1
