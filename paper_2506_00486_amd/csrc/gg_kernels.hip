@@ -459,7 +459,7 @@ struct QuantBody {
     // u_max follows from the extremes of r = -q, since Map grows with |q| on either side of zero.
     static constexpr bool kNearest = (MODE & 1) != 0;
     static constexpr bool kExp0 = (MODE & 2) != 0;
-    static_assert(!kExp0 || (RATE && !EXTRA), "the exponent path serves the lean rate kernels only");
+    static_assert(!kExp0 || (RATE && !EXTRA && !PEN), "the exponent path serves the lean rate-only kernels");
     uint32_t exp_sum = 0;
     float r_max = 0.f, r_min = 0.f;      // 0 is neutral: Map(0) = 0
 
@@ -958,10 +958,9 @@ static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hip
 template <typename T, int MODE>
 static int launch_quant_mode(const Geometry &g, const void *x, QuantOpts &o, hipStream_t st) {
     const bool extra = o.hist || o.symbols;
-    if constexpr ((MODE & 2) != 0) {   // exponent path: lean kernels only
-        if (o.fit_too && !o.pen) return launch_quant_inst<T, MODE, true, false, false, true>(g, x, o, st);
-        if (!o.pen) return launch_quant_inst<T, MODE, true, false, false>(g, x, o, st);
-        return launch_quant_inst<T, MODE, true, true, false>(g, x, o, st);
+    if constexpr ((MODE & 2) != 0) {   // exponent path: the lean rate-only kernels
+        if (o.fit_too) return launch_quant_inst<T, MODE, true, false, false, true>(g, x, o, st);
+        return launch_quant_inst<T, MODE, true, false, false>(g, x, o, st);
     } else {
         if (o.fit_too && o.rate && !o.pen)
             return extra ? launch_quant_inst<T, MODE, true, false, true, true>(g, x, o, st)
@@ -980,7 +979,7 @@ static int launch_quant(const Geometry &g, const void *x, int dtype, QuantOpts &
         using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
         if (!o.rate) return launch_quant_inst<T, GG_FLOOR, false, true, false>(g, x, o, st);
         // kernel MODE: bit 0 = rounding, bit 1 = exponent-based lengths (k = 0, no histogram, no symbols)
-        const bool exp0 = o.eg_k == 0 && !o.hist && !o.symbols;
+        const bool exp0 = o.eg_k == 0 && !o.hist && !o.symbols && !o.pen;
         if (o.round_mode == GG_FLOOR) return exp0 ? launch_quant_mode<T, 2>(g, x, o, st) : launch_quant_mode<T, 0>(g, x, o, st);
         return exp0 ? launch_quant_mode<T, 3>(g, x, o, st) : launch_quant_mode<T, 1>(g, x, o, st);
     });
@@ -1014,7 +1013,7 @@ static int launch_rows_inst(const void *x, const RowsArgs &a, hipStream_t st) {
 template <typename T, int MODE>
 static int launch_rows_mode(const void *x, const RowsArgs &a, bool rate, bool pen, bool extra, hipStream_t st) {
     if constexpr ((MODE & 2) != 0) {
-        return pen ? launch_rows_inst<T, MODE, true, true, false>(x, a, st) : launch_rows_inst<T, MODE, true, false, false>(x, a, st);
+        return launch_rows_inst<T, MODE, true, false, false>(x, a, st);
     } else {
         if (rate && !pen && !extra) return launch_rows_inst<T, MODE, true, false, false>(x, a, st);
         if (rate && pen && !extra) return launch_rows_inst<T, MODE, true, true, false>(x, a, st);
@@ -1039,7 +1038,7 @@ static int launch_rows(const Geometry &g, const void *x, int dtype, RowsArgs a, 
         using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
         if (!rate && !pen) return launch_rows_inst<T, GG_FLOOR, false, false, false>(x, a, st);
         if (!rate) return launch_rows_inst<T, GG_FLOOR, false, true, false>(x, a, st);
-        const bool exp0 = eg_k == 0 && !extra;
+        const bool exp0 = eg_k == 0 && !extra && !pen;
         if (round_mode == GG_FLOOR)
             return exp0 ? launch_rows_mode<T, 2>(x, a, rate, pen, extra, st) : launch_rows_mode<T, 0>(x, a, rate, pen, extra, st);
         return exp0 ? launch_rows_mode<T, 3>(x, a, rate, pen, extra, st) : launch_rows_mode<T, 1>(x, a, rate, pen, extra, st);
