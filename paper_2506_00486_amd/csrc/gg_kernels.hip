@@ -31,7 +31,7 @@
 #define GG_U_FIT 8
 #endif
 #ifndef GG_U_QUANT
-#define GG_U_QUANT 8
+#define GG_U_QUANT 4
 #endif
 
 namespace gg {
@@ -683,7 +683,7 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
         if constexpr (sizeof(T) == 2 && (PEN || EXTRA))
             process_chunk<ElemBf16x4, 8>(x, cur.L.start, cur.L.len, body);
         else
-            process_chunk<Elem<T>, (sizeof(T) == 2 ? GG_U_QUANT / 2 : GG_U_QUANT)>(x, cur.L.start, cur.L.len, body);
+            process_chunk<Elem<T>, GG_U_QUANT>(x, cur.L.start, cur.L.len, body);
         if constexpr (FIT) {   // per chunk: <= 16-term fp32 lane sums into the fp64 lane totals
             d1 += ((double)body.s1[0] + (double)body.s1[1]) + ((double)body.s1[2] + (double)body.s1[3]);
             d2 += ((double)body.s2[0] + (double)body.s2[1]) + ((double)body.s2[2] + (double)body.s2[3]);
@@ -979,7 +979,11 @@ static int launch_quant(const Geometry &g, const void *x, int dtype, QuantOpts &
         using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
         if (!o.rate) return launch_quant_inst<T, GG_FLOOR, false, true, false>(g, x, o, st);
         // kernel MODE: bit 0 = rounding, bit 1 = exponent-based lengths (k = 0, no histogram, no symbols)
+#ifdef GG_NO_EXP0   // tuning builds
+        const bool exp0 = false;
+#else
         const bool exp0 = o.eg_k == 0 && !o.hist && !o.symbols && !o.pen;
+#endif
         if (o.round_mode == GG_FLOOR) return exp0 ? launch_quant_mode<T, 2>(g, x, o, st) : launch_quant_mode<T, 0>(g, x, o, st);
         return exp0 ? launch_quant_mode<T, 3>(g, x, o, st) : launch_quant_mode<T, 1>(g, x, o, st);
     });
