@@ -449,7 +449,7 @@ struct QuantBody {
     int32_t *symbols; float *grad; int accumulate;
     uint32_t *lds_hist; uint64_t *ghist; uint32_t last_bin, lbins;
     // per-lane accumulators
-    uint32_t clz_sum = 0, u_max = 0, n_clamped = 0;
+    uint32_t clz_sum = 0, u_max = 0, n_clamped = 0, n_last = 0;
     bool nan_seen = false;
     // MODE bit 0: 0 = floor, 1 = nearest-even.  MODE bit 1 (only with k = 0 and neither histogram nor
     // symbols): the code length is read off the float exponent of |q| instead of the integer symbol:
@@ -503,7 +503,11 @@ struct QuantBody {
             if (hist_live) {
                 const uint32_t bin = u < last_bin ? u : last_bin;
                 n_clamped += u > last_bin ? 1u : 0u;
+                // Symbols past the block-private bins go straight to the unit's histogram, except the
+                // last bin: it collects every clamped symbol, and atomics of many blocks on that one
+                // address serialise, so each lane counts its hits and the block adds them once.
                 if (bin < lbins) atomicAdd(&lds_hist[bin], 1u);
+                else if (bin == last_bin) n_last += 1u;
                 else atomicAdd(reinterpret_cast<unsigned long long *>(&ghist[bin]), 1ull);
             }
         }
@@ -582,7 +586,7 @@ template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA, bool FIT = fals
 __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restrict__ x, QuantArgs a) {
     extern __shared__ uint32_t lds_hist[];
     __shared__ uint64_t red64[kWaves];
-    __shared__ uint32_t red[3][kWaves];
+    __shared__ uint32_t red[4][kWaves];
     __shared__ double redd[2][kWaves];
     const int tid = threadIdx.x;
     const int64_t first = (int64_t)blockIdx.x * a.chunks_per_block;
@@ -632,8 +636,11 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
                 const uint64_t lsum = block_reduce((uint64_t)(kExp0 ? body.exp_sum : body.clz_sum), OpAdd(), red64);
                 const uint32_t um = block_reduce(kExp0 ? body.exp0_u_max() : body.u_max, OpMax(), red[0]);
                 const uint32_t nan = block_reduce((uint32_t)body.nan_seen, OpOr(), red[1]);
-                uint32_t ncl = 0;
-                if constexpr (EXTRA) ncl = block_reduce(body.n_clamped, OpAdd(), red[2]);
+                uint32_t ncl = 0, nlast = 0;
+                if constexpr (EXTRA) {
+                    ncl = block_reduce(body.n_clamped, OpAdd(), red[2]);
+                    nlast = block_reduce(body.n_last, OpAdd(), red[3]);
+                }
                 if (tid == 0 && rate_live) {
                     gg_rate_t *r = a.rate + piece_seg;
                     // sum of 63-k-2 clz(u+2^k), or with k = 0 on the exponent path of 2e-251
@@ -643,6 +650,7 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
                     atomicMax(&r->u_max, um);
                     if (um) atomicMax(&r->fl_bits, 32u - (uint32_t)__builtin_clz(um));   // bit length is monotone in u
                     if (ncl) atomicAdd(reinterpret_cast<unsigned long long *>(&r->n_clamped), (unsigned long long)ncl);
+                    if (nlast) atomicAdd(reinterpret_cast<unsigned long long *>(&body.ghist[body.last_bin]), (unsigned long long)nlast);
                     const uint32_t fl = (nan ? GG_F_NONFINITE : 0u) | (um >= 2147483647u ? GG_F_SATURATED : 0u);
                     if (fl) atomicOr(&r->flags, fl);
                 }
@@ -661,7 +669,7 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
                 }
             }
         }
-        body.clz_sum = 0; body.u_max = 0; body.n_clamped = 0; body.nan_seen = false;
+        body.clz_sum = 0; body.u_max = 0; body.n_clamped = 0; body.n_last = 0; body.nan_seen = false;
         body.exp_sum = 0; body.r_max = 0.f; body.r_min = 0.f;
         piece_elems = 0; piece_chunks = 0;
     };
@@ -932,7 +940,10 @@ struct QuantOpts {
     int32_t chunks_per_block_out = 1;  // the run length the sweep used (the fit finalisation needs it)
 };
 
-constexpr int kMaxLdsBins = 12288;   // 48 KiB of block-private bins; higher symbols go to L2 atomics
+#ifndef GG_LDS_BINS
+#define GG_LDS_BINS 12288
+#endif
+constexpr int kMaxLdsBins = GG_LDS_BINS;   // block-private bins (4 bytes each); higher symbols go to L2 atomics
 
 template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA, bool FIT = false>
 static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hipStream_t st) {

@@ -172,7 +172,8 @@ def test_histogram_beyond_lds_bins_and_overflow_bin(gg):
     x = gg_inputs.make_tensor((300_000,), 0.5, 0.8, seed=2, device=DEV, dtype=torch.bfloat16, outlier_frac=1e-3,
                               outlier_scale=20.0)
     ws = gg.Workspace(x.numel(), 1)
-    for nbins, div in ((32768, 64), (65536, 512), (1000, 8), (2, 8)):
+    # 12288 block-private bins: the clamping bin sits just inside, on and beyond that boundary
+    for nbins, div in ((32768, 64), (65536, 512), (20000, 512), (12289, 512), (12288, 512), (1000, 8), (2, 8)):
         delta = float(np.float32(0.5) / np.float32(div))
         out, hist, _ = gg.gg_quantize_rate(x, delta, ws, nbins=nbins)
         r, ohist, _ = oracle.quantize_rate(host_bits(x), delta, nbins=nbins)
