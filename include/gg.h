@@ -205,10 +205,16 @@ int gg_gct_update_segmented(float *w_dev, const float *g_dev, float *ghat_prev_d
 /* Order-k Exp-Golomb bit stream of quantised symbols q (as written by the rate sweep): symbol i is
  * (L-1-k) zero bits followed by the L bits of Map(q_i) + 2^k, most significant bit first, bytes filled from
  * their most significant bit.  The stream's length in bits equals gg_rate_t.eg_bits of the same symbols.
- * stream_dev: stream_bytes (a multiple of 4, 4-byte aligned) are cleared and filled; if the stream does not
- * fit, blocks that would overflow are left out (compare *total_bits_dev with 8*stream_bytes).
- * block_offsets_dev: gg_eg_workspace_bytes(n) bytes; on return entry b is the bit offset of symbol 2048*b
- * (an index for parallel decoding), the last entry the total.  total_bits_dev may be NULL. */
+ * symbols_dev: n int32, 16-byte aligned.  stream_dev: room for stream_bytes (a multiple of 4, 4-byte
+ * aligned); the 32-bit words up to the one holding the last bit are written (that one zero-padded), bytes
+ * beyond it are left as they were.  If the stream does not fit, tiles that would overflow are left out
+ * (compare *total_bits_dev with 8*stream_bytes).
+ * block_offsets_dev: gg_eg_workspace_bytes(n) bytes, 8-byte aligned; on return its first T + 1 entries,
+ * T = ceil(n / GG_EG_TILE), are the index for parallel decoding: entry b is the bit offset of symbol
+ * GG_EG_TILE*b, entry T the total (the rest of the buffer is scratch).  total_bits_dev may be NULL.
+ * gg_eg_decode takes those T + 1 entries; it reads only words that hold bits of the indexed tiles, whatever
+ * the stream contains; symbols_dev (out) 16-byte aligned. */
+#define GG_EG_TILE 256
 int gg_eg_workspace_bytes(int64_t n, size_t *bytes_out_host);
 int gg_eg_encode(const int32_t *symbols_dev, int64_t n, int eg_k, uint8_t *stream_dev, uint64_t stream_bytes,
                  uint64_t *block_offsets_dev, uint64_t *total_bits_dev, void *stream);

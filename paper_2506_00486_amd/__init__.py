@@ -5,7 +5,7 @@ PyTorch supplies device memory and streams.  There is no CPU fallback: if the co
 is missing, importing `binding` symbols raises.
 """
 from .binding import (  # noqa: F401
-    GG_F32, GG_BF16, GG_FLOOR, GG_NEAREST_EVEN,
+    GG_F32, GG_BF16, GG_FLOOR, GG_NEAREST_EVEN, GG_EG_TILE,
     GG_F_EMPTY, GG_F_DEGENERATE, GG_F_BETA_CLAMPED_LO, GG_F_BETA_CLAMPED_HI, GG_F_NONFINITE, GG_F_SATURATED,
     FIT_DTYPE, RATE_DTYPE, GGError, lib, lib_path, workspace_bytes, Workspace,
     gg_fit, gg_fit_segmented, gg_fit_rows, gg_quantize_rate, gg_quantize_rate_segmented, gg_quantize_rate_rows,

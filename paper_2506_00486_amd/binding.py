@@ -15,6 +15,7 @@ import torch
 
 GG_F32, GG_BF16 = 0, 1
 GG_FLOOR, GG_NEAREST_EVEN = 0, 1
+GG_EG_TILE = 256            # symbols per entry of the decoding index (GG_EG_TILE in gg.h)
 GG_F_EMPTY, GG_F_DEGENERATE, GG_F_BETA_CLAMPED_LO, GG_F_BETA_CLAMPED_HI, GG_F_NONFINITE, GG_F_SATURATED = \
     1, 2, 4, 8, 16, 32
 
@@ -338,7 +339,8 @@ def gg_eg_encode(symbols: torch.Tensor, eg_k: int = 0, capacity_bytes: Optional[
     total = torch.zeros(1, dtype=torch.int64, device=symbols.device)
     _check(lib().gg_eg_encode(_dev(symbols), n, eg_k, _dev(stream), cap, _dev(index), _dev(total), _stream()),
            "gg_eg_encode")
-    return stream, index, int(total.item())
+    tiles = (n + GG_EG_TILE - 1) // GG_EG_TILE
+    return stream, index[: tiles + 1], int(total.item())
 
 
 def gg_eg_decode(stream: torch.Tensor, index: torch.Tensor, n: int, eg_k: int = 0) -> torch.Tensor:

@@ -167,139 +167,375 @@ __global__ void k_unit_coef(SegView sv, const float *__restrict__ delta_dev, flo
 // ---------------------------------------------------------------------------------------------
 // Exp-Golomb-k bit stream.  Symbol i contributes (L_i - 1 - k) zero bits and then the L_i bits of
 // v_i = u_i + 2^k, most significant bit first; bytes are filled from their most significant bit.
-// Blocks of kEgBlock symbols: (1) bits per block, (2) exclusive scan, (3) each block assembles its
-// span in LDS with bit-wise ORs and copies whole 32-bit words out; the two words a span shares with
-// its neighbours are OR-ed into the (pre-cleared) stream atomically.
+// Packing tiles of kEgBlock symbols; the decoding index has one entry per GG_EG_TILE symbols:
+//   (1) bits per tile (one wave per tile),
+//   (2) exclusive scan of the tile sizes,
+//   (3) each tile's span is assembled in LDS with bit-wise ORs and copied out as whole 32-bit words.  Every
+//       stream word has one writer: a word shared by two tiles of one workgroup is carried from the first
+//       to the second in LDS; a word shared by two workgroups is written by the earlier one, which packs
+//       the first symbols of the later one's tile into it as well.
 // ---------------------------------------------------------------------------------------------
-constexpr int kEgBlock = 2048;                      // symbols per block (8 per lane)
+constexpr int kEgBlock = 2048;                      // symbols per packing tile (8 per lane in the packing kernel)
 constexpr int kEgPerLane = kEgBlock / kBlock;
+constexpr int kEgSubTiles = kEgBlock / GG_EG_TILE;  // index entries per packing tile
+constexpr int kEgSubLanes = kBlock / kEgSubTiles;   // lanes of the packing kernel per index entry
+static_assert(kEgSubTiles * GG_EG_TILE == kEgBlock && kEgSubLanes * kEgPerLane == GG_EG_TILE, "index entries fall on lane boundaries");
 constexpr int kEgLdsWords = kEgBlock * 2 + 2;       // <= 63 bits per symbol, plus the alignment slack
+constexpr int kEgTilesPerBlock = 4;                 // consecutive tiles one workgroup packs, loads of the next in flight
+static_assert(kEgPerLane == 8, "two 16-byte loads per lane and tile");
 
 __device__ __forceinline__ uint32_t map_q(int32_t q) {
     const int32_t m = -q;
     return ((uint32_t)m << 1) ^ (uint32_t)(m >> 31);
 }
 
-__global__ __launch_bounds__(kBlock) void k_eg_block_bits(const int32_t *__restrict__ q, int64_t n, int eg_k,
-                                                          uint64_t *__restrict__ block_bits) {
-    __shared__ uint32_t red[kWaves];
-    const int64_t base = (int64_t)blockIdx.x * kEgBlock;
+__device__ __forceinline__ uint32_t eg_len(uint32_t v, int eg_k) {   // v = u + 2^k
+    return 63u - (uint32_t)eg_k - 2u * (uint32_t)__builtin_clz(v);
+}
+
+// one wave per tile: 8 x 16 bytes per lane in flight
+__global__ __launch_bounds__(kBlock) void k_eg_tile_bits(const int32_t *__restrict__ q, int64_t n, int64_t nb, int eg_k,
+                                                         uint64_t *__restrict__ tile_bits) {
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (tile >= nb) return;
+    const int64_t base = tile * kEgBlock;
+    const uint32_t add = 1u << eg_k;
     uint32_t bits = 0;
+    if (base + kEgBlock <= n) {
+        const gg_i4 *src = reinterpret_cast<const gg_i4 *>(q + base);
+        gg_i4 v[8];
 #pragma unroll
-    for (int j = 0; j < kEgPerLane; ++j) {
-        const int64_t i = base + j * kBlock + threadIdx.x;
-        if (i < n) {
-            const uint32_t v = map_q(q[i]) + (1u << eg_k);
-            bits += 63u - (uint32_t)eg_k - 2u * (uint32_t)__builtin_clz(v);
+        for (int j = 0; j < 8; ++j) v[j] = load_vec<gg_i4, true>(src + j * 64 + lane);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            bits += eg_len(map_q(v[j].x) + add, eg_k) + eg_len(map_q(v[j].y) + add, eg_k) +
+                    eg_len(map_q(v[j].z) + add, eg_k) + eg_len(map_q(v[j].w) + add, eg_k);
+    } else {
+        for (int64_t i = base + lane; i < n; i += 64) bits += eg_len(map_q(q[i]) + add, eg_k);
+    }
+    bits = wave_reduce(bits, OpAdd());
+    if (lane == 0) tile_bits[tile] = bits;
+}
+
+// Exclusive scan of the tile sizes: tile_off[i] = sizes[0] + ... + sizes[i-1], the total to tile_off[nb] and
+// *total_out.  A workgroup owns kEgScanSeg consecutive tiles; it first adds up everything before its
+// segment (coalesced reads of an array that stays in cache), so the groups need not wait for each other.
+constexpr int kEgScanSeg = 8192;                    // 1024 lanes x 8 tiles
+
+__global__ __launch_bounds__(1024) void k_eg_scan(const uint64_t *__restrict__ sizes, uint64_t *__restrict__ tile_off, int64_t nb,
+                                                  uint64_t *__restrict__ index_end, uint64_t *__restrict__ total_out) {
+    __shared__ uint64_t wsum[2][16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t seg0 = (int64_t)blockIdx.x * kEgScanSeg;
+    uint64_t p0 = 0, p1 = 0, p2 = 0, p3 = 0;
+    int64_t i = tid;
+    for (; i + 3072 < seg0; i += 4096) { p0 += sizes[i]; p1 += sizes[i + 1024]; p2 += sizes[i + 2048]; p3 += sizes[i + 3072]; }
+    for (; i < seg0; i += 1024) p0 += sizes[i];
+    const uint64_t before_w = wave_reduce((p0 + p1) + (p2 + p3), OpAdd());
+    if (lane == 0) wsum[0][wave] = before_w;
+
+    const int64_t i0 = seg0 + (int64_t)tid * 8;
+    uint64_t e[8];
+    if (i0 + 8 <= nb) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = sizes[i0 + j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = i0 + j < nb ? sizes[i0 + j] : 0;
+    }
+    uint64_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) mine += e[j];
+    uint64_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint64_t t = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += t;
+    }
+    if (lane == 63) wsum[1][wave] = incl;
+    __syncthreads();
+    uint64_t carry = 0, below = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) { carry += wsum[0][w]; below += w < wave ? wsum[1][w] : 0; all += wsum[1][w]; }
+    uint64_t run = carry + below + (incl - mine);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (i0 + j < nb) {
+            tile_off[i0 + j] = run;
+            run += e[j];
         }
     }
-    const uint32_t total = block_reduce(bits, OpAdd(), red);
-    if (threadIdx.x == 0) block_bits[blockIdx.x] = total;
-}
-
-// exclusive scan of block_bits[0..nb) in place, total to block_bits[nb] and *total_out; one workgroup
-__global__ __launch_bounds__(1024) void k_eg_scan(uint64_t *__restrict__ block_bits, int64_t nb, uint64_t *__restrict__ total_out) {
-    __shared__ uint64_t part[1024];
-    const int tid = threadIdx.x;
-    const int64_t per = (nb + 1023) / 1024;
-    const int64_t lo = tid * per, hi = lo + per < nb ? lo + per : nb;
-    uint64_t s = 0;
-    for (int64_t i = lo; i < hi; ++i) s += block_bits[i];
-    part[tid] = s;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {      // Hillis-Steele inclusive scan over the 1024 partials
-        const uint64_t add = tid >= off ? part[tid - off] : 0;
-        __syncthreads();
-        part[tid] += add;
-        __syncthreads();
+    if (tid == 0 && seg0 + kEgScanSeg >= nb) {          // the group that owns the last tile (or the only group when nb = 0)
+        const uint64_t total = carry + all;
+        tile_off[nb] = total;
+        *index_end = total;                             // the last entry of the decoding index
+        if (total_out) *total_out = total;
     }
-    uint64_t run = tid ? part[tid - 1] : 0;
-    for (int64_t i = lo; i < hi; ++i) { const uint64_t b = block_bits[i]; block_bits[i] = run; run += b; }
-    if (tid == 1023) { block_bits[nb] = part[1023]; if (total_out) *total_out = part[1023]; }
 }
 
-__global__ __launch_bounds__(kBlock) void k_eg_encode(const int32_t *__restrict__ q, int64_t n, int eg_k,
-                                                      const uint64_t *__restrict__ block_off, uint32_t *__restrict__ stream,
-                                                      uint64_t capacity_bits) {
+struct EgSymbols { int32_t q[kEgPerLane]; };
+
+// the eight consecutive symbols of a lane; positions at and beyond n read as "absent" (flag cleared)
+__device__ __forceinline__ EgSymbols eg_load(const int32_t *__restrict__ q, int64_t i0, int64_t n) {
+    EgSymbols s;
+    if (i0 + kEgPerLane <= n) {
+        const gg_i4 a = load_vec<gg_i4, true>(reinterpret_cast<const gg_i4 *>(q + i0));
+        const gg_i4 b = load_vec<gg_i4, true>(reinterpret_cast<const gg_i4 *>(q + i0) + 1);
+        s.q[0] = a.x; s.q[1] = a.y; s.q[2] = a.z; s.q[3] = a.w;
+        s.q[4] = b.x; s.q[5] = b.y; s.q[6] = b.z; s.q[7] = b.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kEgPerLane; ++j) s.q[j] = i0 + j < n ? q[i0 + j] : 0;
+    }
+    return s;
+}
+
+// A workgroup packs kEgTilesPerBlock consecutive tiles.  All its symbol loads and tile offsets are issued up
+// front, so the only wait for global memory comes once; the words it stores are never waited for.
+__global__ __launch_bounds__(kBlock) void k_eg_encode(const int32_t *__restrict__ q, int64_t n, int64_t nb, int eg_k,
+                                                      const uint64_t *__restrict__ tile_off, uint64_t *__restrict__ index,
+                                                      uint32_t *__restrict__ stream, uint64_t capacity_bits) {
     __shared__ uint32_t buf[kEgLdsWords];
     __shared__ uint32_t wave_tot[kWaves];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t base = (int64_t)blockIdx.x * kEgBlock;
-    const uint64_t off0 = block_off[blockIdx.x], off1 = block_off[blockIdx.x + 1];
-    if (off1 > capacity_bits) return;               // stream too small: nothing of this block is written
+    const int64_t tile_first = (int64_t)blockIdx.x * kEgTilesPerBlock;
+    if (tile_first >= nb) return;
+    const int tiles = (int)(nb - tile_first < kEgTilesPerBlock ? nb - tile_first : kEgTilesPerBlock);
+    const uint32_t add = 1u << eg_k;
+
+    EgSymbols sym[kEgTilesPerBlock];
+    uint64_t off[kEgTilesPerBlock + 1];
+#pragma unroll
+    for (int t = 0; t < kEgTilesPerBlock; ++t)
+        sym[t] = eg_load(q, (tile_first + t) * kEgBlock + (int64_t)tid * kEgPerLane, n);   // all zero past n
+#pragma unroll
+    for (int t = 0; t <= kEgTilesPerBlock; ++t) off[t] = tile_off[t <= tiles ? tile_first + t : tile_first + tiles];
+    // the symbols that follow this group's tiles: at most 31 of them reach into the group's last word
+    const int64_t peek_i = (tile_first + tiles) * kEgBlock + tid;
+    const bool peek_live = tid < 32 && peek_i < n;
+    const int32_t peek_q = peek_live ? q[peek_i] : 0;
     for (int i = tid; i < kEgLdsWords; i += kBlock) buf[i] = 0;
+    uint32_t carry = 0;       // held by the lane that copied out a tile's last word: bits to start the next tile with
+    bool carried = false;     // uniform: the previous tile left its last word to this one
 
-    // lane owns kEgPerLane consecutive symbols, so positions follow from one scan of lane totals
-    uint32_t v[kEgPerLane], len[kEgPerLane], mine = 0;
 #pragma unroll
-    for (int j = 0; j < kEgPerLane; ++j) {
-        const int64_t i = base + (int64_t)tid * kEgPerLane + j;
-        v[j] = 0; len[j] = 0;
-        if (i < n) {
-            v[j] = map_q(q[i]) + (1u << eg_k);
-            len[j] = 63u - (uint32_t)eg_k - 2u * (uint32_t)__builtin_clz(v[j]);
+    for (int t = 0; t < kEgTilesPerBlock; ++t) {
+        if (t >= tiles) break;
+        const int64_t i0 = (tile_first + t) * kEgBlock + (int64_t)tid * kEgPerLane;
+        const uint64_t off0 = off[t], off1 = off[t + 1];
+        const bool fits = off1 <= capacity_bits;        // stream too small: nothing of this tile is written
+
+        // a lane owns kEgPerLane consecutive symbols, so positions follow from one scan of lane totals
+        const int64_t left = n - i0;
+        const int nvalid = left >= kEgPerLane ? kEgPerLane : (left > 0 ? (int)left : 0);   // < 8 only at the very end
+        uint32_t v[kEgPerLane], len[kEgPerLane], mine = 0;
+#pragma unroll
+        for (int j = 0; j < kEgPerLane; ++j) {
+            v[j] = map_q(sym[t].q[j]) + add;            // absent symbols were loaded as 0: v >= 1 always
+            len[j] = eg_len(v[j], eg_k);
         }
-        mine += len[j];
-    }
-    uint32_t incl = mine;                           // inclusive scan across the wave
+        if (nvalid < kEgPerLane) {
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t t = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += t;
-    }
-    if (lane == 63) wave_tot[wave] = incl;
-    __syncthreads();
-    uint32_t pos = incl - mine;
-    for (int w = 0; w < wave; ++w) pos += wave_tot[w];
-    pos += (uint32_t)(off0 & 31u);                  // LDS bit 0 is the stream's word boundary below off0
-#pragma unroll
-    for (int j = 0; j < kEgPerLane; ++j) {
-        if (len[j]) {
-            const uint32_t nb = 32u - (uint32_t)__builtin_clz(v[j]);   // significant bits of v
-            const uint32_t p = pos + (len[j] - nb);                     // after the zero prefix
-            // place nb bits so that the first lands at stream bit p (bit 31 of a word is the earliest)
-            const uint64_t window = (uint64_t)v[j] << (64u - nb - (p & 31u));
-            atomicOr(&buf[p >> 5], (uint32_t)(window >> 32));
-            const uint32_t lo = (uint32_t)window;
-            if (lo) atomicOr(&buf[(p >> 5) + 1], lo);
-            pos += len[j];
+            for (int j = 0; j < kEgPerLane; ++j) len[j] = j < nvalid ? len[j] : 0u;
         }
-    }
-    __syncthreads();
-    const uint64_t w0 = off0 >> 5;
-    const uint32_t span_bits = (uint32_t)(off0 & 31u) + (uint32_t)(off1 - off0);
-    const uint32_t nwords = (span_bits + 31u) >> 5;
-    for (uint32_t i = tid; i < nwords; i += kBlock) {
-        const uint32_t word = __builtin_bswap32(buf[i]);     // most significant byte first in memory
-        if (word == 0 && (i == 0 || i == nwords - 1)) continue;
-        if (i == 0 || i == nwords - 1) atomicOr(&stream[w0 + i], word);
-        else stream[w0 + i] = word;
+#pragma unroll
+        for (int j = 0; j < kEgPerLane; ++j) mine += len[j];
+        uint32_t incl = mine;                           // inclusive scan across the wave
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t x = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += x;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();                                // also: buf is all zero (initial clear / previous copy-out)
+        uint32_t pos = incl - mine;
+        for (int w = 0; w < wave; ++w) pos += wave_tot[w];
+        if ((tid & (kEgSubLanes - 1)) == 0 && i0 < n) index[i0 / GG_EG_TILE] = off0 + pos;   // bit offset of symbol i0
+        pos += (uint32_t)(off0 & 31u);                  // LDS bit 0 is the stream's word boundary below off0
+        if (fits) {
+            if (carry) { atomicOr(&buf[0], carry); carry = 0; }   // the previous tile's last, partial word
+            // the zero prefix is already there (buf is clear); OR the significant bits of v in, first bit at
+            // stream bit p (bit 31 of a word is the earliest).  The second word is OR-ed even when nothing
+            // spills into it: cheaper than a divergent branch.
+            auto place = [&](int j) {
+                const uint32_t nbit = 32u - (uint32_t)__builtin_clz(v[j]);   // significant bits of v
+                const uint32_t p = pos + (len[j] - nbit);
+                const uint64_t window = (uint64_t)v[j] << (64u - nbit - (p & 31u));
+                atomicOr(&buf[p >> 5], (uint32_t)(window >> 32));
+                atomicOr(&buf[(p >> 5) + 1], (uint32_t)window);
+                pos += len[j];
+            };
+            if (nvalid == kEgPerLane) {
+#pragma unroll
+                for (int j = 0; j < kEgPerLane; ++j) place(j);
+            } else {
+#pragma unroll
+                for (int j = 0; j < kEgPerLane; ++j) if (j < nvalid) place(j);
+            }
+            const uint32_t span_end = (uint32_t)(off0 & 31u) + (uint32_t)(off1 - off0);   // LDS bit after the tile
+            if (t + 1 == tiles && wave == 0 && (span_end & 31u)) {
+                // complete the group's last word with the first bits of the next group's tile
+                const uint32_t pv = map_q(peek_q) + add;
+                const uint32_t plen = peek_live ? eg_len(pv, eg_k) : 0u;
+                uint32_t pincl = plen;
+#pragma unroll
+                for (int d = 1; d < 32; d <<= 1) {
+                    const uint32_t x = __shfl_up(pincl, d, 64);
+                    if (lane >= d) pincl += x;
+                }
+                const uint32_t pstart = span_end + (pincl - plen);
+                if (plen && pstart < ((span_end + 31u) & ~31u)) {       // starts inside that word
+                    const uint32_t nbit = 32u - (uint32_t)__builtin_clz(pv);
+                    const uint32_t p = pstart + (plen - nbit);
+                    const uint64_t window = (uint64_t)pv << (64u - nbit - (p & 31u));
+                    atomicOr(&buf[p >> 5], (uint32_t)(window >> 32));
+                    atomicOr(&buf[(p >> 5) + 1], (uint32_t)window);
+                }
+            }
+        }
+        __syncthreads();
+        if (fits) {
+            const uint64_t w0 = off0 >> 5;
+            const uint32_t span_bits = (uint32_t)(off0 & 31u) + (uint32_t)(off1 - off0);
+            const uint32_t nwords = (span_bits + 31u) >> 5;
+            const bool tail_shared = (off1 & 31u) != 0;     // the last word also holds the next tile's first bits
+            // The word shared with the next tile stays in the workgroup when that tile is packed here too: its
+            // bits are carried into the next tile's first LDS word.  The group's very last word was completed
+            // above and is stored whole; the first word of the group's first tile, when it starts inside a
+            // word, belongs to the group before.
+            const bool keep_tail = tail_shared && t + 1 < tiles && off[t + 2 <= kEgTilesPerBlock ? t + 2 : t + 1] <= capacity_bits;
+            const bool head_foreign = !carried && (off0 & 31u) != 0;
+            for (uint32_t i = tid; i < nwords; i += kBlock) {
+                const uint32_t raw = buf[i];
+                buf[i] = 0;
+                if (i == nwords - 1 && keep_tail) carry = raw;
+                else if (i == 0 && head_foreign) {}
+                else stream[w0 + i] = __builtin_bswap32(raw);       // most significant byte first in memory
+            }
+            carried = keep_tail;
+        } else {
+            carried = false;
+        }
+        // the barrier after the next tile's lane scan separates this copy-out from the next tile's ORs
     }
 }
 
-__global__ void k_fill_u32(uint32_t *p, int64_t n) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
-}
+// Decoder: one lane per index tile (GG_EG_TILE symbols), a wave decodes 64 tiles side by side.  Each lane
+// keeps the next words of its tile in an LDS ring that is topped up four words at a time by a load issued
+// before four symbols are decoded and stored after them, so decoding does not wait for global memory.
+// Sixteen symbols per lane are collected in LDS and written as one 64-byte piece per tile.  Reads stay
+// below the word that holds the tile's last bit, whatever the stream contains.
+constexpr int kEgDecStep = 4;      // symbols between top-ups
+constexpr int kEgDecRow = 16;      // symbols per lane between writes
+constexpr int kEgRing = 16;        // ring words per lane
+constexpr int kEgTopUp = 4;        // words a lane loads per top-up
+constexpr int kEgStepWords = 10;   // a step takes at most 4 x 63 bits < 8 words, plus the look-ahead word and slack
+static_assert(kEgStepWords + kEgTopUp <= kEgRing && GG_EG_TILE % kEgDecRow == 0 && kEgDecRow % kEgDecStep == 0,
+              "ring holds a step and a top-up");
+typedef unsigned int EgWords4 __attribute__((ext_vector_type(4), aligned(4)));   // four stream words at any word address
 
-// one lane decodes one block of kEgBlock symbols from its indexed bit offset
-__global__ __launch_bounds__(64) void k_eg_decode(const uint8_t *__restrict__ stream, const uint64_t *__restrict__ block_off,
-                                                  int64_t n, int64_t nb, int eg_k, int32_t *__restrict__ q) {
-    const int64_t b = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    if (b >= nb) return;
-    uint64_t pos = block_off[b];
-    const uint64_t end = block_off[b + 1];
-    const int64_t first = b * kEgBlock;
-    const int64_t cnt = n - first < kEgBlock ? n - first : kEgBlock;
-    auto bit = [&](uint64_t p) -> uint32_t { return (stream[p >> 3] >> (7u - (uint32_t)(p & 7u))) & 1u; };
-    for (int64_t i = 0; i < cnt; ++i) {
-        int zeros = 0;
-        while (pos < end && !bit(pos)) { ++zeros; ++pos; }
-        const int L = zeros + eg_k + 1;
-        uint64_t v = 0;
-        for (int j = 0; j < L && pos < end; ++j) { v = (v << 1) | bit(pos); ++pos; }
-        const uint32_t u = (uint32_t)(v - (1ull << eg_k));
-        // inverse Map: odd -> positive (u+1)/2, even -> negative -u/2
-        q[first + i] = (u & 1u) ? (int32_t)((u + 1u) >> 1) : -(int32_t)(u >> 1);
+__global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ stream, const uint64_t *__restrict__ index,
+                                                  int64_t n, int64_t tiles, int eg_k, int32_t *__restrict__ q) {
+    __shared__ uint32_t ring[kEgRing][64];
+    __shared__ int32_t stage[64][kEgDecRow + 1];
+    const int lane = threadIdx.x;
+    const int64_t tile0 = (int64_t)blockIdx.x * 64;
+    const int64_t tile = tile0 + lane;
+    const bool live = tile < tiles;
+    const uint64_t pos = live ? index[tile] : 0;
+    const uint64_t end = live ? index[tile + 1] : 0;
+    const uint32_t *src = stream + (pos >> 5);                              // the lane's words, counted from its first
+    const uint32_t end_rel = end > pos ? (uint32_t)(((end + 31u) >> 5) - (pos >> 5)) : 0u;   // words from here on read as zero
+    uint32_t ld = 0, rd = 0;          // words loaded into / taken from the ring; rd <= ld <= rd + kEgRing
+    // four words from the lane's position `ld` on (a 16-byte load from a 4-byte-aligned address)
+    auto fetch4 = [&]() -> EgWords4 {
+        EgWords4 w = {0u, 0u, 0u, 0u};
+        if (ld + kEgTopUp <= end_rel) {
+            w = *reinterpret_cast<const EgWords4 *>(src + ld);
+        } else {
+            if (ld < end_rel) w.x = src[ld];
+            if (ld + 1 < end_rel) w.y = src[ld + 1];
+            if (ld + 2 < end_rel) w.z = src[ld + 2];
+        }
+        return w;
+    };
+    auto commit4 = [&](EgWords4 w) {
+        ring[ld & (kEgRing - 1)][lane] = __builtin_bswap32(w.x);
+        ring[(ld + 1) & (kEgRing - 1)][lane] = __builtin_bswap32(w.y);
+        ring[(ld + 2) & (kEgRing - 1)][lane] = __builtin_bswap32(w.z);
+        ring[(ld + 3) & (kEgRing - 1)][lane] = __builtin_bswap32(w.w);
+        ld += kEgTopUp;
+    };
+#pragma unroll 1
+    for (int r = 0; r < kEgRing / kEgTopUp; ++r) commit4(fetch4());       // fill the ring
+
+    // `win` holds the next `avail` (33..64) bits of the stream, earliest on top; `ahead` is the word after them
+    uint64_t win = ((uint64_t)ring[0][lane] << 32) | (uint64_t)ring[1][lane];
+    win <<= (uint32_t)(pos & 31u);
+    uint32_t avail = 64u - (uint32_t)(pos & 31u);
+    uint32_t ahead = ring[2][lane];
+    rd = 3;
+    // branch-free: in nearly every step some lane of the wave needs a word, so all take the same path
+    auto refill = [&]() {
+        const bool take = avail <= 32u;
+        const uint64_t more_bits = (uint64_t)ahead << (32u - (take ? avail : 32u));
+        win |= take ? more_bits : 0ull;
+        avail += take ? 32u : 0u;
+        const uint32_t nxt = ring[rd & (kEgRing - 1)][lane];   // used only when the slot is loaded (rd < ld)
+        ahead = take ? nxt : ahead;
+        rd += take ? 1u : 0u;
+    };
+
+    const uint32_t add = 1u << eg_k;
+    for (int s0 = 0; s0 < GG_EG_TILE; s0 += kEgDecRow) {
+#pragma unroll
+        for (int s1 = 0; s1 < kEgDecRow; s1 += kEgDecStep) {
+            while (__any(ld - rd < (uint32_t)kEgStepWords)) {          // rare: only streams with very long codes
+                if (ld - rd < (uint32_t)kEgStepWords) commit4(fetch4());
+            }
+            const bool more = ld - rd <= (uint32_t)(kEgRing - kEgTopUp);   // room for four more whatever this step takes
+            EgWords4 pre = {0u, 0u, 0u, 0u};
+            if (more) pre = fetch4();
+            // lanes past the end of the data decode zeros or stale bits; nothing of that is written
+#pragma unroll
+            for (int j = 0; j < kEgDecStep; ++j) {
+                const uint32_t top = (uint32_t)(win >> 32);
+                uint32_t zeros = top ? (uint32_t)__builtin_clz(top) : 31u;
+                zeros = zeros > 31u ? 31u : zeros;                  // a valid stream has at most 31
+                uint32_t L = zeros + (uint32_t)eg_k + 1u;
+                L = L > 32u ? 32u : L;
+                uint32_t v;
+                if (__any(zeros + L > 32u)) {       // some lane's code does not fit the 32 bits that are sure to be there
+                    win <<= zeros; avail -= zeros;
+                    refill();
+                    v = (uint32_t)(win >> 32) >> (32u - L);
+                    win <<= L; avail -= L;
+                } else {
+                    v = (top << zeros) >> (32u - L);
+                    win <<= zeros + L; avail -= zeros + L;
+                }
+                refill();
+                const uint32_t u = v - add;
+                // inverse Map: odd -> positive (u+1)/2, even -> negative -u/2
+                stage[lane][s1 + j] = (u & 1u) ? (int32_t)((u >> 1) + 1u) : -(int32_t)(u >> 1);
+            }
+            if (more) commit4(pre);
+        }
+        __syncthreads();
+        // four lanes cover one tile's 16 symbols (64 bytes); 16 tiles per instruction, 4 instructions
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = r * 16 + (lane >> 2), c = (lane & 3) * 4;
+            const int64_t g = (tile0 + row) * GG_EG_TILE + s0 + c;
+            if (g + 4 <= n) {
+                const gg_i4 val = {stage[row][c], stage[row][c + 1], stage[row][c + 2], stage[row][c + 3]};
+                *reinterpret_cast<gg_i4 *>(q + g) = val;
+            } else {
+                for (int x = 0; x < 4; ++x) if (g + x < n) q[g + x] = stage[row][c + x];
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -400,9 +636,13 @@ int gg_gct_update_segmented(float *w_dev, const float *g_dev, float *ghat_prev_d
     return check_launch();
 }
 
+// workspace: decoding index (T + 1 entries, T = ceil(n / GG_EG_TILE)) | packing-tile offsets (P + 1) | tile sizes (P)
+static int64_t eg_index_tiles(int64_t n) { return (n + GG_EG_TILE - 1) / GG_EG_TILE; }
+static int64_t eg_pack_tiles(int64_t n) { return (n + kEgBlock - 1) / kEgBlock; }
+
 int gg_eg_workspace_bytes(int64_t n, size_t *bytes_out_host) {
     if (!bytes_out_host || n < 0) return GG_ERR_INVALID_ARG;
-    *bytes_out_host = (size_t)((n + kEgBlock - 1) / kEgBlock + 1) * sizeof(uint64_t);
+    *bytes_out_host = (size_t)(eg_index_tiles(n) + 2 * eg_pack_tiles(n) + 2) * sizeof(uint64_t);
     return GG_OK;
 }
 
@@ -412,27 +652,26 @@ int gg_eg_encode(const int32_t *symbols_dev, int64_t n, int eg_k, uint8_t *strea
     if (!block_offsets_dev || !aligned8(block_offsets_dev)) return GG_ERR_WORKSPACE;
     if (total_bits_dev && !aligned8(total_bits_dev)) return GG_ERR_INVALID_ARG;
     if (stream_bytes && (!stream_dev || (reinterpret_cast<uintptr_t>(stream_dev) & 3u))) return GG_ERR_INVALID_ARG;
-    if (n > 0 && !symbols_dev) return GG_ERR_INVALID_ARG;
+    if (n > 0 && (!symbols_dev || !aligned16(symbols_dev))) return GG_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    const int64_t nb = (n + kEgBlock - 1) / kEgBlock;
-    if (nb > 2147483647LL) return GG_ERR_INVALID_ARG;
+    const int64_t nb = eg_pack_tiles(n), T = eg_index_tiles(n);
+    if (nb > 2147483647LL * kWaves) return GG_ERR_INVALID_ARG;
+    uint64_t *tile_off = block_offsets_dev + T + 1;
+    uint64_t *sizes = tile_off + nb + 1;
     int rc;
-    if (stream_bytes) {
-        const int64_t words = (int64_t)(stream_bytes / 4);
-        int64_t fb = (words + 255) / 256;
-        if (fb > 8192) fb = 8192;
-        hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)fb), dim3(256), 0, st, reinterpret_cast<uint32_t *>(stream_dev), words);
-        if ((rc = check_launch()) != GG_OK) return rc;
-    }
     if (nb > 0) {
-        hipLaunchKernelGGL(k_eg_block_bits, dim3((unsigned)nb), dim3(kBlock), 0, st, symbols_dev, n, eg_k, block_offsets_dev);
+        hipLaunchKernelGGL(k_eg_tile_bits, dim3((unsigned)((nb + kWaves - 1) / kWaves)), dim3(kBlock), 0, st, symbols_dev, n,
+                           nb, eg_k, sizes);
         if ((rc = check_launch()) != GG_OK) return rc;
     }
-    hipLaunchKernelGGL(k_eg_scan, dim3(1), dim3(1024), 0, st, block_offsets_dev, nb, total_bits_dev);
+    const int64_t groups = nb > 0 ? (nb + kEgScanSeg - 1) / kEgScanSeg : 1;
+    hipLaunchKernelGGL(k_eg_scan, dim3((unsigned)groups), dim3(1024), 0, st, sizes, tile_off, nb, block_offsets_dev + T,
+                       total_bits_dev);
     if ((rc = check_launch()) != GG_OK) return rc;
-    if (nb > 0) {
-        hipLaunchKernelGGL(k_eg_encode, dim3((unsigned)nb), dim3(kBlock), 0, st, symbols_dev, n, eg_k, block_offsets_dev,
-                           reinterpret_cast<uint32_t *>(stream_dev), stream_bytes * 8ull);
+    if (nb > 0) {   // also without room for any stream: this kernel writes the index
+        hipLaunchKernelGGL(k_eg_encode, dim3((unsigned)((nb + kEgTilesPerBlock - 1) / kEgTilesPerBlock)), dim3(kBlock), 0, st,
+                           symbols_dev, n, nb, eg_k, tile_off, block_offsets_dev, reinterpret_cast<uint32_t *>(stream_dev),
+                           stream_bytes * 8ull);
         if ((rc = check_launch()) != GG_OK) return rc;
     }
     return GG_OK;
@@ -442,10 +681,13 @@ int gg_eg_decode(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, i
                  void *stream) {
     if (n < 0 || eg_k < 0 || eg_k > GG_MAX_EG_K) return GG_ERR_INVALID_ARG;
     if (n == 0) return GG_OK;
-    if (!stream_dev || !block_offsets_dev || !symbols_dev) return GG_ERR_INVALID_ARG;
-    const int64_t nb = (n + kEgBlock - 1) / kEgBlock;
-    hipLaunchKernelGGL(k_eg_decode, dim3((unsigned)((nb + 63) / 64)), dim3(64), 0, (hipStream_t)stream, stream_dev,
-                       block_offsets_dev, n, nb, eg_k, symbols_dev);
+    if (!stream_dev || (reinterpret_cast<uintptr_t>(stream_dev) & 3u) || !block_offsets_dev || !aligned8(block_offsets_dev) ||
+        !symbols_dev || !aligned16(symbols_dev))
+        return GG_ERR_INVALID_ARG;
+    const int64_t T = eg_index_tiles(n);
+    if ((T + 63) / 64 > 2147483647LL) return GG_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_eg_decode, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
+                       reinterpret_cast<const uint32_t *>(stream_dev), block_offsets_dev, n, T, eg_k, symbols_dev);
     return check_launch();
 }
 

@@ -152,7 +152,8 @@ def test_eg_stream_equals_oracle_stream(gg, n, k):
     if n:
         assert total == int(gg.rate_records(out)[0]["eg_bits"])       # the rate estimate is the stream size
     sb = stream.cpu().numpy()
-    assert np.array_equal(sb[: obuf.size], obuf) and not sb[obuf.size:].any()
+    assert np.array_equal(sb[: obuf.size], obuf)
+    assert not sb[obuf.size: (obuf.size + 3) // 4 * 4].any()      # the last word is zero-padded
     idx = index.cpu().numpy()
     assert idx[0] == 0 and idx[-1] == total and np.all(np.diff(idx) >= 0)
     back = gg.gg_eg_decode(stream, index, n, eg_k=k)
@@ -174,6 +175,40 @@ def test_eg_stream_extreme_symbols_and_tight_capacity(gg):
     stream, index, total = gg.gg_eg_encode(q, eg_k=0, capacity_bytes=64)
     assert total == oracle.eg_encode(np.array([oracle.map_symbol(int(v)) for v in q.cpu().numpy()], dtype=np.uint32), 0)[1]
     assert total > 64 * 8 and stream.numel() == 64
+
+
+def test_eg_stream_of_longest_codes(gg):
+    # every symbol takes 63 bits (k = 0): the decoder's buffered words run out within a step and are topped up
+    n = 5000
+    q = torch.full((n,), 2 ** 30, dtype=torch.int32, device=DEV)
+    q[1::2] = -(2 ** 30)
+    u = np.array([oracle.map_symbol(int(v)) for v in q.cpu().numpy()], dtype=np.uint32)
+    obuf, obits = oracle.eg_encode(u, 0)
+    stream, index, total = gg.gg_eg_encode(q, eg_k=0)
+    assert total == obits
+    assert np.array_equal(stream.cpu().numpy()[: obuf.size], obuf)
+    assert torch.equal(gg.gg_eg_decode(stream, index, n, eg_k=0), q)
+
+
+def test_eg_stream_many_tiles(gg):
+    # more packing tiles (2048 symbols) than one scan group holds (8192), ragged last tile
+    n = 2 * 8192 * 2048 + 12345
+    x = make(n, 0.02, 0.9, seed=21)
+    ws = gg.Workspace(n, 1)
+    out, _, sym = gg.gg_quantize_rate(x, 0.02 / 16.0, ws, want_symbols=True)
+    stream, index, total = gg.gg_eg_encode(sym, eg_k=0)
+    assert total == int(gg.rate_records(out)[0]["eg_bits"])
+    q = sym.cpu().numpy()
+    u = np.where(q > 0, 2 * q.astype(np.int64) - 1, -2 * q.astype(np.int64)).astype(np.uint32)
+    obuf, obits = oracle.eg_encode(u, 0)
+    assert total == obits
+    assert np.array_equal(stream.cpu().numpy()[: obuf.size], obuf)
+    idx = index.cpu().numpy()
+    assert idx.size == (n + gg.GG_EG_TILE - 1) // gg.GG_EG_TILE + 1 and idx[0] == 0 and idx[-1] == total
+    # index entries are the bit offsets of every GG_EG_TILE-th symbol
+    lens = 2 * np.floor(np.log2(u.astype(np.float64) + 1.0)).astype(np.int64) + 1
+    assert np.array_equal(idx[1:-1], np.cumsum(lens)[gg.GG_EG_TILE - 1::gg.GG_EG_TILE][: idx.size - 2])
+    assert torch.equal(gg.gg_eg_decode(stream, index, n, eg_k=0), sym)
 
 
 # ---- torch glue: GG init driver, differentiable rate, GCT state ---------------------------------
