@@ -263,12 +263,26 @@ def main():
         rec, _, sym = gg.gg_quantize_rate(flat[:m], float(frec["alpha"][0]) / 16.0, wsq, want_symbols=True)
         bits = int(gg.rate_records(rec)[0]["eg_bits"])
 
+        bufs = gg.eg_buffers(m, (bits + 7) // 8, dev)
+
         def step_enc():
-            gg.gg_eg_encode(sym, 0, capacity_bytes=(bits + 7) // 8)
+            gg.gg_eg_encode(sym, 0, buffers=bufs)
 
         step_enc()
-        _, ms_e = time_steps(step_enc, 5, torch)
+        _, ms_e = time_steps(step_enc, 10, torch)
+        stream_e, index_e, _ = gg.gg_eg_encode(sym, 0, buffers=bufs)
+        assert int(bufs[2].item()) == bits                 # the stream is exactly as long as the rate sweep said
+        back = torch.empty_like(sym)
+
+        def step_dec():
+            gg.gg_eg_decode(stream_e, index_e, m, 0, out=back)
+
+        step_dec()
+        _, ms_d = time_steps(step_dec, 10, torch)
+        assert torch.equal(back, sym)
         extra["eg_encode"] = {"symbols": m, "stream_bits": bits, "ms": round(ms_e, 4), "Gsymbols/s": round(m / ms_e / 1e6, 2)}
+        extra["eg_decode"] = {"symbols": m, "ms": round(ms_d, 4), "Gsymbols/s": round(m / ms_d / 1e6, 2)}
+        del back, stream_e, index_e, bufs
         del sym
         if args.all:
             extra.update(other_configs(gg, gg_inputs, torch, dev, args))

@@ -326,25 +326,36 @@ def gg_gct_update_segmented(w: torch.Tensor, g: torch.Tensor, ghat_prev: torch.T
                                          _stream()), "gg_gct_update_segmented")
 
 
-def gg_eg_encode(symbols: torch.Tensor, eg_k: int = 0, capacity_bytes: Optional[int] = None):
-    """Returns (stream uint8 tensor, block bit offsets int64 tensor, total_bits int).  Without a capacity the
-    stream is sized for the worst case of 8 bytes per symbol."""
+def gg_eg_encode(symbols: torch.Tensor, eg_k: int = 0, capacity_bytes: Optional[int] = None, buffers=None):
+    """Returns (stream uint8 tensor, index int64 tensor of bit offsets, total_bits int).  Without a capacity the
+    stream is sized for the worst case of 8 bytes per symbol.  `buffers` = (stream, workspace, total) from an
+    earlier call's `eg_buffers` reuses device memory and skips the read-back of the total (returned as None)."""
     n = symbols.numel()
-    out = C.c_size_t(0)
-    _check(lib().gg_eg_workspace_bytes(n, C.byref(out)), "gg_eg_workspace_bytes")
-    index = torch.empty(out.value // 8, dtype=torch.int64, device=symbols.device)
-    cap = (8 * n + 4) if capacity_bytes is None else int(capacity_bytes)
-    cap = (cap + 3) // 4 * 4
-    stream = torch.empty(cap, dtype=torch.uint8, device=symbols.device)
-    total = torch.zeros(1, dtype=torch.int64, device=symbols.device)
-    _check(lib().gg_eg_encode(_dev(symbols), n, eg_k, _dev(stream), cap, _dev(index), _dev(total), _stream()),
+    if buffers is None:
+        stream, work, total = eg_buffers(n, capacity_bytes, symbols.device)
+    else:
+        stream, work, total = buffers
+    _check(lib().gg_eg_encode(_dev(symbols), n, eg_k, _dev(stream), stream.numel(), _dev(work), _dev(total), _stream()),
            "gg_eg_encode")
     tiles = (n + GG_EG_TILE - 1) // GG_EG_TILE
-    return stream, index[: tiles + 1], int(total.item())
+    return stream, work[: tiles + 1], (int(total.item()) if buffers is None else None)
 
 
-def gg_eg_decode(stream: torch.Tensor, index: torch.Tensor, n: int, eg_k: int = 0) -> torch.Tensor:
-    out = torch.empty(n, dtype=torch.int32, device=stream.device)
+def eg_buffers(n: int, capacity_bytes: Optional[int] = None, device="cuda"):
+    """Device buffers for gg_eg_encode: (stream, index workspace, total)."""
+    out = C.c_size_t(0)
+    _check(lib().gg_eg_workspace_bytes(n, C.byref(out)), "gg_eg_workspace_bytes")
+    work = torch.empty(out.value // 8, dtype=torch.int64, device=device)
+    cap = (8 * n + 4) if capacity_bytes is None else int(capacity_bytes)
+    cap = (cap + 3) // 4 * 4
+    stream = torch.empty(cap, dtype=torch.uint8, device=device)
+    total = torch.zeros(1, dtype=torch.int64, device=device)
+    return stream, work, total
+
+
+def gg_eg_decode(stream: torch.Tensor, index: torch.Tensor, n: int, eg_k: int = 0, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty(n, dtype=torch.int32, device=stream.device)
     _check(lib().gg_eg_decode(_dev(stream), _dev(index), n, eg_k, _dev(out), _stream()), "gg_eg_decode")
     return out
 
