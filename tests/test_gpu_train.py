@@ -177,6 +177,53 @@ def test_eg_stream_extreme_symbols_and_tight_capacity(gg):
     assert total > 64 * 8 and stream.numel() == 64
 
 
+def test_eg_stream_truncated_by_capacity(gg):
+    # the stream buffer ends inside the data: every packing tile (2048 symbols) that fits is written whole,
+    # wherever the cut falls relative to the groups of four tiles a workgroup packs
+    n = 11 * 2048 + 77
+    rng = np.random.default_rng(5)
+    qh = rng.integers(-40, 41, size=n).astype(np.int32)
+    qh[rng.integers(0, n, size=50)] = rng.integers(-2 ** 20, 2 ** 20, size=50).astype(np.int32)
+    q = torch.tensor(qh, device=DEV)
+    u = np.where(qh > 0, 2 * qh.astype(np.int64) - 1, -2 * qh.astype(np.int64)).astype(np.uint32)
+    for k in (0, 2):
+        obuf, obits = oracle.eg_encode(u, k)
+        lens = 2 * np.floor(np.log2(u.astype(np.float64) + float(1 << k))).astype(np.int64) - k + 1
+        tile_end = np.cumsum(lens)[np.minimum(np.arange(1, 13) * 2048, n) - 1]      # bit offset after each tile
+        assert tile_end[-1] == obits
+        for cut in range(1, 12):
+            for slack in (0, 4, 8):        # capacity just at / beyond the end of tile `cut`
+                cap = (int(tile_end[cut - 1]) + 31) // 32 * 4 + slack
+                stream, index, total = gg.gg_eg_encode(q, eg_k=k, capacity_bytes=cap)
+                assert total == obits and stream.numel() == cap
+                fit = int(np.searchsorted(tile_end, cap * 8, side="right"))            # tiles that end within the buffer
+                assert fit >= cut
+                good_bits = int(tile_end[fit - 1])
+                sb = stream.cpu().numpy()
+                whole = good_bits // 8
+                assert np.array_equal(sb[:whole], obuf[:whole]), (k, cut, slack)
+                if good_bits % 8:
+                    mask = (0xFF << (8 - good_bits % 8)) & 0xFF
+                    assert (sb[whole] & mask) == (obuf[whole] & mask)
+                # the index does not depend on the buffer
+                idx = index.cpu().numpy()
+                assert np.array_equal(idx[1:-1], np.cumsum(lens)[gg.GG_EG_TILE - 1::gg.GG_EG_TILE][: idx.size - 2])
+
+
+@pytest.mark.parametrize("k", [1, 7, 15])
+def test_eg_stream_orders_and_tile_multiples(gg, k):
+    rng = np.random.default_rng(k)
+    for n in (256, 2048 - 256, 4 * 2048, 8 * 2048 + 255, 8 * 2048 + 256 + 1):
+        qh = (rng.standard_cauchy(n) * 30).clip(-2 ** 29, 2 ** 29).astype(np.int32)
+        q = torch.tensor(qh, device=DEV)
+        u = np.where(qh > 0, 2 * qh.astype(np.int64) - 1, -2 * qh.astype(np.int64)).astype(np.uint32)
+        obuf, obits = oracle.eg_encode(u, k)
+        stream, index, total = gg.gg_eg_encode(q, eg_k=k)
+        assert total == obits
+        assert np.array_equal(stream.cpu().numpy()[: obuf.size], obuf)
+        assert torch.equal(gg.gg_eg_decode(stream, index, n, eg_k=k), q)
+
+
 def test_eg_stream_of_longest_codes(gg):
     # every symbol takes 63 bits (k = 0): the decoder's buffered words run out within a step and are topped up
     n = 5000
@@ -231,7 +278,7 @@ def test_differentiable_eg_rate(gg):
     r = gg.eg_rate(a, delta, 0)
     ws = gg.Workspace(a.numel(), 1)
     rec = gg.rate_records(gg.gg_quantize_rate(a.detach().view(-1), delta, ws)[0])[0]
-    assert float(r) == pytest.approx(float(rec["eg_bits"]) / a.numel(), rel=1e-6)
+    assert float(r.detach()) == pytest.approx(float(rec["eg_bits"]) / a.numel(), rel=1e-6)
     (3.0 * r).backward()
     o = oracle.rate_grad(host_bits(a.detach().view(-1)), inv32(delta), 0, a.numel(), scale=3.0)
     assert np.allclose(a.grad.view(-1).cpu().numpy(), o, rtol=1e-5, atol=1e-30)
