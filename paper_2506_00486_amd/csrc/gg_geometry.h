@@ -132,9 +132,20 @@ static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
 
 constexpr int kSolveTable = 4096;   // intervals of the tabulated moment-ratio curve (many-unit solves)
 
+// What one run contributes to the rate record of a unit that several runs share; a later kernel folds the
+// slots into the record, so the sweep needs no atomics on a record that hundreds of blocks finish on at the
+// same time.  A run shares at most two units with other runs: the one it starts in (slot 2 run) and the one
+// it ends in (slot 2 run + 1); a piece that starts with the run takes the first.
+struct RatePiece {
+    uint64_t bits;           // sum of code lengths
+    uint32_t u_max, n_clamped, flags, _pad[3];
+};
+static_assert(sizeof(RatePiece) == 32, "two 16-byte stores");
+constexpr int64_t kMaxRuns = 256 * 64;   // blocks of one sweep (resident blocks: at most 8 per compute unit)
+
 struct WsLayout {
-    size_t off_bytes, params_bytes, partials_bytes, table_bytes, total;   // off_bytes: offsets + chunk prefix
-    size_t off_at, params_at, partials_at, table_at;
+    size_t off_bytes, params_bytes, partials_bytes, pieces_bytes, table_bytes, total;   // off_bytes: offsets + chunk prefix
+    size_t off_at, params_at, partials_at, pieces_at, table_at;
 };
 
 static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
@@ -147,8 +158,10 @@ static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
     w.off_at = 256;
     w.params_at = w.off_at + w.off_bytes;
     w.partials_at = w.params_at + w.params_bytes;
+    w.pieces_bytes = (size_t)kMaxRuns * 2 * sizeof(RatePiece);
+    w.pieces_at = w.partials_at + w.partials_bytes;
     w.table_bytes = align_up((size_t)(kSolveTable + 1) * sizeof(double2), 256);
-    w.table_at = w.partials_at + w.partials_bytes;
+    w.table_at = w.pieces_at + w.pieces_bytes;
     w.total = w.table_at + w.table_bytes;
     return w;
 }
@@ -171,6 +184,7 @@ struct Geometry {
                                       // followed by S+1 int32 chunk prefix sums, as it lies in the workspace
     SegParam *params() const { return reinterpret_cast<SegParam *>(ws + wl.params_at); }
     double2 *partials() const { return reinterpret_cast<double2 *>(ws + wl.partials_at); }
+    RatePiece *rate_pieces() const { return reinterpret_cast<RatePiece *>(ws + wl.pieces_at); }
     double2 *solve_table() const { return reinterpret_cast<double2 *>(ws + wl.table_at); }
 };
 

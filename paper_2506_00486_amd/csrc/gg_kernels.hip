@@ -9,8 +9,10 @@
 //                     bracketing of the moment-ratio equation, Eq. 2 for alpha; derives the
 //                     unit's quantiser / penalty parameters and clears its rate record
 //   k_quant           re-reads x: quantise, Map, Exp-Golomb bits, u_max, optional LDS-privatised
-//                     histogram, symbols, penalty gradient; integer atomics into the rate record
-//   k_rate_finalize   histogram entropy in fp64 (only when a histogram was asked for)
+//                     histogram, symbols, penalty gradient; a unit inside one run gets its rate record
+//                     from that block, a unit that several runs share one slot of sums per run
+//   k_rate_reduce     folds the per-run rate sums of units that several runs share into their records
+//   k_rate_finalize   the same, plus the histogram entropy in fp64 (when a histogram was asked for)
 // All reductions are order-fixed (floating point) or integer, so results are reproducible.
 
 #include <hip/hip_runtime.h>
@@ -399,6 +401,7 @@ struct QuantArgs {
     int accumulate;
     // FIT
     double2 *partials;
+    RatePiece *pieces;        // RATE: per-run slots for units that several runs share
     // work split
     int64_t n_chunks;
     int32_t chunks_per_block;
@@ -578,8 +581,10 @@ struct QuantBody {
 };
 
 // A block owns a run of consecutive chunks.  Lane accumulators (bit-length sum, u_max, NaN seen,
-// clamped count) live across chunks and are combined, then added to the unit's rate record with
-// integer atomics, only when the run leaves a unit or ends.
+// clamped count) live across chunks and are combined only when the run leaves a unit or ends: into the
+// unit's rate record when the whole unit lies in this run, else into the run's slot for a unit that other
+// runs share (k_rate_reduce / k_rate_finalize fold the slots).  Many blocks finishing on one record with
+// atomics cost a single-tensor sweep of 67 M elements 25-35 us of 55-80.
 // With FIT the same sweep also accumulates the moments exactly as k_fit_partials does (one-sweep mode:
 // the steps are given up front, so nothing has to wait for the fit).
 template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA, bool FIT = false>
@@ -608,7 +613,7 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
     body.lbins = (uint32_t)a.lbins;
 
     int piece_seg = -1;
-    bool rate_live = false;
+    bool rate_live = false, piece_shared = false, piece_flushed = false;
     int64_t piece_elems = 0, piece_first = first;
     int32_t piece_chunks = 0;
     double d1 = 0.0, d2 = 0.0;     // FIT: fp64 lane totals of the (run, unit) piece
@@ -642,18 +647,32 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
                     nlast = block_reduce(body.n_last, OpAdd(), red[3]);
                 }
                 if (tid == 0 && rate_live) {
-                    gg_rate_t *r = a.rate + piece_seg;
                     // sum of 63-k-2 clz(u+2^k), or with k = 0 on the exponent path of 2e-251
                     const uint64_t bits = kExp0 ? 2ull * lsum - 251ull * (uint64_t)piece_elems
                                                 : (uint64_t)piece_elems * a.eg_const - 2ull * lsum;
-                    atomicAdd(reinterpret_cast<unsigned long long *>(&r->eg_bits), (unsigned long long)bits);
-                    atomicMax(&r->u_max, um);
-                    if (um) atomicMax(&r->fl_bits, 32u - (uint32_t)__builtin_clz(um));   // bit length is monotone in u
-                    if (ncl) atomicAdd(reinterpret_cast<unsigned long long *>(&r->n_clamped), (unsigned long long)ncl);
-                    if (nlast) atomicAdd(reinterpret_cast<unsigned long long *>(&body.ghist[body.last_bin]), (unsigned long long)nlast);
                     const uint32_t fl = (nan ? GG_F_NONFINITE : 0u) | (um >= 2147483647u ? GG_F_SATURATED : 0u);
-                    if (fl) atomicOr(&r->flags, fl);
+                    if (piece_shared) {
+                        // other runs hold pieces of this unit: leave the sums in this run's slot
+                        RatePiece *s = a.pieces + 2 * (int64_t)blockIdx.x + (piece_first == first ? 0 : 1);
+                        RatePiece v;
+                        v.bits = bits; v.u_max = um; v.n_clamped = ncl; v.flags = fl; v._pad[0] = v._pad[1] = v._pad[2] = 0;
+                        if (piece_flushed) {
+                            v.bits += s->bits; v.u_max = um > s->u_max ? um : s->u_max; v.n_clamped += s->n_clamped; v.flags |= s->flags;
+                        }
+                        *s = v;
+                    } else {
+                        // the whole unit lies in this run: its record is this block's alone
+                        gg_rate_t *r = a.rate + piece_seg;
+                        r->eg_bits += bits;
+                        const uint32_t m = um > r->u_max ? um : r->u_max;
+                        r->u_max = m;
+                        if (m) r->fl_bits = 32u - (uint32_t)__builtin_clz(m);
+                        r->n_clamped += ncl;
+                        if (fl) r->flags |= fl;
+                    }
+                    if (nlast) atomicAdd(reinterpret_cast<unsigned long long *>(&body.ghist[body.last_bin]), (unsigned long long)nlast);
                 }
+                piece_flushed = true;
                 if (want_hist && rate_live) {   // merge the block-private bins into the unit's histogram
                     uint64_t *g = a.hist + (int64_t)piece_seg * a.nbins;
                     // bins above the largest symbol this block saw are still zero
@@ -678,7 +697,13 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
     for (cur.init(sv, first, last); cur.valid(); cur.next(sv)) {
         if (cur.L.seg != piece_seg || piece_chunks >= 32768) {
             flush(cur.L.seg != piece_seg);
-            if (cur.L.seg != piece_seg) piece_first = cur.chunk;
+            if (cur.L.seg != piece_seg) {
+                piece_first = cur.chunk;
+                piece_flushed = false;
+                // does the unit reach into another run?
+                const int64_t c0 = unit_chunk0(sv, cur.L.seg), c1 = unit_chunk1(sv, cur.L.seg);
+                piece_shared = c0 < first || c1 > last;
+            }
             piece_seg = cur.L.seg;
             const SegParam P = a.params ? a.params[piece_seg] : a.single;
             rate_live = RATE && !(P.flags & kSkipRate);
@@ -786,16 +811,98 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Rate records of units that several runs share: the sweep left one slot per run (see RatePiece); these
+// kernels fold them, in run order, into the record.  Units inside a single run are final already.
+// ---------------------------------------------------------------------------------------------
+struct PieceSum {
+    uint64_t bits = 0;
+    uint32_t u_max = 0, n_clamped = 0, flags = 0;
+    __device__ __forceinline__ void add(const RatePiece &p) {
+        bits += p.bits; u_max = p.u_max > u_max ? p.u_max : u_max; n_clamped += p.n_clamped; flags |= p.flags;
+    }
+};
+
+// runs r0 .. r1 that overlap the chunks [c0, c1) of a unit; shared iff r0 < r1
+__device__ __forceinline__ const RatePiece &piece_slot(const RatePiece *pieces, int64_t run, int32_t cpb, int64_t c0) {
+    return pieces[2 * run + (run * cpb >= c0 ? 0 : 1)];   // the piece starts with the run unless the unit starts later
+}
+
+__device__ __forceinline__ void store_piece_sum(gg_rate_t *r, const PieceSum &t) {
+    r->eg_bits = t.bits;
+    r->u_max = t.u_max;
+    r->fl_bits = t.u_max ? 32u - (uint32_t)__builtin_clz(t.u_max) : 1u;
+    r->n_clamped = t.n_clamped;
+    if (t.flags) r->flags |= t.flags;
+}
+
+// one workgroup per unit
+__global__ __launch_bounds__(kBlock) void k_rate_reduce(SegView sv, const RatePiece *__restrict__ pieces, int32_t cpb,
+                                                        gg_rate_t *__restrict__ rate) {
+    __shared__ uint64_t red_bits[kWaves];
+    __shared__ uint32_t red_u[3][kWaves];
+    const int seg = blockIdx.x, tid = threadIdx.x;
+    const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
+    if (c1 <= c0) return;
+    const int64_t r0 = c0 / cpb, r1 = (c1 - 1) / cpb;
+    if (r0 == r1) return;
+    gg_rate_t *r = rate + seg;
+    if (r->flags & (GG_F_DEGENERATE | GG_F_EMPTY)) return;       // no rate was evaluated: the slots are stale
+    PieceSum t;
+#pragma unroll 4
+    for (int64_t run = r0 + tid; run <= r1; run += kBlock) t.add(piece_slot(pieces, run, cpb, c0));
+    t.bits = block_reduce(t.bits, OpAdd(), red_bits);
+    t.u_max = block_reduce(t.u_max, OpMax(), red_u[0]);
+    t.n_clamped = block_reduce(t.n_clamped, OpAdd(), red_u[1]);
+    t.flags = block_reduce(t.flags, OpOr(), red_u[2]);
+    if (tid == 0) store_piece_sum(r, t);
+}
+
+// one lane per unit (many small units: few of them are shared, and those by few runs)
+__global__ __launch_bounds__(64) void k_rate_reduce_lanes(SegView sv, const RatePiece *__restrict__ pieces, int32_t cpb,
+                                                          gg_rate_t *__restrict__ rate) {
+    const int seg = blockIdx.x * 64 + threadIdx.x;
+    if (seg >= sv.S) return;
+    const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
+    if (c1 <= c0) return;
+    const int64_t r0 = c0 / cpb, r1 = (c1 - 1) / cpb;
+    if (r0 == r1) return;
+    gg_rate_t *r = rate + seg;
+    if (r->flags & (GG_F_DEGENERATE | GG_F_EMPTY)) return;
+    PieceSum t;
+    for (int64_t run = r0; run <= r1; ++run) t.add(piece_slot(pieces, run, cpb, c0));
+    store_piece_sum(r, t);
+}
+
+// With a histogram: the same folding, then the entropy of the unit's bins, one workgroup per unit.
 constexpr int kFinalizeThreads = 1024;
-__global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(gg_rate_t *__restrict__ rate,
+__global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, const RatePiece *__restrict__ pieces, int32_t cpb,
+                                                                    gg_rate_t *__restrict__ rate,
                                                                     const uint64_t *__restrict__ hist, int32_t nbins) {
     __shared__ double red[kFinalizeThreads / 64];
+    __shared__ uint64_t red_bits[kFinalizeThreads / 64];
+    __shared__ uint32_t red_u[3][kFinalizeThreads / 64];
     const int seg = blockIdx.x, tid = threadIdx.x;
     gg_rate_t *r = rate + seg;
     const uint32_t flags = r->flags;
     const uint64_t n = r->n;
+    const bool live = n > 0 && !(flags & GG_F_DEGENERATE);
+    const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
+    const int64_t r0 = c1 > c0 ? c0 / cpb : 0, r1 = c1 > c0 ? (c1 - 1) / cpb : 0;
+    const bool shared = live && r0 < r1;           // uniform over the block
+    if (shared) {
+        PieceSum t;
+        for (int64_t run = r0 + tid; run <= r1; run += kFinalizeThreads) t.add(piece_slot(pieces, run, cpb, c0));
+        t.bits = wave_reduce(t.bits, OpAdd());
+        t.u_max = wave_reduce(t.u_max, OpMax());
+        t.n_clamped = wave_reduce(t.n_clamped, OpAdd());
+        t.flags = wave_reduce(t.flags, OpOr());
+        if ((tid & 63) == 0) {
+            red_bits[tid >> 6] = t.bits; red_u[0][tid >> 6] = t.u_max; red_u[1][tid >> 6] = t.n_clamped; red_u[2][tid >> 6] = t.flags;
+        }
+    }
     double h = 0.0;
-    if (hist && n > 0 && !(flags & GG_F_DEGENERATE)) {
+    if (live) {
         const uint64_t *g = hist + (int64_t)seg * nbins;
         const double inv_n = 1.0 / (double)n;
         for (int b = tid; b < nbins; b += kFinalizeThreads) {   // ascending bins per lane, fixed tree above
@@ -803,18 +910,20 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(gg_rate_t *_
             if (c) { const double p = (double)c * inv_n; h -= p * log2(p); }
         }
     }
-    if (hist) {   // uniform over the block
-        h = wave_reduce(h, OpAdd());
-        if ((tid & 63) == 0) red[tid >> 6] = h;
-        __syncthreads();
-    }
+    h = wave_reduce(h, OpAdd());
+    if ((tid & 63) == 0) red[tid >> 6] = h;
+    __syncthreads();
     if (tid == 0) {
-        if (hist) { h = 0.0; for (int w = 0; w < kFinalizeThreads / 64; ++w) h += red[w]; }
-        const uint32_t um = r->u_max;
-        uint32_t f = flags;
-        if (um >= 2147483647u) f |= GG_F_SATURATED;
-        r->flags = f;
-        r->fl_bits = (flags & GG_F_DEGENERATE) ? 0u : (um ? 32u - (uint32_t)__builtin_clz(um) : 1u);
+        if (shared) {
+            PieceSum t;
+            for (int w = 0; w < kFinalizeThreads / 64; ++w) {
+                t.bits += red_bits[w]; t.u_max = red_u[0][w] > t.u_max ? red_u[0][w] : t.u_max;
+                t.n_clamped += red_u[1][w]; t.flags |= red_u[2][w];
+            }
+            store_piece_sum(r, t);
+        }
+        h = 0.0;
+        for (int w = 0; w < kFinalizeThreads / 64; ++w) h += red[w];
         r->entropy_bits = h;
     }
 }
@@ -943,12 +1052,13 @@ struct QuantOpts {
 #ifndef GG_LDS_BINS
 #define GG_LDS_BINS 12288
 #endif
-constexpr int kMaxLdsBins = GG_LDS_BINS;   // block-private bins (4 bytes each); higher symbols go to L2 atomics
+constexpr int kMaxLdsBins = GG_LDS_BINS;   // block-private bins (4 bytes each); higher symbols go to atomics on the unit's histogram
 
 template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA, bool FIT = false>
 static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hipStream_t st) {
     QuantArgs a{};
     a.partials = g.ws ? g.partials() : nullptr;
+    a.pieces = g.ws ? g.rate_pieces() : nullptr;
     a.params = o.params; a.single = o.single; a.rate = o.rate_out;
     a.eg_add = 1u << o.eg_k; a.eg_const = 63u - (uint32_t)o.eg_k;
     a.symbols = o.symbols; a.hist = o.hist; a.nbins = o.nbins;
@@ -959,6 +1069,7 @@ static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hip
     // bins are in use), so the whole grid starts together and no block waits for a free slot
     const size_t lds = (size_t)a.lbins * sizeof(uint32_t);
     const RunSplit rs = split_runs(g.n_chunks, resident_blocks(k_quant<T, MODE, RATE, PEN, EXTRA, FIT>, lds, GG_QUANT_BLOCKS_PER_CU));
+    if (RATE && (rs.blocks > kMaxRuns || !a.pieces)) return GG_ERR_WORKSPACE;
     a.chunks_per_block = rs.chunks_per_block;
     o.chunks_per_block_out = rs.chunks_per_block;
     hipLaunchKernelGGL((k_quant<T, MODE, RATE, PEN, EXTRA, FIT>), dim3((unsigned)rs.blocks), dim3(kBlock), lds, st, g.sv,
@@ -1001,9 +1112,21 @@ static int launch_quant(const Geometry &g, const void *x, int dtype, QuantOpts &
 }
 
 
-static int launch_rate_finalize(const Geometry &g, gg_rate_t *rate, const uint64_t *hist, int32_t nbins, hipStream_t st) {
-    if (g.S == 0) return GG_OK;
-    hipLaunchKernelGGL(k_rate_finalize, dim3((unsigned)g.S), dim3(hist ? kFinalizeThreads : 64), 0, st, rate, hist, nbins);
+// after a rate sweep: fold the run slots of shared units into their records; with a histogram also the entropy
+static int launch_rate_finalize(const Geometry &g, gg_rate_t *rate, const uint64_t *hist, int32_t nbins, int32_t cpb,
+                                hipStream_t st) {
+    if (g.S == 0 || g.n_chunks == 0) return GG_OK;
+    if (hist) {
+        hipLaunchKernelGGL(k_rate_finalize, dim3((unsigned)g.S), dim3(kFinalizeThreads), 0, st, g.sv, g.rate_pieces(), cpb, rate,
+                           hist, nbins);
+        return check_launch();
+    }
+    if (g.n_chunks <= cpb) return GG_OK;                 // a single run: nothing is shared
+    if (g.S >= kManyUnits)
+        hipLaunchKernelGGL(k_rate_reduce_lanes, dim3((unsigned)((g.S + 63) / 64)), dim3(64), 0, st, g.sv, g.rate_pieces(), cpb,
+                           rate);
+    else
+        hipLaunchKernelGGL(k_rate_reduce, dim3((unsigned)g.S), dim3(kBlock), 0, st, g.sv, g.rate_pieces(), cpb, rate);
     return check_launch();
 }
 
@@ -1078,8 +1201,7 @@ static int run_second_sweep(const Geometry &g, const void *x, int dtype, QuantOp
     if (o.rate || o.pen) {
         if ((rc = launch_quant(g, x, dtype, o, st)) != GG_OK) return rc;
     }
-    // without a histogram the sweep's integer atomics leave the rate records final; the entropy needs a pass over the bins
-    if (o.rate && o.hist) return launch_rate_finalize(g, o.rate_out, o.hist, o.nbins, st);
+    if (o.rate) return launch_rate_finalize(g, o.rate_out, o.hist, o.nbins, o.chunks_per_block_out, st);
     return GG_OK;
 }
 
