@@ -107,9 +107,26 @@ __global__ __launch_bounds__(kBlock) void k_fit_partials(SegView sv, const T *__
 }
 
 // log of the moment ratio rho(b) = Gamma(2/b)^2 / (Gamma(1/b) Gamma(3/b)) of a GGD (from Eq. 1, 3)
-__device__ __forceinline__ double log_rho(double b) {
+__device__ __forceinline__ double log_rho(double b, double &g1_minus_g3) {
     const double r = 1.0 / b;
-    return 2.0 * lgamma_pos(2.0 * r) - lgamma_pos(r) - lgamma_pos(3.0 * r);
+    const double g1 = lgamma_pos(r), g3 = lgamma_pos(3.0 * r);
+    g1_minus_g3 = g1 - g3;      // the log of the scale factor of Eq. 2 comes for free
+    return 2.0 * lgamma_pos(2.0 * r) - g1 - g3;
+}
+__device__ __forceinline__ double log_rho(double b) { double unused; return log_rho(b, unused); }
+
+// cubic Lagrange through (xs[k], ys[k]), k = 0..3, evaluated at x
+__device__ __forceinline__ double lagrange4(const double (&xs)[4], const double (&ys)[4], double x) {
+    double acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        double p = ys[k];
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+            if (m != k) p *= (x - xs[m]) / (xs[k] - xs[m]);
+        acc += p;
+    }
+    return acc;
 }
 
 // log_rho at the ends of the supported shape range, evaluated once on the host
@@ -132,22 +149,35 @@ __device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, cons
     } else if (!(target < sc.lrho_max)) {
         b = GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI;
     } else {
-        // Three rounds of 64 log-spaced candidates shrink the bracket in ln b to ln(400)/65^3 = 2e-5;
-        // the residuals at its two ends are known from the last round, and one secant step between
-        // them lands within 1e-10 (relative) of the root.
+        // Two rounds of 64 log-spaced candidates shrink the bracket in l = ln b to ln(400)/65^2 = 1.4e-3;
+        // the four candidates of the second round around the root then give l by inverse cubic
+        // interpolation (7e-12 relative in b at this spacing) and, through the same points, the log of
+        // the scale factor of Eq. 2.
         double llo = log(GG_BETA_MIN), lhi = log(GG_BETA_MAX);
-        double flo = sc.lrho_min - target, fhi = sc.lrho_max - target;
-        for (int round = 0; round < 3; ++round) {
+        double cand = 0.0, fv = 0.0, a13 = 0.0;
+        int cnt = 0;
+        for (int round = 0; round < 2; ++round) {
             const double step = (lhi - llo) * (1.0 / 65.0);
-            const double cand = llo + step * (double)(lane + 1);
-            const double fv = log_rho(exp(cand)) - target;     // rho increases with b
-            const int cnt = __popcll(__ballot(fv < 0.0));      // candidates below the root: lanes 0..cnt-1
-            const double c_lo = __shfl(cand, cnt > 0 ? cnt - 1 : 0, 64), f_lo = __shfl(fv, cnt > 0 ? cnt - 1 : 0, 64);
-            const double c_hi = __shfl(cand, cnt < 64 ? cnt : 63, 64), f_hi = __shfl(fv, cnt < 64 ? cnt : 63, 64);
-            if (cnt > 0) { llo = c_lo; flo = f_lo; }
-            if (cnt < 64) { lhi = c_hi; fhi = f_hi; }
+            cand = llo + step * (double)(lane + 1);
+            fv = log_rho(exp(cand), a13) - target;             // rho increases with b
+            cnt = __popcll(__ballot(fv < 0.0));                // candidates below the root: lanes 0..cnt-1
+            if (round == 0) {
+                const double c_lo = __shfl(cand, cnt > 0 ? cnt - 1 : 0, 64), c_hi = __shfl(cand, cnt < 64 ? cnt : 63, 64);
+                if (cnt > 0) llo = c_lo;
+                if (cnt < 64) lhi = c_hi;
+            }
         }
-        b = exp(fhi > flo ? llo - flo * (lhi - llo) / (fhi - flo) : 0.5 * (llo + lhi));
+        int j0 = cnt - 2;
+        j0 = j0 < 0 ? 0 : (j0 > 60 ? 60 : j0);
+        double ls[4], fs[4], as[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            ls[k] = __shfl(cand, j0 + k, 64); fs[k] = __shfl(fv, j0 + k, 64); as[k] = __shfl(a13, j0 + k, 64);
+        }
+        const double l = lagrange4(fs, ls, 0.0);
+        f.beta = (float)exp(l);
+        f.alpha = (float)sqrt(m2 * exp(lagrange4(ls, as, l)));   // Eq. 2 with sigma^2 = m2
+        return;
     }
     const double r = 1.0 / b;
     f.beta = (float)b;
@@ -167,20 +197,6 @@ __global__ void k_build_solve_table(double2 *__restrict__ table) {
     const double r = 1.0 / exp(l_min + h * (double)j);
     const double g1 = lgamma_pos(r), g3 = lgamma_pos(3.0 * r);
     table[j] = make_double2(2.0 * lgamma_pos(2.0 * r) - g1 - g3, g1 - g3);
-}
-
-// cubic Lagrange through (xs[k], ys[k]), k = 0..3, evaluated at x
-__device__ __forceinline__ double lagrange4(const double (&xs)[4], const double (&ys)[4], double x) {
-    double acc = 0.0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        double p = ys[k];
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-            if (m != k) p *= (x - xs[m]) / (xs[k] - xs[m]);
-        acc += p;
-    }
-    return acc;
 }
 
 // beta and alpha from the interval index j (table[j].x <= target < table[j+1].x)
@@ -299,7 +315,8 @@ __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *
     if (c1 > c0) {
         // one piece per run that overlaps the unit; lane-strided over runs, ascending: a fixed order
         const int64_t r0 = c0 / chunks_per_block, r1 = (c1 - 1) / chunks_per_block;
-        for (int64_t r = r0 + lane; r <= r1; r += 64) {
+#pragma unroll 8
+        for (int64_t r = r0 + lane; r <= r1; r += 64) {    // loads of several rounds in flight; the order of the sums stays
             const int64_t run_first = r * chunks_per_block;
             const double2 p = partials[run_first > c0 ? run_first : c0];
             s1 += p.x; s2 += p.y;

@@ -167,6 +167,33 @@ def test_lean_rate_kernel_matches_integer_path(gg, dtype, mode):
         check_rate(b, r, f"full delta={delta}", entropy=False)
 
 
+def test_solver_alone_from_the_kernel_s_own_moments(gg):
+    # the moment sums read back from the GPU record go through the oracle's solver: what is left is the
+    # difference of the two root finders (64-way bracketing + inverse cubic vs 200-step bisection)
+    # and the rounding of beta, alpha to fp32
+    shapes = [0.06, 0.1, 0.3, 0.5, 0.8, 1.0, 1.5, 2.0, 3.0, 7.0, 15.0, 19.0]
+    sizes = [200_000] * len(shapes)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    x = torch.cat([make(n, 0.01 * (i + 1), b, seed=100 + i) for i, (n, b) in enumerate(zip(sizes, shapes))])
+    for S_units, fit in ((len(shapes), gg.gg_fit_segmented(x, off, gg.Workspace(x.numel(), len(shapes)))),):
+        rec = gg.fit_records(fit)
+        for s in range(S_units):
+            o = oracle.fit_from_moments(float(rec[s]["sum_abs"]), float(rec[s]["sum_sq"]), int(rec[s]["n"]))
+            assert int(rec[s]["flags"]) == o.flags
+            assert abs(float(rec[s]["beta"]) - o.beta) <= 2e-7 * o.beta, (s, rec[s], o)
+            assert abs(float(rec[s]["alpha"]) - o.alpha) <= 2e-7 * o.alpha, (s, rec[s], o)
+    # single tensor (wave solver) and a many-unit call (tabulated curve): same bar
+    one = gg.fit_records(gg.gg_fit(x[:200_000], gg.Workspace(200_000, 1)))[0]
+    o = oracle.fit_from_moments(float(one["sum_abs"]), float(one["sum_sq"]), int(one["n"]))
+    assert abs(float(one["beta"]) - o.beta) <= 2e-7 * o.beta and abs(float(one["alpha"]) - o.alpha) <= 2e-7 * o.alpha
+    rows, cols = 4800, 500
+    fr = gg.fit_records(gg.gg_fit_rows(x, rows, cols, gg.Workspace(x.numel(), rows)))
+    for r in range(0, rows, 97):
+        o = oracle.fit_from_moments(float(fr[r]["sum_abs"]), float(fr[r]["sum_sq"]), int(fr[r]["n"]))
+        assert abs(float(fr[r]["beta"]) - o.beta) <= 2e-7 * o.beta, (r, fr[r], o)
+        assert abs(float(fr[r]["alpha"]) - o.alpha) <= 2e-7 * o.alpha, (r, fr[r], o)
+
+
 def test_histogram_beyond_lds_bins_and_overflow_bin(gg):
     # activation-like: heavy tail with outliers; symbols far above the LDS-resident bins and above nbins
     x = gg_inputs.make_tensor((300_000,), 0.5, 0.8, seed=2, device=DEV, dtype=torch.bfloat16, outlier_frac=1e-3,
