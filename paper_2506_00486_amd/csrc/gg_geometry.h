@@ -141,7 +141,7 @@ struct RatePiece {
     uint32_t u_max, n_clamped, flags, _pad[3];
 };
 static_assert(sizeof(RatePiece) == 32, "two 16-byte stores");
-constexpr int64_t kMaxRuns = 256 * 64;   // blocks of one sweep (resident blocks: at most 8 per compute unit)
+constexpr int64_t kMaxRuns = 256 * 64;   // blocks of one reducing sweep (8 resident, or 64 with a written stream, per compute unit)
 
 struct WsLayout {
     size_t off_bytes, params_bytes, partials_bytes, pieces_bytes, table_bytes, total;   // off_bytes: offsets + chunk prefix

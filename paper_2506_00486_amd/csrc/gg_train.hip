@@ -546,7 +546,12 @@ static SlopeArgs slope_args(const Geometry &g, int eg_k, int blocks_per_cu, unsi
     SlopeArgs a{};
     a.eg_add = 1u << eg_k;
     a.n_chunks = g.n_chunks;
+#ifdef GG_TRAIN_RUNS
     const RunSplit rs = split_runs(g.n_chunks, blocks_per_cu);
+#else
+    (void)blocks_per_cu;
+    const RunSplit rs{g.n_chunks, 1};     // element-wise kernels: many short blocks (one chunk each) stream fastest
+#endif
     a.chunks_per_block = rs.chunks_per_block;
     blocks_out = (unsigned)rs.blocks;
     return a;
