@@ -73,6 +73,15 @@ __device__ __forceinline__ int64_t unit_end(const SegView &sv, int seg) {
 
 // Walks the consecutive chunks [first, last) a block owns; the unit table is searched only when
 // the walk crosses into another unit.
+// Element-wise sweeps let `parts` blocks share a chunk: part p takes elements [p, p+1) * kChunk/parts of it.
+__device__ __forceinline__ bool chunk_part(int64_t start, int len, int part, int parts, int64_t &pstart, int &plen) {
+    const int piece = kChunk / parts, lo = part * piece;
+    if (lo >= len) return false;
+    pstart = start + lo;
+    plen = len - lo < piece ? len - lo : piece;
+    return true;
+}
+
 struct RunCursor {
     ChunkLoc L;
     int64_t chunk, last, seg_chunks;

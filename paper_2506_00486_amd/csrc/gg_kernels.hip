@@ -422,6 +422,7 @@ struct QuantArgs {
     // work split
     int64_t n_chunks;
     int32_t chunks_per_block;
+    int32_t parts;            // element-wise sweeps: blocks per chunk
 };
 
 constexpr int32_t kQLimI = 1 << 30;   // |q| <= 2^30
@@ -611,6 +612,24 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
     __shared__ uint32_t red[4][kWaves];
     __shared__ double redd[2][kWaves];
     const int tid = threadIdx.x;
+    if constexpr (!RATE && !FIT) {
+        // element-wise (penalty only): many short blocks, `parts` of them per chunk, nothing to combine
+        const int64_t chunk = blockIdx.x / a.parts;
+        if (chunk >= a.n_chunks) return;
+        const ChunkLoc L = locate(sv, chunk);
+        int64_t start; int len;
+        if (!chunk_part(L.start, L.len, (int)(blockIdx.x - chunk * a.parts), a.parts, start, len)) return;
+        QuantBody<MODE, RATE, PEN, EXTRA, FIT> body;
+        body.eg_add = a.eg_add; body.symbols = nullptr; body.grad = a.grad; body.accumulate = a.accumulate;
+        body.lds_hist = nullptr; body.ghist = nullptr; body.last_bin = 0; body.lbins = 0; body.hist_live = false;
+        const SegParam P = a.params ? a.params[L.seg] : a.single;
+        body.inv_delta = P.inv_delta; body.inv_alpha = P.inv_alpha; body.beta_m1 = P.beta_m1;
+        body.pen_coef = P.pen_coef; body.pen_live = !(P.flags & kPenZero);
+        // 4096 elements per block at the default split: four loads per lane, all issued at once
+        if constexpr (sizeof(T) == 2) process_chunk<ElemBf16x4, 4>(x, start, len, body);
+        else process_chunk<Elem<T>, 4>(x, start, len, body);
+        return;
+    }
     const int64_t first = (int64_t)blockIdx.x * a.chunks_per_block;
     int64_t last = first + a.chunks_per_block;
     if (last > a.n_chunks) last = a.n_chunks;
@@ -1066,8 +1085,8 @@ struct QuantOpts {
     int32_t chunks_per_block_out = 1;  // the run length the sweep used (the fit finalisation needs it)
 };
 
-#ifndef GG_SHORT_BLOCKS
-#define GG_SHORT_BLOCKS 1   // tuning: 0 = element-wise sweeps use resident runs too
+#ifndef GG_PEN_PARTS
+#define GG_PEN_PARTS 4   // element-wise sweeps: blocks per chunk of 16384 elements
 #endif
 #ifndef GG_PEN_RUNS_PER_CU
 #define GG_PEN_RUNS_PER_CU 64
@@ -1091,11 +1110,16 @@ static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hip
     // one run per block that can be resident at once (registers, and LDS when block-private histogram
     // bins are in use), so the whole grid starts together and no block waits for a free slot
     const size_t lds = (size_t)a.lbins * sizeof(uint32_t);
-    // A sweep that only writes per-element results (no sums to combine) runs fastest as many short blocks, one
-    // chunk each: 5.4 against 5.1 TB/s for a read + write stream on MI355X.  Sweeps that reduce keep one run
-    // per resident block (their per-block epilogue costs more than the better balance gains).
+    // A sweep that only writes per-element results (no sums to combine) runs fastest as many short blocks: a
+    // plain copy reaches 5.8 TB/s with 16 KiB per block against 5.1 TB/s with resident runs on MI355X.  Sweeps
+    // that reduce keep one run per resident block (their per-block epilogue costs more than the balance gains).
     RunSplit rs;
-    if (!RATE && !FIT && GG_SHORT_BLOCKS) rs = RunSplit{g.n_chunks, 1};
+    a.parts = 1;
+    if (!RATE && !FIT) {
+        a.parts = GG_PEN_PARTS;      // 4096 elements per block = 256 lanes x 4 loads x 4 elements
+        if (g.n_chunks > 2147483647LL / a.parts) return GG_ERR_INVALID_ARG;
+        rs = RunSplit{g.n_chunks * a.parts, 1};
+    }
     else if (PEN) rs = split_runs(g.n_chunks, GG_PEN_RUNS_PER_CU);   // sums and a written stream: in between (measured 8..64)
     else rs = split_runs(g.n_chunks, resident_blocks(k_quant<T, MODE, RATE, PEN, EXTRA, FIT>, lds, GG_QUANT_BLOCKS_PER_CU));
     if (RATE && (rs.blocks > kMaxRuns || !a.pieces)) return GG_ERR_WORKSPACE;

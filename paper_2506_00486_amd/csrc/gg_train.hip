@@ -45,7 +45,7 @@ struct SlopeArgs {
     UnitCoef single;
     uint32_t eg_add;
     int64_t n_chunks;
-    int32_t chunks_per_block;
+    int32_t parts;           // blocks that share one chunk (the grid has n_chunks * parts blocks)
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -72,22 +72,16 @@ struct RateGradBody {
 template <typename E>
 __global__ __launch_bounds__(kBlock) void k_rate_grad(SegView sv, const typename E::type *__restrict__ x, SlopeArgs a,
                                                       float *__restrict__ grad, int accumulate) {
-    const int64_t first = (int64_t)blockIdx.x * a.chunks_per_block;
-    int64_t last = first + a.chunks_per_block;
-    if (last > a.n_chunks) last = a.n_chunks;
-    if (first >= last) return;
+    const int64_t chunk = blockIdx.x / a.parts;
+    if (chunk >= a.n_chunks) return;
+    const ChunkLoc L = locate(sv, chunk);
+    int64_t start; int len;
+    if (!chunk_part(L.start, L.len, (int)(blockIdx.x - chunk * a.parts), a.parts, start, len)) return;
     RateGradBody body;
     body.eg_add = a.eg_add; body.grad = grad; body.accumulate = accumulate;
-    int seg = -1;
-    RunCursor cur;
-    for (cur.init(sv, first, last); cur.valid(); cur.next(sv)) {
-        if (cur.L.seg != seg) {
-            seg = cur.L.seg;
-            const UnitCoef uc = a.units ? a.units[seg] : a.single;
-            body.inv_delta = uc.inv_delta; body.coef = uc.coef;
-        }
-        process_chunk<E, 8>(x, cur.L.start, cur.L.len, body);
-    }
+    const UnitCoef uc = a.units ? a.units[L.seg] : a.single;
+    body.inv_delta = uc.inv_delta; body.coef = uc.coef;
+    process_chunk<E, 4>(x, start, len, body);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -131,23 +125,17 @@ struct GctScalars { float eta, inv_eta, lambda, eps; int first_step; };
 
 __global__ __launch_bounds__(kBlock) void k_gct_update(SegView sv, const float *__restrict__ g, SlopeArgs a, GctScalars sc,
                                                        float *__restrict__ w, float *__restrict__ ghat_prev) {
-    const int64_t first = (int64_t)blockIdx.x * a.chunks_per_block;
-    int64_t last = first + a.chunks_per_block;
-    if (last > a.n_chunks) last = a.n_chunks;
-    if (first >= last) return;
+    const int64_t chunk = blockIdx.x / a.parts;
+    if (chunk >= a.n_chunks) return;
+    const ChunkLoc L = locate(sv, chunk);
+    int64_t start; int len;
+    if (!chunk_part(L.start, L.len, (int)(blockIdx.x - chunk * a.parts), a.parts, start, len)) return;
     GctBody body;
     body.eg_add = a.eg_add; body.eta = sc.eta; body.inv_eta = sc.inv_eta; body.lambda = sc.lambda; body.eps = sc.eps;
     body.first_step = sc.first_step; body.w = w; body.ghat_prev = ghat_prev;
-    int seg = -1;
-    RunCursor cur;
-    for (cur.init(sv, first, last); cur.valid(); cur.next(sv)) {
-        if (cur.L.seg != seg) {
-            seg = cur.L.seg;
-            const UnitCoef uc = a.units ? a.units[seg] : a.single;
-            body.inv_delta = uc.inv_delta; body.coef = uc.coef;
-        }
-        process_chunk<Elem<float>, 4>(g, cur.L.start, cur.L.len, body);
-    }
+    const UnitCoef uc = a.units ? a.units[L.seg] : a.single;
+    body.inv_delta = uc.inv_delta; body.coef = uc.coef;
+    process_chunk<Elem<float>, 4>(g, start, len, body);
 }
 
 // per-unit 1/Delta and slope coefficient from device steps; a unit without a usable step gets 0 (no rate term)
@@ -542,19 +530,19 @@ __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ s
 // ---------------------------------------------------------------------------------------------
 // host
 // ---------------------------------------------------------------------------------------------
-static SlopeArgs slope_args(const Geometry &g, int eg_k, int blocks_per_cu, unsigned &blocks_out) {
-    SlopeArgs a{};
+// Element-wise kernels run as many short blocks (one read + write stream each): `parts` blocks per chunk,
+// so that a block issues all its loads at once.
+#ifndef GG_TRAIN_PARTS_F32
+#define GG_TRAIN_PARTS_F32 4      // 4096 elements per block = 256 lanes x 4 loads x 4 elements
+#endif
+static int slope_args(const Geometry &g, int eg_k, int parts, SlopeArgs &a, unsigned &blocks_out) {
+    a = SlopeArgs{};
     a.eg_add = 1u << eg_k;
     a.n_chunks = g.n_chunks;
-#ifdef GG_TRAIN_RUNS
-    const RunSplit rs = split_runs(g.n_chunks, blocks_per_cu);
-#else
-    (void)blocks_per_cu;
-    const RunSplit rs{g.n_chunks, 1};     // element-wise kernels: many short blocks (one chunk each) stream fastest
-#endif
-    a.chunks_per_block = rs.chunks_per_block;
-    blocks_out = (unsigned)rs.blocks;
-    return a;
+    a.parts = parts;
+    if (g.n_chunks > 2147483647LL / parts) return GG_ERR_INVALID_ARG;
+    blocks_out = (unsigned)(g.n_chunks * parts);
+    return GG_OK;
 }
 
 static UnitCoef host_coef(float delta, int64_t n_rate, float scale) {
@@ -582,7 +570,8 @@ int gg_rate_grad(const void *x_dev, int dtype, int64_t n, float delta, int eg_k,
     int rc = geometry_uniform(1, n, nullptr, 0, false, g);
     if (rc != GG_OK) return rc;
     unsigned blocks;
-    SlopeArgs a = slope_args(g, eg_k, 8, blocks);
+    SlopeArgs a;
+    if ((rc = slope_args(g, eg_k, GG_TRAIN_PARTS_F32, a, blocks)) != GG_OK) return rc;
     a.single = host_coef(delta, n_rate, scale);
     hipStream_t st = (hipStream_t)stream;
     if (dtype == GG_F32)
@@ -611,7 +600,8 @@ int gg_gct_update(float *w_dev, const float *g_dev, float *ghat_prev_dev, int64_
     Geometry g;
     if ((rc = geometry_uniform(1, n, nullptr, 0, false, g)) != GG_OK) return rc;
     unsigned blocks;
-    SlopeArgs a = slope_args(g, eg_k, 8, blocks);
+    SlopeArgs a;
+    if ((rc = slope_args(g, eg_k, GG_TRAIN_PARTS_F32, a, blocks)) != GG_OK) return rc;
     a.single = host_coef(delta, n_rate, 1.0f);
     GctScalars sc{eta, (float)(1.0 / (double)eta), lambda, eps, first_step ? 1 : 0};
     hipLaunchKernelGGL(k_gct_update, dim3(blocks), dim3(kBlock), 0, (hipStream_t)stream, g.sv, g_dev, a, sc, w_dev,
@@ -634,7 +624,8 @@ int gg_gct_update_segmented(float *w_dev, const float *g_dev, float *ghat_prev_d
     hipLaunchKernelGGL(k_unit_coef, dim3((unsigned)((S + 255) / 256)), dim3(256), 0, st, g.sv, delta_dev, 1.0f, units);
     if ((rc = check_launch()) != GG_OK) return rc;
     unsigned blocks;
-    SlopeArgs a = slope_args(g, eg_k, 8, blocks);
+    SlopeArgs a;
+    if ((rc = slope_args(g, eg_k, GG_TRAIN_PARTS_F32, a, blocks)) != GG_OK) return rc;
     a.units = units;
     GctScalars sc{eta, (float)(1.0 / (double)eta), lambda, eps, first_step ? 1 : 0};
     hipLaunchKernelGGL(k_gct_update, dim3(blocks), dim3(kBlock), 0, st, g.sv, g_dev, a, sc, w_dev, ghat_prev_dev);
