@@ -150,7 +150,7 @@ struct RatePiece {
     uint32_t u_max, n_clamped, flags, _pad[3];
 };
 static_assert(sizeof(RatePiece) == 32, "two 16-byte stores");
-constexpr int64_t kMaxRuns = 256 * 64;   // blocks of one reducing sweep (8 resident, or 64 with a written stream, per compute unit)
+constexpr int64_t kMaxRuns = 256 * 512;  // most blocks a reducing sweep is split into
 
 struct WsLayout {
     size_t off_bytes, params_bytes, partials_bytes, pieces_bytes, table_bytes, total;   // off_bytes: offsets + chunk prefix
@@ -167,7 +167,7 @@ static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
     w.off_at = 256;
     w.params_at = w.off_at + w.off_bytes;
     w.partials_at = w.params_at + w.params_bytes;
-    w.pieces_bytes = (size_t)kMaxRuns * 2 * sizeof(RatePiece);
+    w.pieces_bytes = align_up((size_t)(max_chunks < (size_t)kMaxRuns ? max_chunks : (size_t)kMaxRuns) * 2 * sizeof(RatePiece), 256);   // runs <= chunks
     w.pieces_at = w.partials_at + w.partials_bytes;
     w.table_bytes = align_up((size_t)(kSolveTable + 1) * sizeof(double2), 256);
     w.table_at = w.pieces_at + w.pieces_bytes;
@@ -282,10 +282,6 @@ static RunSplit split_runs(int64_t n_chunks, int blocks_per_cu) {
 // resident blocks of `kernel` per compute unit, capped at `cap` (a pure function of the code object)
 template <typename K>
 static int resident_blocks(K kernel, size_t dyn_lds, int cap) {
-#ifdef GG_RUNS_PER_CU   // tuning builds: a fixed number of runs per compute unit, resident or not
-    (void)kernel; (void)dyn_lds; (void)cap;
-    return GG_RUNS_PER_CU;
-#endif
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, dyn_lds) != hipSuccess || n < 1) n = 1;
     return n < cap ? n : cap;

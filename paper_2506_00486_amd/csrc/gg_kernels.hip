@@ -1030,11 +1030,19 @@ static SolveConst solve_const() {
     return SolveConst{lrho(GG_BETA_MIN), lrho(GG_BETA_MAX)};
 }
 
-#ifndef GG_FIT_BLOCKS_PER_CU
-#define GG_FIT_BLOCKS_PER_CU 8
+// Runs (blocks) per compute unit of the sweeps that reduce.  With no atomics in their epilogues (fit: one
+// slot per piece; rate: records or run slots) several waves of blocks per compute unit balance the finish
+// times better than one resident wave: 32-96 measured 1.5 % faster than 8 on the 1.5 G-element bucket, 128
+// and more slower again.  Sweeps with block-private histogram bins stay at one resident wave: every block
+// has its bins to merge.
+#ifndef GG_FIT_RUNS_PER_CU
+#define GG_FIT_RUNS_PER_CU 32
 #endif
-#ifndef GG_QUANT_BLOCKS_PER_CU
-#define GG_QUANT_BLOCKS_PER_CU 8
+#ifndef GG_RATE_RUNS_PER_CU
+#define GG_RATE_RUNS_PER_CU 64
+#endif
+#ifndef GG_HIST_BLOCKS_PER_CU
+#define GG_HIST_BLOCKS_PER_CU 8
 #endif
 
 // per-unit sums of the pieces written by a sweep that used `chunks_per_block`, and the solve
@@ -1055,9 +1063,7 @@ static int launch_fit_finalize(const Geometry &g, int32_t chunks_per_block, gg_f
 }
 
 static int launch_fit(const Geometry &g, const void *x, int dtype, gg_fit_t *out, const PrepArgs *prep, hipStream_t st) {
-    const int bpc = dtype == GG_BF16 ? resident_blocks(k_fit_partials<bf16_t>, 0, GG_FIT_BLOCKS_PER_CU)
-                                     : resident_blocks(k_fit_partials<float>, 0, GG_FIT_BLOCKS_PER_CU);
-    const RunSplit rs = split_runs(g.n_chunks, bpc);
+    const RunSplit rs = split_runs(g.n_chunks, GG_FIT_RUNS_PER_CU);
     if (g.n_chunks > 0) {
         int rc = by_dtype(dtype, [&](auto *tag) {
             using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
@@ -1088,9 +1094,6 @@ struct QuantOpts {
 #ifndef GG_PEN_PARTS
 #define GG_PEN_PARTS 4   // element-wise sweeps: blocks per chunk of 16384 elements
 #endif
-#ifndef GG_PEN_RUNS_PER_CU
-#define GG_PEN_RUNS_PER_CU 64
-#endif
 #ifndef GG_LDS_BINS
 #define GG_LDS_BINS 12288
 #endif
@@ -1107,8 +1110,6 @@ static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hip
     a.lbins = o.hist ? (o.nbins < kMaxLdsBins ? o.nbins : kMaxLdsBins) : 0;
     a.grad = o.grad; a.accumulate = o.accumulate;
     a.n_chunks = g.n_chunks;
-    // one run per block that can be resident at once (registers, and LDS when block-private histogram
-    // bins are in use), so the whole grid starts together and no block waits for a free slot
     const size_t lds = (size_t)a.lbins * sizeof(uint32_t);
     // A sweep that only writes per-element results (no sums to combine) runs fastest as many short blocks: a
     // plain copy reaches 5.8 TB/s with 16 KiB per block against 5.1 TB/s with resident runs on MI355X.  Sweeps
@@ -1120,8 +1121,8 @@ static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hip
         if (g.n_chunks > 2147483647LL / a.parts) return GG_ERR_INVALID_ARG;
         rs = RunSplit{g.n_chunks * a.parts, 1};
     }
-    else if (PEN) rs = split_runs(g.n_chunks, GG_PEN_RUNS_PER_CU);   // sums and a written stream: in between (measured 8..64)
-    else rs = split_runs(g.n_chunks, resident_blocks(k_quant<T, MODE, RATE, PEN, EXTRA, FIT>, lds, GG_QUANT_BLOCKS_PER_CU));
+    else if (lds > 0) rs = split_runs(g.n_chunks, resident_blocks(k_quant<T, MODE, RATE, PEN, EXTRA, FIT>, lds, GG_HIST_BLOCKS_PER_CU));
+    else rs = split_runs(g.n_chunks, GG_RATE_RUNS_PER_CU);
     if (RATE && (rs.blocks > kMaxRuns || !a.pieces)) return GG_ERR_WORKSPACE;
     a.chunks_per_block = rs.chunks_per_block;
     o.chunks_per_block_out = rs.chunks_per_block;
