@@ -674,13 +674,28 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
         if constexpr (RATE) {
             if (piece_seg >= 0) {
                 constexpr bool kExp0 = decltype(body)::kExp0;
-                const uint64_t lsum = block_reduce((uint64_t)(kExp0 ? body.exp_sum : body.clz_sum), OpAdd(), red64);
-                const uint32_t um = block_reduce(kExp0 ? body.exp0_u_max() : body.u_max, OpMax(), red[0]);
-                const uint32_t nan = block_reduce((uint32_t)body.nan_seen, OpOr(), red[1]);
-                uint32_t ncl = 0, nlast = 0;
+                // wave results of all sums through LDS at once: one barrier, every thread combines in wave order
+                const uint64_t lsum_w = wave_reduce((uint64_t)(kExp0 ? body.exp_sum : body.clz_sum), OpAdd());
+                const uint32_t um_w = wave_reduce(kExp0 ? body.exp0_u_max() : body.u_max, OpMax());
+                const uint32_t nan_w = wave_reduce((uint32_t)body.nan_seen, OpOr());
+                uint32_t ncl_w = 0, nlast_w = 0;
                 if constexpr (EXTRA) {
-                    ncl = block_reduce(body.n_clamped, OpAdd(), red[2]);
-                    nlast = block_reduce(body.n_last, OpAdd(), red[3]);
+                    ncl_w = wave_reduce(body.n_clamped, OpAdd());
+                    nlast_w = wave_reduce(body.n_last, OpAdd());
+                }
+                if ((tid & 63) == 0) {
+                    const int w = tid >> 6;
+                    red64[w] = lsum_w; red[0][w] = um_w; red[1][w] = nan_w;
+                    if constexpr (EXTRA) { red[2][w] = ncl_w; red[3][w] = nlast_w; }
+                }
+                __syncthreads();
+                uint64_t lsum = red64[0];
+                uint32_t um = red[0][0], nan = red[1][0], ncl = 0, nlast = 0;
+                if constexpr (EXTRA) { ncl = red[2][0]; nlast = red[3][0]; }
+#pragma unroll
+                for (int w = 1; w < kWaves; ++w) {
+                    lsum += red64[w]; um = red[0][w] > um ? red[0][w] : um; nan |= red[1][w];
+                    if constexpr (EXTRA) { ncl += red[2][w]; nlast += red[3][w]; }
                 }
                 if (tid == 0 && rate_live) {
                     // sum of 63-k-2 clz(u+2^k), or with k = 0 on the exponent path of 2e-251
@@ -720,8 +735,8 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
                             lds_hist[b] = 0;
                         }
                     }
-                    __syncthreads();
                 }
+                __syncthreads();   // the LDS slots (and bins) are free for the next piece
             }
         }
         body.clz_sum = 0; body.u_max = 0; body.n_clamped = 0; body.n_last = 0; body.nan_seen = false;
