@@ -115,18 +115,26 @@ __device__ __forceinline__ double log_rho(double b, double &g1_minus_g3) {
 }
 __device__ __forceinline__ double log_rho(double b) { double unused; return log_rho(b, unused); }
 
-// cubic Lagrange through (xs[k], ys[k]), k = 0..3, evaluated at x
+// cubic Lagrange through (xs[k], ys[k]), k = 0..3, evaluated at x: one division per node
 __device__ __forceinline__ double lagrange4(const double (&xs)[4], const double (&ys)[4], double x) {
     double acc = 0.0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        double p = ys[k];
+        double num = ys[k], den = 1.0;
 #pragma unroll
         for (int m = 0; m < 4; ++m)
-            if (m != k) p *= (x - xs[m]) / (xs[k] - xs[m]);
-        acc += p;
+            if (m != k) { num *= x - xs[m]; den *= xs[k] - xs[m]; }
+        acc += num / den;
     }
     return acc;
+}
+
+// the same for equally spaced nodes x0, x0 + h, x0 + 2h, x0 + 3h: the denominators are -6, 2, -2, 6 times h^3
+__device__ __forceinline__ double lagrange4_uniform(double x0, double h, const double (&ys)[4], double x) {
+    const double t = (x - x0) / h;                     // node k sits at t = k
+    const double t0 = t, t1 = t - 1.0, t2 = t - 2.0, t3 = t - 3.0;
+    return ys[0] * (t1 * t2 * t3) * (-1.0 / 6.0) + ys[1] * (t0 * t2 * t3) * 0.5 + ys[2] * (t0 * t1 * t3) * (-0.5) +
+           ys[3] * (t0 * t1 * t2) * (1.0 / 6.0);
 }
 
 // log_rho at the ends of the supported shape range, evaluated once on the host
@@ -176,7 +184,7 @@ __device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, cons
         }
         const double l = lagrange4(fs, ls, 0.0);
         f.beta = (float)exp(l);
-        f.alpha = (float)sqrt(m2 * exp(lagrange4(ls, as, l)));   // Eq. 2 with sigma^2 = m2
+        f.alpha = (float)sqrt(m2 * exp(lagrange4_uniform(ls[0], ls[1] - ls[0], as, l)));   // Eq. 2 with sigma^2 = m2
         return;
     }
     const double r = 1.0 / b;
@@ -199,21 +207,34 @@ __global__ void k_build_solve_table(double2 *__restrict__ table) {
     table[j] = make_double2(2.0 * lgamma_pos(2.0 * r) - g1 - g3, g1 - g3);
 }
 
-// beta and alpha from the interval index j (table[j].x <= target < table[j+1].x)
+// beta and alpha from four consecutive table points j0 .. j0+3 around the root
+__device__ __forceinline__ void finish_from_points(int j0, const double (&fs)[4], const double (&as)[4], double target, double m2,
+                                                   gg_fit_t &f) {
+    const double l_min = log(GG_BETA_MIN), h = (log(GG_BETA_MAX) - l_min) / (double)kSolveTable;
+    double ls[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) ls[k] = l_min + h * (double)(j0 + k);
+    const double l = lagrange4(fs, ls, target);          // inverse interpolation: l as a function of log rho
+    f.beta = (float)exp(l);
+    f.alpha = (float)sqrt(m2 * exp(lagrange4_uniform(ls[0], h, as, l)));   // Eq. 2 with sigma^2 = m2
+}
+
+// first of the four points used for the interval j (table[j].x <= target < table[j+1].x)
+__device__ __forceinline__ int first_point(int j) {
+    const int j0 = j - 1;
+    return j0 < 0 ? 0 : (j0 > kSolveTable - 3 ? kSolveTable - 3 : j0);
+}
+
 __device__ __forceinline__ void finish_from_table(const double2 *__restrict__ table, int j, double target, double m2,
                                                   gg_fit_t &f) {
-    const double l_min = log(GG_BETA_MIN), h = (log(GG_BETA_MAX) - l_min) / (double)kSolveTable;
-    int j0 = j - 1;
-    j0 = j0 < 0 ? 0 : (j0 > kSolveTable - 3 ? kSolveTable - 3 : j0);
-    double ls[4], fs[4], as[4];
+    const int j0 = first_point(j);
+    double fs[4], as[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const double2 t = table[j0 + k];
-        ls[k] = l_min + h * (double)(j0 + k); fs[k] = t.x; as[k] = t.y;
+        fs[k] = t.x; as[k] = t.y;
     }
-    const double l = lagrange4(fs, ls, target);          // inverse interpolation: l as a function of log rho
-    f.beta = (float)exp(l);
-    f.alpha = (float)sqrt(m2 * exp(lagrange4(ls, as, l)));   // Eq. 2 with sigma^2 = m2
+    finish_from_points(j0, fs, as, target, m2, f);
 }
 
 // common head of the table solvers; returns true when the root has to be searched
@@ -260,9 +281,18 @@ __device__ __forceinline__ void solve_fit_table_wave(double s1, double s2, uint6
     int c1 = __popcll(__ballot(table[64 * lane].x <= target));
     c1 = c1 < 1 ? 1 : c1;
     const int coarse = 64 * (c1 - 1);
-    int c2 = __popcll(__ballot(table[coarse + lane].x <= target));
+    const double2 t2 = table[coarse + lane];
+    int c2 = __popcll(__ballot(t2.x <= target));
     c2 = c2 < 1 ? 1 : c2;
-    finish_from_table(table, coarse + c2 - 1, target, m2, f);
+    const int j0 = first_point(coarse + c2 - 1);
+    if (j0 >= coarse && j0 + 3 <= coarse + 63) {          // the four points are in this round's lanes
+        double fs[4], as[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { fs[k] = __shfl(t2.x, j0 - coarse + k, 64); as[k] = __shfl(t2.y, j0 - coarse + k, 64); }
+        finish_from_points(j0, fs, as, target, m2, f);
+    } else {
+        finish_from_table(table, coarse + c2 - 1, target, m2, f);
+    }
 }
 
 // where the step and the penalty parameters of a unit come from
