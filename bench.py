@@ -280,6 +280,15 @@ def main():
         step_dec()
         _, ms_d = time_steps(step_dec, 10, torch)
         assert torch.equal(back, sym)
+        d_enc = float(frec["alpha"][0]) / 16.0
+
+        def step_enc_t():
+            gg.gg_eg_encode_tensor(flat[:m], d_enc, 0, buffers=bufs)
+
+        step_enc_t()
+        _, ms_t = time_steps(step_enc_t, 10, torch)
+        assert int(bufs[2].item()) == bits
+        extra["eg_encode_tensor"] = {"elements": m, "ms": round(ms_t, 4), "Gelem/s": round(m / ms_t / 1e6, 2)}
         extra["eg_encode"] = {"symbols": m, "stream_bits": bits, "ms": round(ms_e, 4), "Gsymbols/s": round(m / ms_e / 1e6, 2)}
         extra["eg_decode"] = {"symbols": m, "ms": round(ms_d, 4), "Gsymbols/s": round(m / ms_d / 1e6, 2)}
         del back, stream_e, index_e, bufs

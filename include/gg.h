@@ -220,6 +220,13 @@ int gg_eg_encode(const int32_t *symbols_dev, int64_t n, int eg_k, uint8_t *strea
                  uint64_t *block_offsets_dev, uint64_t *total_bits_dev, void *stream);
 int gg_eg_decode(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, int64_t n, int eg_k,
                  int32_t *symbols_dev, void *stream);
+/* The same stream straight from a tensor: symbol i is the quantised x_i (the rate sweep's arithmetic: one
+ * fp32 product with 1/delta, NaN -> 0, clamp to +-2^30, GG_FLOOR or GG_NEAREST_EVEN), so the stream is bit for
+ * bit what gg_quantize_rate's symbols would give and its length the eg_bits of that call, with no symbol
+ * array in memory.  x_dev 16-byte aligned, delta > 0 and finite; buffers as for gg_eg_encode. */
+int gg_eg_encode_tensor(const void *x_dev, int dtype, int64_t n, float delta, int round_mode, int eg_k,
+                        uint8_t *stream_dev, uint64_t stream_bytes, uint64_t *block_offsets_dev,
+                        uint64_t *total_bits_dev, void *stream);
 
 /* Host helper: mean Huffman code length in bits/symbol of a histogram (the HM column of the paper's
  * tables, Sec. 5.1); 0 for an empty histogram, 1 when a single symbol occurs. */

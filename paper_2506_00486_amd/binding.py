@@ -75,6 +75,7 @@ def lib():
             "gg_gct_update_segmented": (ci, [vp, vp, vp, vp, i32, vp, f32, f32, f32, ci, ci, vp, sz, vp]),
             "gg_eg_workspace_bytes": (ci, [i64, C.POINTER(sz)]),
             "gg_eg_encode": (ci, [vp, i64, ci, vp, u64, vp, vp, vp]),
+            "gg_eg_encode_tensor": (ci, [vp, ci, i64, f32, ci, ci, vp, u64, vp, vp, vp]),
             "gg_eg_decode": (ci, [vp, vp, i64, ci, vp, vp]),
             "gg_huffman_mean_bits": (ci, [vp, i32, C.POINTER(f64)]),
         }
@@ -337,6 +338,20 @@ def gg_eg_encode(symbols: torch.Tensor, eg_k: int = 0, capacity_bytes: Optional[
         stream, work, total = buffers
     _check(lib().gg_eg_encode(_dev(symbols), n, eg_k, _dev(stream), stream.numel(), _dev(work), _dev(total), _stream()),
            "gg_eg_encode")
+    tiles = (n + GG_EG_TILE - 1) // GG_EG_TILE
+    return stream, work[: tiles + 1], (int(total.item()) if buffers is None else None)
+
+
+def gg_eg_encode_tensor(x: torch.Tensor, delta: float, eg_k: int = 0, round_mode: int = GG_FLOOR,
+                        capacity_bytes: Optional[int] = None, buffers=None):
+    """Quantise and encode in one go (no symbol array): returns (stream, index, total_bits) as gg_eg_encode."""
+    n = x.numel()
+    if buffers is None:
+        stream, work, total = eg_buffers(n, capacity_bytes, x.device)
+    else:
+        stream, work, total = buffers
+    _check(lib().gg_eg_encode_tensor(_dev(x), _dtype_code(x), n, _f32(delta), round_mode, eg_k, _dev(stream),
+                                     stream.numel(), _dev(work), _dev(total), _stream()), "gg_eg_encode_tensor")
     tiles = (n + GG_EG_TILE - 1) // GG_EG_TILE
     return stream, work[: tiles + 1], (int(total.item()) if buffers is None else None)
 

@@ -181,9 +181,55 @@ __device__ __forceinline__ uint32_t eg_len(uint32_t v, int eg_k) {   // v = u + 
     return 63u - (uint32_t)eg_k - 2u * (uint32_t)__builtin_clz(v);
 }
 
+// Where the coder's symbols come from: an int32 array (as written by the rate sweep), or a tensor quantised
+// on the fly with the rate sweep's arithmetic (one fp32 product, NaN -> 0, clamp to +-2^30, floor or
+// nearest-even), so that a tensor goes to its bit stream without a symbol array in between.
+struct SymbolArray {
+    const int32_t *q;
+    using raw4 = gg_i4;
+    __device__ __forceinline__ raw4 load4(int64_t i) const { return load_vec<gg_i4, true>(reinterpret_cast<const gg_i4 *>(q + i)); }
+    __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o) const { o[0] = r.x; o[1] = r.y; o[2] = r.z; o[3] = r.w; }
+    __device__ __forceinline__ int32_t one(int64_t i) const { return q[i]; }
+};
+
+template <bool NEAREST>
+__device__ __forceinline__ int32_t quantise(float x, float inv_delta) {
+    const float t = x * inv_delta;
+    int32_t m;
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(m) : "v"(NEAREST ? rintf(-t) : ceilf(-t)));   // m = -q; NaN -> 0, saturating
+    m = m < -kQLimT ? -kQLimT : (m > kQLimT ? kQLimT : m);
+    return -m;
+}
+
+template <typename T, bool NEAREST> struct QuantisedTensor;
+template <bool NEAREST> struct QuantisedTensor<float, NEAREST> {
+    const float *x; float inv_delta;
+    using raw4 = gg_f4;
+    __device__ __forceinline__ raw4 load4(int64_t i) const { return load_vec<gg_f4, true>(reinterpret_cast<const gg_f4 *>(x + i)); }
+    __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o) const {
+        o[0] = quantise<NEAREST>(r.x, inv_delta); o[1] = quantise<NEAREST>(r.y, inv_delta);
+        o[2] = quantise<NEAREST>(r.z, inv_delta); o[3] = quantise<NEAREST>(r.w, inv_delta);
+    }
+    __device__ __forceinline__ int32_t one(int64_t i) const { return quantise<NEAREST>(x[i], inv_delta); }
+};
+template <bool NEAREST> struct QuantisedTensor<bf16_t, NEAREST> {
+    const bf16_t *x; float inv_delta;
+    using raw4 = gg_u2;
+    __device__ __forceinline__ raw4 load4(int64_t i) const { return load_vec<gg_u2, true>(reinterpret_cast<const gg_u2 *>(x + i)); }
+    __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o) const {
+        o[0] = quantise<NEAREST>(__uint_as_float(r.x << 16), inv_delta);
+        o[1] = quantise<NEAREST>(__uint_as_float(r.x & 0xffff0000u), inv_delta);
+        o[2] = quantise<NEAREST>(__uint_as_float(r.y << 16), inv_delta);
+        o[3] = quantise<NEAREST>(__uint_as_float(r.y & 0xffff0000u), inv_delta);
+    }
+    __device__ __forceinline__ int32_t one(int64_t i) const {
+        return quantise<NEAREST>(__uint_as_float((uint32_t)x[i].bits << 16), inv_delta);
+    }
+};
+
 // one wave per tile: 8 x 16 bytes per lane in flight
-__global__ __launch_bounds__(kBlock) void k_eg_tile_bits(const int32_t *__restrict__ q, int64_t n, int64_t nb, int eg_k,
-                                                         uint64_t *__restrict__ tile_bits) {
+template <typename Src>
+__global__ __launch_bounds__(kBlock) void k_eg_tile_bits(Src src, int64_t n, int64_t nb, int eg_k, uint64_t *__restrict__ tile_bits) {
     const int lane = threadIdx.x & 63;
     const int64_t tile = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
     if (tile >= nb) return;
@@ -191,16 +237,18 @@ __global__ __launch_bounds__(kBlock) void k_eg_tile_bits(const int32_t *__restri
     const uint32_t add = 1u << eg_k;
     uint32_t bits = 0;
     if (base + kEgBlock <= n) {
-        const gg_i4 *src = reinterpret_cast<const gg_i4 *>(q + base);
-        gg_i4 v[8];
+        typename Src::raw4 v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = load_vec<gg_i4, true>(src + j * 64 + lane);
+        for (int j = 0; j < 8; ++j) v[j] = src.load4(base + (int64_t)(j * 64 + lane) * 4);
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            bits += eg_len(map_q(v[j].x) + add, eg_k) + eg_len(map_q(v[j].y) + add, eg_k) +
-                    eg_len(map_q(v[j].z) + add, eg_k) + eg_len(map_q(v[j].w) + add, eg_k);
+        for (int j = 0; j < 8; ++j) {
+            int32_t q[4];
+            src.conv4(v[j], q);
+            bits += eg_len(map_q(q[0]) + add, eg_k) + eg_len(map_q(q[1]) + add, eg_k) + eg_len(map_q(q[2]) + add, eg_k) +
+                    eg_len(map_q(q[3]) + add, eg_k);
+        }
     } else {
-        for (int64_t i = base + lane; i < n; i += 64) bits += eg_len(map_q(q[i]) + add, eg_k);
+        for (int64_t i = base + lane; i < n; i += 64) bits += eg_len(map_q(src.one(i)) + add, eg_k);
     }
     bits = wave_reduce(bits, OpAdd());
     if (lane == 0) tile_bits[tile] = bits;
@@ -264,24 +312,25 @@ __global__ __launch_bounds__(1024) void k_eg_scan(const uint64_t *__restrict__ s
 
 struct EgSymbols { int32_t q[kEgPerLane]; };
 
-// the eight consecutive symbols of a lane; positions at and beyond n read as "absent" (flag cleared)
-__device__ __forceinline__ EgSymbols eg_load(const int32_t *__restrict__ q, int64_t i0, int64_t n) {
+// the eight consecutive symbols of a lane; positions at and beyond n read as 0
+template <typename Src>
+__device__ __forceinline__ EgSymbols eg_load(const Src &src, int64_t i0, int64_t n) {
     EgSymbols s;
     if (i0 + kEgPerLane <= n) {
-        const gg_i4 a = load_vec<gg_i4, true>(reinterpret_cast<const gg_i4 *>(q + i0));
-        const gg_i4 b = load_vec<gg_i4, true>(reinterpret_cast<const gg_i4 *>(q + i0) + 1);
-        s.q[0] = a.x; s.q[1] = a.y; s.q[2] = a.z; s.q[3] = a.w;
-        s.q[4] = b.x; s.q[5] = b.y; s.q[6] = b.z; s.q[7] = b.w;
+        const typename Src::raw4 a = src.load4(i0), b = src.load4(i0 + 4);
+        src.conv4(a, s.q);
+        src.conv4(b, s.q + 4);
     } else {
 #pragma unroll
-        for (int j = 0; j < kEgPerLane; ++j) s.q[j] = i0 + j < n ? q[i0 + j] : 0;
+        for (int j = 0; j < kEgPerLane; ++j) s.q[j] = i0 + j < n ? src.one(i0 + j) : 0;
     }
     return s;
 }
 
 // A workgroup packs kEgTilesPerBlock consecutive tiles.  All its symbol loads and tile offsets are issued up
 // front, so the only wait for global memory comes once; the words it stores are never waited for.
-__global__ __launch_bounds__(kBlock) void k_eg_encode(const int32_t *__restrict__ q, int64_t n, int64_t nb, int eg_k,
+template <typename Src>
+__global__ __launch_bounds__(kBlock) void k_eg_encode(Src src, int64_t n, int64_t nb, int eg_k,
                                                       const uint64_t *__restrict__ tile_off, uint64_t *__restrict__ index,
                                                       uint32_t *__restrict__ stream, uint64_t capacity_bits) {
     __shared__ uint32_t buf[kEgLdsWords];
@@ -296,13 +345,13 @@ __global__ __launch_bounds__(kBlock) void k_eg_encode(const int32_t *__restrict_
     uint64_t off[kEgTilesPerBlock + 1];
 #pragma unroll
     for (int t = 0; t < kEgTilesPerBlock; ++t)
-        sym[t] = eg_load(q, (tile_first + t) * kEgBlock + (int64_t)tid * kEgPerLane, n);   // all zero past n
+        sym[t] = eg_load(src, (tile_first + t) * kEgBlock + (int64_t)tid * kEgPerLane, n);   // all zero past n
 #pragma unroll
     for (int t = 0; t <= kEgTilesPerBlock; ++t) off[t] = tile_off[t <= tiles ? tile_first + t : tile_first + tiles];
     // the symbols that follow this group's tiles: at most 31 of them reach into the group's last word
     const int64_t peek_i = (tile_first + tiles) * kEgBlock + tid;
     const bool peek_live = tid < 32 && peek_i < n;
-    const int32_t peek_q = peek_live ? q[peek_i] : 0;
+    const int32_t peek_q = peek_live ? src.one(peek_i) : 0;
     for (int i = tid; i < kEgLdsWords; i += kBlock) buf[i] = 0;
     uint32_t carry = 0;       // held by the lane that copied out a tile's last word: bits to start the next tile with
     bool carried = false;     // uniform: the previous tile left its last word to this one
@@ -552,6 +601,46 @@ static UnitCoef host_coef(float delta, int64_t n_rate, float scale) {
     return uc;
 }
 
+// workspace: decoding index (T + 1 entries, T = ceil(n / GG_EG_TILE)) | packing-tile offsets (P + 1) | tile sizes (P)
+static int64_t eg_index_tiles(int64_t n) { return (n + GG_EG_TILE - 1) / GG_EG_TILE; }
+static int64_t eg_pack_tiles(int64_t n) { return (n + kEgBlock - 1) / kEgBlock; }
+
+// the three launches of the coder for any symbol source
+template <typename Src>
+static int eg_encode_launch(const Src &src, int64_t n, int eg_k, uint8_t *stream_dev, uint64_t stream_bytes,
+                            uint64_t *block_offsets_dev, uint64_t *total_bits_dev, hipStream_t st) {
+    const int64_t nb = eg_pack_tiles(n), T = eg_index_tiles(n);
+    if (nb > 2147483647LL * kWaves) return GG_ERR_INVALID_ARG;
+    uint64_t *tile_off = block_offsets_dev + T + 1;
+    uint64_t *sizes = tile_off + nb + 1;
+    int rc;
+    if (nb > 0) {
+        hipLaunchKernelGGL(k_eg_tile_bits<Src>, dim3((unsigned)((nb + kWaves - 1) / kWaves)), dim3(kBlock), 0, st, src, n, nb,
+                           eg_k, sizes);
+        if ((rc = check_launch()) != GG_OK) return rc;
+    }
+    const int64_t groups = nb > 0 ? (nb + kEgScanSeg - 1) / kEgScanSeg : 1;
+    hipLaunchKernelGGL(k_eg_scan, dim3((unsigned)groups), dim3(1024), 0, st, sizes, tile_off, nb, block_offsets_dev + T,
+                       total_bits_dev);
+    if ((rc = check_launch()) != GG_OK) return rc;
+    if (nb > 0) {   // also without room for any stream: this kernel writes the index
+        hipLaunchKernelGGL(k_eg_encode<Src>, dim3((unsigned)((nb + kEgTilesPerBlock - 1) / kEgTilesPerBlock)), dim3(kBlock), 0,
+                           st, src, n, nb, eg_k, tile_off, block_offsets_dev, reinterpret_cast<uint32_t *>(stream_dev),
+                           stream_bytes * 8ull);
+        if ((rc = check_launch()) != GG_OK) return rc;
+    }
+    return GG_OK;
+}
+
+static int check_eg_buffers(int64_t n, int eg_k, const uint8_t *stream_dev, uint64_t stream_bytes,
+                            const uint64_t *block_offsets_dev, const uint64_t *total_bits_dev) {
+    if (n < 0 || eg_k < 0 || eg_k > GG_MAX_EG_K || (stream_bytes & 3u)) return GG_ERR_INVALID_ARG;
+    if (!block_offsets_dev || !aligned8(block_offsets_dev)) return GG_ERR_WORKSPACE;
+    if (total_bits_dev && !aligned8(total_bits_dev)) return GG_ERR_INVALID_ARG;
+    if (stream_bytes && (!stream_dev || (reinterpret_cast<uintptr_t>(stream_dev) & 3u))) return GG_ERR_INVALID_ARG;
+    return GG_OK;
+}
+
 }  // namespace gg
 
 using namespace gg;
@@ -632,10 +721,6 @@ int gg_gct_update_segmented(float *w_dev, const float *g_dev, float *ghat_prev_d
     return check_launch();
 }
 
-// workspace: decoding index (T + 1 entries, T = ceil(n / GG_EG_TILE)) | packing-tile offsets (P + 1) | tile sizes (P)
-static int64_t eg_index_tiles(int64_t n) { return (n + GG_EG_TILE - 1) / GG_EG_TILE; }
-static int64_t eg_pack_tiles(int64_t n) { return (n + kEgBlock - 1) / kEgBlock; }
-
 int gg_eg_workspace_bytes(int64_t n, size_t *bytes_out_host) {
     if (!bytes_out_host || n < 0) return GG_ERR_INVALID_ARG;
     *bytes_out_host = (size_t)(eg_index_tiles(n) + 2 * eg_pack_tiles(n) + 2) * sizeof(uint64_t);
@@ -644,33 +729,36 @@ int gg_eg_workspace_bytes(int64_t n, size_t *bytes_out_host) {
 
 int gg_eg_encode(const int32_t *symbols_dev, int64_t n, int eg_k, uint8_t *stream_dev, uint64_t stream_bytes,
                  uint64_t *block_offsets_dev, uint64_t *total_bits_dev, void *stream) {
-    if (n < 0 || eg_k < 0 || eg_k > GG_MAX_EG_K || (stream_bytes & 3u)) return GG_ERR_INVALID_ARG;
-    if (!block_offsets_dev || !aligned8(block_offsets_dev)) return GG_ERR_WORKSPACE;
-    if (total_bits_dev && !aligned8(total_bits_dev)) return GG_ERR_INVALID_ARG;
-    if (stream_bytes && (!stream_dev || (reinterpret_cast<uintptr_t>(stream_dev) & 3u))) return GG_ERR_INVALID_ARG;
+    int rc = check_eg_buffers(n, eg_k, stream_dev, stream_bytes, block_offsets_dev, total_bits_dev);
+    if (rc != GG_OK) return rc;
     if (n > 0 && (!symbols_dev || !aligned16(symbols_dev))) return GG_ERR_INVALID_ARG;
+    return eg_encode_launch(SymbolArray{symbols_dev}, n, eg_k, stream_dev, stream_bytes, block_offsets_dev, total_bits_dev,
+                            (hipStream_t)stream);
+}
+
+int gg_eg_encode_tensor(const void *x_dev, int dtype, int64_t n, float delta, int round_mode, int eg_k, uint8_t *stream_dev,
+                        uint64_t stream_bytes, uint64_t *block_offsets_dev, uint64_t *total_bits_dev, void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    int rc = check_eg_buffers(n, eg_k, stream_dev, stream_bytes, block_offsets_dev, total_bits_dev);
+    if (rc != GG_OK) return rc;
+    if (!(delta > 0.f) || !std::isfinite(delta)) return GG_ERR_INVALID_ARG;
+    if (round_mode != GG_FLOOR && round_mode != GG_NEAREST_EVEN) return GG_ERR_INVALID_ARG;
+    if (n > 0 && (!x_dev || !aligned16(x_dev))) return GG_ERR_INVALID_ARG;
+    const float inv_delta = (float)(1.0 / (double)delta);
     hipStream_t st = (hipStream_t)stream;
-    const int64_t nb = eg_pack_tiles(n), T = eg_index_tiles(n);
-    if (nb > 2147483647LL * kWaves) return GG_ERR_INVALID_ARG;
-    uint64_t *tile_off = block_offsets_dev + T + 1;
-    uint64_t *sizes = tile_off + nb + 1;
-    int rc;
-    if (nb > 0) {
-        hipLaunchKernelGGL(k_eg_tile_bits, dim3((unsigned)((nb + kWaves - 1) / kWaves)), dim3(kBlock), 0, st, symbols_dev, n,
-                           nb, eg_k, sizes);
-        if ((rc = check_launch()) != GG_OK) return rc;
+    const bool nearest = round_mode == GG_NEAREST_EVEN;
+    if (dtype == GG_F32) {
+        const float *x = static_cast<const float *>(x_dev);
+        return nearest ? eg_encode_launch(QuantisedTensor<float, true>{x, inv_delta}, n, eg_k, stream_dev, stream_bytes,
+                                          block_offsets_dev, total_bits_dev, st)
+                       : eg_encode_launch(QuantisedTensor<float, false>{x, inv_delta}, n, eg_k, stream_dev, stream_bytes,
+                                          block_offsets_dev, total_bits_dev, st);
     }
-    const int64_t groups = nb > 0 ? (nb + kEgScanSeg - 1) / kEgScanSeg : 1;
-    hipLaunchKernelGGL(k_eg_scan, dim3((unsigned)groups), dim3(1024), 0, st, sizes, tile_off, nb, block_offsets_dev + T,
-                       total_bits_dev);
-    if ((rc = check_launch()) != GG_OK) return rc;
-    if (nb > 0) {   // also without room for any stream: this kernel writes the index
-        hipLaunchKernelGGL(k_eg_encode, dim3((unsigned)((nb + kEgTilesPerBlock - 1) / kEgTilesPerBlock)), dim3(kBlock), 0, st,
-                           symbols_dev, n, nb, eg_k, tile_off, block_offsets_dev, reinterpret_cast<uint32_t *>(stream_dev),
-                           stream_bytes * 8ull);
-        if ((rc = check_launch()) != GG_OK) return rc;
-    }
-    return GG_OK;
+    const bf16_t *x = static_cast<const bf16_t *>(x_dev);
+    return nearest ? eg_encode_launch(QuantisedTensor<bf16_t, true>{x, inv_delta}, n, eg_k, stream_dev, stream_bytes,
+                                      block_offsets_dev, total_bits_dev, st)
+                   : eg_encode_launch(QuantisedTensor<bf16_t, false>{x, inv_delta}, n, eg_k, stream_dev, stream_bytes,
+                                      block_offsets_dev, total_bits_dev, st);
 }
 
 int gg_eg_decode(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, int64_t n, int eg_k, int32_t *symbols_dev,

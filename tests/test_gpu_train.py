@@ -224,6 +224,33 @@ def test_eg_stream_orders_and_tile_multiples(gg, k):
         assert torch.equal(gg.gg_eg_decode(stream, index, n, eg_k=k), q)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_eg_stream_straight_from_the_tensor(gg, dtype, mode):
+    # quantise + encode in one call == rate sweep's symbols through the coder == the oracle's stream
+    n = 3 * 8192 + 2048 + 333
+    x = make(n, 0.02, 0.7, seed=31, dtype=dtype)
+    special = torch.tensor([float("nan"), float("inf"), -float("inf"), 1e30, -1e30, 0.0, -0.0, 1e-30, -1e-30, 0.00124999, -0.00125],
+                           device=DEV).to(dtype)
+    x[100:100 + special.numel()] = special
+    x[-special.numel():] = special
+    delta = float(np.float32(0.02) / np.float32(16))
+    ws = gg.Workspace(n, 1)
+    for k in (0, 2):
+        out, _, sym = gg.gg_quantize_rate(x, delta, ws, eg_k=k, round_mode=mode, want_symbols=True)
+        s_ref, i_ref, t_ref = gg.gg_eg_encode(sym, eg_k=k)
+        s_new, i_new, t_new = gg.gg_eg_encode_tensor(x, delta, eg_k=k, round_mode=mode)
+        assert t_new == t_ref == int(gg.rate_records(out)[0]["eg_bits"])
+        nbytes = (t_ref + 7) // 8
+        assert torch.equal(s_new[:nbytes], s_ref[:nbytes]) and torch.equal(i_new, i_ref)
+        r, _, osym = oracle.quantize_rate(host_bits(x), delta, eg_k=k, round_mode=mode, want_symbols=True)
+        u = np.where(osym > 0, 2 * osym.astype(np.int64) - 1, -2 * osym.astype(np.int64)).astype(np.uint32)
+        obuf, obits = oracle.eg_encode(u, k)
+        assert t_new == obits == r.eg_bits
+        assert np.array_equal(s_new.cpu().numpy()[: obuf.size], obuf)
+        assert torch.equal(gg.gg_eg_decode(s_new, i_new, n, eg_k=k), sym)
+
+
 def test_eg_stream_of_longest_codes(gg):
     # every symbol takes 63 bits (k = 0): the decoder's buffered words run out within a step and are topped up
     n = 5000
