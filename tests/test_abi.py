@@ -116,6 +116,18 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.gg_eg_encode(P, 100, 16, P, 1024, P, None, None) == -1                                # k > 15
     assert L.gg_eg_encode(P, 100, 0, P, 1022, P, None, None) == -1                                 # size not a multiple of 4
     assert L.gg_eg_encode(P, 100, 0, P, 1024, None, None, None) == -4                              # no index buffer
+    assert L.gg_eg_encode(P + 4, 100, 0, P, 1024, P, None, None) == -1                             # misaligned symbols
+    assert L.gg_eg_encode(P, 100, 0, P + 2, 1024, P, None, None) == -1                             # misaligned stream
+    assert L.gg_eg_encode_tensor(P, 4, 100, 0.1, 0, 0, P, 1024, P, None, None) == -2               # dtype
+    assert L.gg_eg_encode_tensor(P, 0, 100, 0.0, 0, 0, P, 1024, P, None, None) == -1               # step 0
+    assert L.gg_eg_encode_tensor(P, 0, 100, float("nan"), 0, 0, P, 1024, P, None, None) == -1
+    assert L.gg_eg_encode_tensor(P, 0, 100, 0.1, 3, 0, P, 1024, P, None, None) == -1               # round mode
+    assert L.gg_eg_encode_tensor(P + 8, 1, 100, 0.1, 0, 0, P, 1024, P, None, None) == -1           # misaligned x
+    assert L.gg_eg_encode_tensor(P, 1, 100, 0.1, 0, 0, P, 1024, None, None, None) == -4
+    assert L.gg_eg_decode(P, P, -1, 0, P, None) == -1
+    assert L.gg_eg_decode(P + 1, P, 100, 0, P, None) == -1                                         # misaligned stream
+    assert L.gg_eg_decode(P, P, 100, 0, P + 4, None) == -1                                         # misaligned output
+    assert L.gg_eg_decode(P, P, 0, 0, None, None) == 0                                             # nothing to decode
     out = C.c_double(0)
     assert L.gg_huffman_mean_bits(None, 4, C.byref(out)) == -1
 
