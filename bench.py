@@ -293,6 +293,22 @@ def main():
         extra["eg_decode"] = {"symbols": m, "ms": round(ms_d, 4), "Gsymbols/s": round(m / ms_d / 1e6, 2)}
         del back, stream_e, index_e, bufs
         del sym
+        # the whole bucket, each segment with its own step, straight to one bit stream (what a compressed
+        # gradient exchange would send): its length must be the sum of the segments' eg_bits of the pass
+        rrec = gg.rate_records(rate)
+        bucket_bits = int(rrec["eg_bits"].astype(np.uint64).sum())
+        bbufs = gg.eg_buffers(n, (bucket_bits + 7) // 8, dev)
+
+        def step_enc_b():
+            gg.gg_eg_encode_segmented(flat, off, delta, ws, 0, buffers=bbufs)
+
+        step_enc_b()
+        _, ms_b = time_steps(step_enc_b, 5, torch)
+        assert int(bbufs[2].item()) == bucket_bits
+        extra["eg_encode_segmented_bucket"] = {"elements": n, "stream_bits": bucket_bits, "ms": round(ms_b, 4),
+                                               "Gelem/s": round(n / ms_b / 1e6, 2),
+                                               "bits_per_element": round(bucket_bits / n, 3)}
+        del bbufs
         if args.all:
             extra.update(other_configs(gg, gg_inputs, torch, dev, args))
         out["extra"] = extra

@@ -227,6 +227,14 @@ int gg_eg_decode(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, i
 int gg_eg_encode_tensor(const void *x_dev, int dtype, int64_t n, float delta, int round_mode, int eg_k,
                         uint8_t *stream_dev, uint64_t stream_bytes, uint64_t *block_offsets_dev,
                         uint64_t *total_bits_dev, void *stream);
+/* The same for a flat bucket with one step per unit (delta_dev[S], e.g. from gg_delta_from_fit; offsets as in
+ * gg_fit_segmented): one stream for the whole bucket, equal to the stream of gg_quantize_rate_segmented's
+ * symbols; a unit without a positive finite step contributes symbol 0 for every element.  ws_dev as for the
+ * segmented calls (it receives the unit table). */
+int gg_eg_encode_segmented(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S,
+                           const float *delta_dev, int round_mode, int eg_k, uint8_t *stream_dev,
+                           uint64_t stream_bytes, uint64_t *block_offsets_dev, uint64_t *total_bits_dev,
+                           void *ws_dev, size_t ws_bytes, void *stream);
 
 /* Host helper: mean Huffman code length in bits/symbol of a histogram (the HM column of the paper's
  * tables, Sec. 5.1); 0 for an empty histogram, 1 when a single symbol occurs. */

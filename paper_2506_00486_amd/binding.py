@@ -76,6 +76,7 @@ def lib():
             "gg_eg_workspace_bytes": (ci, [i64, C.POINTER(sz)]),
             "gg_eg_encode": (ci, [vp, i64, ci, vp, u64, vp, vp, vp]),
             "gg_eg_encode_tensor": (ci, [vp, ci, i64, f32, ci, ci, vp, u64, vp, vp, vp]),
+            "gg_eg_encode_segmented": (ci, [vp, ci, vp, i32, vp, ci, ci, vp, u64, vp, vp, vp, sz, vp]),
             "gg_eg_decode": (ci, [vp, vp, i64, ci, vp, vp]),
             "gg_huffman_mean_bits": (ci, [vp, i32, C.POINTER(f64)]),
         }
@@ -352,6 +353,22 @@ def gg_eg_encode_tensor(x: torch.Tensor, delta: float, eg_k: int = 0, round_mode
         stream, work, total = buffers
     _check(lib().gg_eg_encode_tensor(_dev(x), _dtype_code(x), n, _f32(delta), round_mode, eg_k, _dev(stream),
                                      stream.numel(), _dev(work), _dev(total), _stream()), "gg_eg_encode_tensor")
+    tiles = (n + GG_EG_TILE - 1) // GG_EG_TILE
+    return stream, work[: tiles + 1], (int(total.item()) if buffers is None else None)
+
+
+def gg_eg_encode_segmented(x: torch.Tensor, offsets: Sequence[int], delta: torch.Tensor, ws: Workspace, eg_k: int = 0,
+                           round_mode: int = GG_FLOOR, capacity_bytes: Optional[int] = None, buffers=None):
+    """One stream for a flat bucket with a step per unit (device tensor `delta`); returns as gg_eg_encode."""
+    off = _offsets(offsets)
+    n = int(off[-1]) if off.size else 0
+    if buffers is None:
+        stream, work, total = eg_buffers(n, capacity_bytes, x.device)
+    else:
+        stream, work, total = buffers
+    _check(lib().gg_eg_encode_segmented(_dev(x), _dtype_code(x), off.ctypes.data, off.size - 1, _dev(delta), round_mode, eg_k,
+                                        _dev(stream), stream.numel(), _dev(work), _dev(total), ws.ptr, ws.bytes, _stream()),
+           "gg_eg_encode_segmented")
     tiles = (n + GG_EG_TILE - 1) // GG_EG_TILE
     return stream, work[: tiles + 1], (int(total.item()) if buffers is None else None)
 

@@ -184,12 +184,20 @@ __device__ __forceinline__ uint32_t eg_len(uint32_t v, int eg_k) {   // v = u + 
 // Where the coder's symbols come from: an int32 array (as written by the rate sweep), or a tensor quantised
 // on the fly with the rate sweep's arithmetic (one fp32 product, NaN -> 0, clamp to +-2^30, floor or
 // nearest-even), so that a tensor goes to its bit stream without a symbol array in between.
+// A source also says which elements share one set of parameters: `begin(i)` gives the context of element
+// i, `covers(ctx, end)` tells whether it holds unchanged up to element `end`, `one(i, ctx)` moves it on
+// as needed (i must not decrease).  Only the bucket source has more than one context.
+struct NoCtx {};
+
 struct SymbolArray {
     const int32_t *q;
     using raw4 = gg_i4;
+    using Ctx = NoCtx;
+    __device__ __forceinline__ Ctx begin(int64_t) const { return {}; }
+    __device__ __forceinline__ bool covers(const Ctx &, int64_t) const { return true; }
     __device__ __forceinline__ raw4 load4(int64_t i) const { return load_vec<gg_i4, true>(reinterpret_cast<const gg_i4 *>(q + i)); }
-    __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o) const { o[0] = r.x; o[1] = r.y; o[2] = r.z; o[3] = r.w; }
-    __device__ __forceinline__ int32_t one(int64_t i) const { return q[i]; }
+    __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o, const Ctx &) const { o[0] = r.x; o[1] = r.y; o[2] = r.z; o[3] = r.w; }
+    __device__ __forceinline__ int32_t one(int64_t i, Ctx &) const { return q[i]; }
 };
 
 template <bool NEAREST>
@@ -201,29 +209,64 @@ __device__ __forceinline__ int32_t quantise(float x, float inv_delta) {
     return -m;
 }
 
-template <typename T, bool NEAREST> struct QuantisedTensor;
-template <bool NEAREST> struct QuantisedTensor<float, NEAREST> {
-    const float *x; float inv_delta;
+// four consecutive elements of a tensor as raw bits, and their values
+template <typename T> struct Quad;
+template <> struct Quad<float> {
     using raw4 = gg_f4;
-    __device__ __forceinline__ raw4 load4(int64_t i) const { return load_vec<gg_f4, true>(reinterpret_cast<const gg_f4 *>(x + i)); }
-    __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o) const {
-        o[0] = quantise<NEAREST>(r.x, inv_delta); o[1] = quantise<NEAREST>(r.y, inv_delta);
-        o[2] = quantise<NEAREST>(r.z, inv_delta); o[3] = quantise<NEAREST>(r.w, inv_delta);
-    }
-    __device__ __forceinline__ int32_t one(int64_t i) const { return quantise<NEAREST>(x[i], inv_delta); }
+    static __device__ __forceinline__ raw4 load(const float *p) { return load_vec<gg_f4, true>(reinterpret_cast<const gg_f4 *>(p)); }
+    static __device__ __forceinline__ void values(const raw4 &r, float (&v)[4]) { v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w; }
+    static __device__ __forceinline__ float value(const float *p) { return *p; }
 };
-template <bool NEAREST> struct QuantisedTensor<bf16_t, NEAREST> {
-    const bf16_t *x; float inv_delta;
+template <> struct Quad<bf16_t> {
     using raw4 = gg_u2;
-    __device__ __forceinline__ raw4 load4(int64_t i) const { return load_vec<gg_u2, true>(reinterpret_cast<const gg_u2 *>(x + i)); }
-    __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o) const {
-        o[0] = quantise<NEAREST>(__uint_as_float(r.x << 16), inv_delta);
-        o[1] = quantise<NEAREST>(__uint_as_float(r.x & 0xffff0000u), inv_delta);
-        o[2] = quantise<NEAREST>(__uint_as_float(r.y << 16), inv_delta);
-        o[3] = quantise<NEAREST>(__uint_as_float(r.y & 0xffff0000u), inv_delta);
+    static __device__ __forceinline__ raw4 load(const bf16_t *p) { return load_vec<gg_u2, true>(reinterpret_cast<const gg_u2 *>(p)); }
+    static __device__ __forceinline__ void values(const raw4 &r, float (&v)[4]) {
+        v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
     }
-    __device__ __forceinline__ int32_t one(int64_t i) const {
-        return quantise<NEAREST>(__uint_as_float((uint32_t)x[i].bits << 16), inv_delta);
+    static __device__ __forceinline__ float value(const bf16_t *p) { return __uint_as_float((uint32_t)p->bits << 16); }
+};
+
+template <typename T, bool NEAREST> struct QuantisedTensor {
+    const T *x; float inv_delta;
+    using raw4 = typename Quad<T>::raw4;
+    using Ctx = NoCtx;
+    __device__ __forceinline__ Ctx begin(int64_t) const { return {}; }
+    __device__ __forceinline__ bool covers(const Ctx &, int64_t) const { return true; }
+    __device__ __forceinline__ raw4 load4(int64_t i) const { return Quad<T>::load(x + i); }
+    __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o, const Ctx &) const {
+        float v[4];
+        Quad<T>::values(r, v);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = quantise<NEAREST>(v[j], inv_delta);
+    }
+    __device__ __forceinline__ int32_t one(int64_t i, Ctx &) const { return quantise<NEAREST>(Quad<T>::value(x + i), inv_delta); }
+};
+
+// a flat bucket with one step per unit (off: S + 1 element offsets, units: 1/Delta per unit, 0 = no usable step)
+template <typename T, bool NEAREST> struct QuantisedBucket {
+    const T *x; const int64_t *off; const UnitCoef *units; int32_t S;
+    using raw4 = typename Quad<T>::raw4;
+    struct Ctx { int32_t unit; int64_t end; float inv_delta; };
+    __device__ __forceinline__ Ctx begin(int64_t i) const {     // i < off[S]
+        int lo = 0, hi = S;        // the largest u with off[u] <= i: its unit is not empty and holds i
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (off[mid] <= i) lo = mid; else hi = mid;
+        }
+        return Ctx{lo, off[lo + 1], units[lo].inv_delta};
+    }
+    __device__ __forceinline__ bool covers(const Ctx &c, int64_t end) const { return end <= c.end; }
+    __device__ __forceinline__ raw4 load4(int64_t i) const { return Quad<T>::load(x + i); }
+    __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o, const Ctx &c) const {
+        float v[4];
+        Quad<T>::values(r, v);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = quantise<NEAREST>(v[j], c.inv_delta);
+    }
+    __device__ __forceinline__ int32_t one(int64_t i, Ctx &c) const {
+        while (i >= c.end) { ++c.unit; c.end = off[c.unit + 1]; c.inv_delta = units[c.unit].inv_delta; }
+        return quantise<NEAREST>(Quad<T>::value(x + i), c.inv_delta);
     }
 };
 
@@ -234,21 +277,23 @@ __global__ __launch_bounds__(kBlock) void k_eg_tile_bits(Src src, int64_t n, int
     const int64_t tile = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
     if (tile >= nb) return;
     const int64_t base = tile * kEgBlock;
+    const int64_t stop = base + kEgBlock < n ? base + kEgBlock : n;
     const uint32_t add = 1u << eg_k;
     uint32_t bits = 0;
-    if (base + kEgBlock <= n) {
+    typename Src::Ctx ctx = src.begin(base);
+    if (base + kEgBlock <= n && src.covers(ctx, base + kEgBlock)) {
         typename Src::raw4 v[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) v[j] = src.load4(base + (int64_t)(j * 64 + lane) * 4);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             int32_t q[4];
-            src.conv4(v[j], q);
+            src.conv4(v[j], q, ctx);
             bits += eg_len(map_q(q[0]) + add, eg_k) + eg_len(map_q(q[1]) + add, eg_k) + eg_len(map_q(q[2]) + add, eg_k) +
                     eg_len(map_q(q[3]) + add, eg_k);
         }
     } else {
-        for (int64_t i = base + lane; i < n; i += 64) bits += eg_len(map_q(src.one(i)) + add, eg_k);
+        for (int64_t i = base + lane; i < stop; i += 64) bits += eg_len(map_q(src.one(i, ctx)) + add, eg_k);
     }
     bits = wave_reduce(bits, OpAdd());
     if (lane == 0) tile_bits[tile] = bits;
@@ -312,17 +357,22 @@ __global__ __launch_bounds__(1024) void k_eg_scan(const uint64_t *__restrict__ s
 
 struct EgSymbols { int32_t q[kEgPerLane]; };
 
-// the eight consecutive symbols of a lane; positions at and beyond n read as 0
+// the eight consecutive symbols of a lane; positions at and beyond n read as 0.  `tile_ctx` is the context of
+// the tile's first element (if the tile has any).
 template <typename Src>
-__device__ __forceinline__ EgSymbols eg_load(const Src &src, int64_t i0, int64_t n) {
+__device__ __forceinline__ EgSymbols eg_load(const Src &src, const typename Src::Ctx &tile_ctx, int64_t i0, int64_t n) {
     EgSymbols s;
-    if (i0 + kEgPerLane <= n) {
+    if (i0 + kEgPerLane <= n && src.covers(tile_ctx, i0 + kEgPerLane)) {
         const typename Src::raw4 a = src.load4(i0), b = src.load4(i0 + 4);
-        src.conv4(a, s.q);
-        src.conv4(b, s.q + 4);
+        src.conv4(a, s.q, tile_ctx);
+        src.conv4(b, s.q + 4, tile_ctx);
+    } else if (i0 < n) {
+        typename Src::Ctx c = src.begin(i0);
+#pragma unroll
+        for (int j = 0; j < kEgPerLane; ++j) s.q[j] = i0 + j < n ? src.one(i0 + j, c) : 0;
     } else {
 #pragma unroll
-        for (int j = 0; j < kEgPerLane; ++j) s.q[j] = i0 + j < n ? src.one(i0 + j) : 0;
+        for (int j = 0; j < kEgPerLane; ++j) s.q[j] = 0;
     }
     return s;
 }
@@ -344,14 +394,19 @@ __global__ __launch_bounds__(kBlock) void k_eg_encode(Src src, int64_t n, int64_
     EgSymbols sym[kEgTilesPerBlock];
     uint64_t off[kEgTilesPerBlock + 1];
 #pragma unroll
-    for (int t = 0; t < kEgTilesPerBlock; ++t)
-        sym[t] = eg_load(src, (tile_first + t) * kEgBlock + (int64_t)tid * kEgPerLane, n);   // all zero past n
+    for (int t = 0; t < kEgTilesPerBlock; ++t) {
+        const int64_t tile_base = (tile_first + t) * kEgBlock;
+        typename Src::Ctx tile_ctx{};
+        if (tile_base < n) tile_ctx = src.begin(tile_base);
+        sym[t] = eg_load(src, tile_ctx, tile_base + (int64_t)tid * kEgPerLane, n);   // all zero past n
+    }
 #pragma unroll
     for (int t = 0; t <= kEgTilesPerBlock; ++t) off[t] = tile_off[t <= tiles ? tile_first + t : tile_first + tiles];
     // the symbols that follow this group's tiles: at most 31 of them reach into the group's last word
     const int64_t peek_i = (tile_first + tiles) * kEgBlock + tid;
     const bool peek_live = tid < 32 && peek_i < n;
-    const int32_t peek_q = peek_live ? src.one(peek_i) : 0;
+    int32_t peek_q = 0;
+    if (peek_live) { typename Src::Ctx c = src.begin(peek_i); peek_q = src.one(peek_i, c); }
     for (int i = tid; i < kEgLdsWords; i += kBlock) buf[i] = 0;
     uint32_t carry = 0;       // held by the lane that copied out a tile's last word: bits to start the next tile with
     bool carried = false;     // uniform: the previous tile left its last word to this one
@@ -758,6 +813,41 @@ int gg_eg_encode_tensor(const void *x_dev, int dtype, int64_t n, float delta, in
     return nearest ? eg_encode_launch(QuantisedTensor<bf16_t, true>{x, inv_delta}, n, eg_k, stream_dev, stream_bytes,
                                       block_offsets_dev, total_bits_dev, st)
                    : eg_encode_launch(QuantisedTensor<bf16_t, false>{x, inv_delta}, n, eg_k, stream_dev, stream_bytes,
+                                      block_offsets_dev, total_bits_dev, st);
+}
+
+int gg_eg_encode_segmented(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S, const float *delta_dev,
+                           int round_mode, int eg_k, uint8_t *stream_dev, uint64_t stream_bytes, uint64_t *block_offsets_dev,
+                           uint64_t *total_bits_dev, void *ws_dev, size_t ws_bytes, void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    Geometry g;
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    if (rc != GG_OK) return rc;
+    const int64_t n = g.n_total;
+    if ((rc = check_eg_buffers(n, eg_k, stream_dev, stream_bytes, block_offsets_dev, total_bits_dev)) != GG_OK) return rc;
+    if (round_mode != GG_FLOOR && round_mode != GG_NEAREST_EVEN) return GG_ERR_INVALID_ARG;
+    if (n > 0 && (!x_dev || !aligned16(x_dev) || !delta_dev)) return GG_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const UnitCoef *units = nullptr;
+    if (S > 0) {
+        if ((rc = upload_geometry(g, st)) != GG_OK) return rc;
+        UnitCoef *u = reinterpret_cast<UnitCoef *>(g.params());   // the per-unit parameter area of the workspace
+        hipLaunchKernelGGL(k_unit_coef, dim3((unsigned)((S + 255) / 256)), dim3(256), 0, st, g.sv, delta_dev, 1.0f, u);
+        if ((rc = check_launch()) != GG_OK) return rc;
+        units = u;
+    }
+    const bool nearest = round_mode == GG_NEAREST_EVEN;
+    if (dtype == GG_F32) {
+        const float *x = static_cast<const float *>(x_dev);
+        return nearest ? eg_encode_launch(QuantisedBucket<float, true>{x, g.sv.off, units, S}, n, eg_k, stream_dev, stream_bytes,
+                                          block_offsets_dev, total_bits_dev, st)
+                       : eg_encode_launch(QuantisedBucket<float, false>{x, g.sv.off, units, S}, n, eg_k, stream_dev, stream_bytes,
+                                          block_offsets_dev, total_bits_dev, st);
+    }
+    const bf16_t *x = static_cast<const bf16_t *>(x_dev);
+    return nearest ? eg_encode_launch(QuantisedBucket<bf16_t, true>{x, g.sv.off, units, S}, n, eg_k, stream_dev, stream_bytes,
+                                      block_offsets_dev, total_bits_dev, st)
+                   : eg_encode_launch(QuantisedBucket<bf16_t, false>{x, g.sv.off, units, S}, n, eg_k, stream_dev, stream_bytes,
                                       block_offsets_dev, total_bits_dev, st);
 }
 

@@ -124,6 +124,10 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.gg_eg_encode_tensor(P, 0, 100, 0.1, 3, 0, P, 1024, P, None, None) == -1               # round mode
     assert L.gg_eg_encode_tensor(P + 8, 1, 100, 0.1, 0, 0, P, 1024, P, None, None) == -1           # misaligned x
     assert L.gg_eg_encode_tensor(P, 1, 100, 0.1, 0, 0, P, 1024, None, None, None) == -4
+    assert L.gg_eg_encode_segmented(P, 0, off.ctypes.data, 3, P, 0, 0, P, 1024, P, None, P, ws_bytes, None) == -3
+    assert L.gg_eg_encode_segmented(P, 0, ok_off.ctypes.data, 3, None, 0, 0, P, 1024, P, None, P, ws_bytes, None) == -1   # no steps
+    assert L.gg_eg_encode_segmented(P, 0, ok_off.ctypes.data, 3, P, 0, 0, P, 1024, P, None, None, 0, None) == -4           # no workspace
+    assert L.gg_eg_encode_segmented(P, 2, ok_off.ctypes.data, 3, P, 0, 0, P, 1024, P, None, P, ws_bytes, None) == -2
     assert L.gg_eg_decode(P, P, -1, 0, P, None) == -1
     assert L.gg_eg_decode(P + 1, P, 100, 0, P, None) == -1                                         # misaligned stream
     assert L.gg_eg_decode(P, P, 100, 0, P + 4, None) == -1                                         # misaligned output

@@ -251,6 +251,45 @@ def test_eg_stream_straight_from_the_tensor(gg, dtype, mode):
         assert torch.equal(gg.gg_eg_decode(s_new, i_new, n, eg_k=k), sym)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_eg_stream_of_a_bucket_with_a_step_per_unit(gg, dtype):
+    # unit boundaries inside tiles, inside a lane's eight symbols, empty / one-element / unusable-step units
+    sizes = [0, 17, 4096, 1, 30_000, 0, 99_999, 16_384, 3, 1, 1, 5, 3 * 2048 + 5, 0, 2048, 7]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    x = make(n, 0.02, 0.7, seed=41, dtype=dtype)
+    delta_h = np.array([0.01, 0.002, 0.0, 0.004, 0.001, 0.01, float("nan"), 0.0005, 0.003, 0.02, 0.001, 0.004, 0.0007,
+                        0.1, 0.0011, 0.05], dtype=np.float32)
+    delta = torch.tensor(delta_h, device=DEV)
+    ws = gg.Workspace(n, len(sizes))
+    hb = host_bits(x)
+    for mode, k in ((0, 0), (1, 3)):
+        out, _, sym = gg.gg_quantize_rate_segmented(x, off, delta, ws, eg_k=k, round_mode=mode, want_symbols=True)
+        s_ref, i_ref, t_ref = gg.gg_eg_encode(sym, eg_k=k)
+        s_new, i_new, t_new = gg.gg_eg_encode_segmented(x, off, delta, ws, eg_k=k, round_mode=mode)
+        assert t_new == t_ref
+        nbytes = (t_ref + 7) // 8
+        assert torch.equal(s_new[:nbytes], s_ref[:nbytes]) and torch.equal(i_new, i_ref)
+        # the oracle's symbols unit by unit (an unusable step gives zeros), then its stream
+        osym = np.zeros(n, dtype=np.int32)
+        bits = 0
+        rec = gg.rate_records(out)
+        for u, sz in enumerate(sizes):
+            d = delta_h[u]
+            if sz == 0 or not (d > 0 and np.isfinite(d)):
+                bits += sz * (k + 1)                    # symbol 0 costs k + 1 bits
+                continue
+            r, _, q = oracle.quantize_rate(hb[off[u]:off[u + 1]], float(d), eg_k=k, round_mode=mode, want_symbols=True)
+            osym[off[u]:off[u + 1]] = q
+            bits += r.eg_bits
+            assert int(rec[u]["eg_bits"]) == r.eg_bits
+        uu = np.where(osym > 0, 2 * osym.astype(np.int64) - 1, -2 * osym.astype(np.int64)).astype(np.uint32)
+        obuf, obits = oracle.eg_encode(uu, k)
+        assert t_new == obits == bits
+        assert np.array_equal(s_new.cpu().numpy()[: obuf.size], obuf)
+        assert np.array_equal(gg.gg_eg_decode(s_new, i_new, n, eg_k=k).cpu().numpy(), osym)
+
+
 def test_eg_stream_of_longest_codes(gg):
     # every symbol takes 63 bits (k = 0): the decoder's buffered words run out within a step and are topped up
     n = 5000
