@@ -1022,24 +1022,26 @@ struct SampleArgs {
     int64_t n;
 };
 
-__device__ __forceinline__ float gg_draw(const SampleArgs &s, uint64_t idx) {
-    float gam = s.d;            // fallback if every attempt is rejected (probability < 1e-80)
-    uint32_t w3_first = 0;
-    for (uint32_t attempt = 0; attempt < (uint32_t)kMaxAttempts; ++attempt) {
-        uint32_t w[4];
-        philox4x32_10(attempt, s.stream_id, (uint32_t)idx, (uint32_t)(idx >> 32), s.key0, s.key1, w);
-        if (attempt == 0) w3_first = w[3];
-        // Box-Muller: v_cos_f32 takes its argument in revolutions
-        const float rad = sqrtf(-2.0f * 0.69314718056f * __builtin_amdgcn_logf(unit_open(w[0])));
-        const float z = rad * __builtin_amdgcn_cosf(unit_open(w[1]));
-        const float t = 1.0f + s.c * z;
-        const float v = t * t * t;
-        if (v <= 0.f) continue;
-        const float lu = 0.69314718056f * __builtin_amdgcn_logf(unit_open(w[2]));
-        const float lv = 0.69314718056f * __builtin_amdgcn_logf(v);
-        if (lu < 0.5f * z * z + s.d - s.d * v + s.d * lv) { gam = s.d * v; break; }
-    }
-    // G^(1/beta); with the boost G = G' U^beta so G^(1/beta) = G'^(1/beta) U
+// One Marsaglia-Tsang attempt for element idx: true and the Gamma variate on acceptance.  w3 is the fourth
+// Philox word of the attempt (sign and boost uniform are taken from attempt 0).
+__device__ __forceinline__ bool gg_attempt(const SampleArgs &s, uint64_t idx, uint32_t attempt, float &gam, uint32_t &w3) {
+    uint32_t w[4];
+    philox4x32_10(attempt, s.stream_id, (uint32_t)idx, (uint32_t)(idx >> 32), s.key0, s.key1, w);
+    w3 = w[3];
+    // Box-Muller: v_cos_f32 takes its argument in revolutions
+    const float rad = sqrtf(-2.0f * 0.69314718056f * __builtin_amdgcn_logf(unit_open(w[0])));
+    const float z = rad * __builtin_amdgcn_cosf(unit_open(w[1]));
+    const float t = 1.0f + s.c * z;
+    const float v = t * t * t;
+    if (v <= 0.f) return false;
+    const float lu = 0.69314718056f * __builtin_amdgcn_logf(unit_open(w[2]));
+    const float lv = 0.69314718056f * __builtin_amdgcn_logf(v);
+    gam = s.d * v;
+    return lu < 0.5f * z * z + s.d - s.d * v + s.d * lv;
+}
+
+// x from the accepted Gamma variate: G^(1/beta); with the boost G = G' U^beta so G^(1/beta) = G'^(1/beta) U
+__device__ __forceinline__ float gg_finish(const SampleArgs &s, float gam, uint32_t w3_first) {
     float mag = __builtin_amdgcn_exp2f(s.a * __builtin_amdgcn_logf(gam));
     if (s.boost) mag *= unit_open(w3_first);
     const float xv = s.alpha * mag;
@@ -1047,12 +1049,65 @@ __device__ __forceinline__ float gg_draw(const SampleArgs &s, uint64_t idx) {
 }
 
 template <typename T>
+__device__ __forceinline__ void gg_store(T *__restrict__ out, int64_t i, float v) {
+    if constexpr (sizeof(T) == 2) out[i].bits = f32_to_bf16_rne(v);
+    else out[i] = v;
+}
+
+// A wave draws kSampleRounds x 64 consecutive elements.  Every element's first attempt runs with all lanes
+// busy; the few rejected ones (2-5 %) are queued in LDS and retried together, lanes packed, attempt after
+// attempt -- instead of the whole wave looping until its slowest lane is through (twice the work on average).
+// Element i always uses the Philox blocks (attempt, stream, i), so the result does not depend on this order.
+#ifndef GG_SAMPLE_ROUNDS
+#define GG_SAMPLE_ROUNDS 16
+#endif
+constexpr int kSampleRounds = GG_SAMPLE_ROUNDS;
+constexpr int kSampleSpan = 64 * kSampleRounds;
+
+template <typename T>
 __global__ __launch_bounds__(kBlock) void k_sample(T *__restrict__ out, SampleArgs s) {
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < s.n; i += stride) {
-        const float v = gg_draw(s, s.offset + (uint64_t)i);
-        if constexpr (sizeof(T) == 2) out[i].bits = f32_to_bf16_rne(v);
-        else out[i] = v;
+    __shared__ int64_t q_idx[kWaves][kSampleSpan];
+    __shared__ uint32_t q_w3[kWaves][kSampleSpan];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t below = (1ull << lane) - 1ull;               // lanes before this one
+    const int64_t n_waves = (int64_t)gridDim.x * kWaves;
+    int64_t *qi = q_idx[wave];
+    uint32_t *qw = q_w3[wave];
+    for (int64_t base = ((int64_t)blockIdx.x * kWaves + wave) * kSampleSpan; base < s.n; base += n_waves * kSampleSpan) {
+        int count = 0;                                          // queued elements (uniform over the wave)
+#pragma unroll 2
+        for (int r = 0; r < kSampleRounds; ++r) {
+            const int64_t i = base + r * 64 + lane;
+            const bool there = i < s.n;
+            float gam = s.d;
+            uint32_t w3 = 0;
+            const bool ok = gg_attempt(s, s.offset + (uint64_t)i, 0u, gam, w3);
+            if (there && ok) gg_store(out, i, gg_finish(s, gam, w3));
+            const bool again = there && !ok;
+            const uint64_t m = __ballot(again);
+            if (again) { const int p = count + (int)__popcll(m & below); qi[p] = i; qw[p] = w3; }
+            count += (int)__popcll(m);
+        }
+        for (uint32_t attempt = 1; attempt < (uint32_t)kMaxAttempts && count > 0; ++attempt) {
+            int kept = 0;
+            for (int b = 0; b < count; b += 64) {               // entries are read before any of this batch is re-queued
+                const bool have = b + lane < count;
+                const int64_t i = have ? qi[b + lane] : 0;
+                const uint32_t w3_first = have ? qw[b + lane] : 0u;
+                float gam = s.d;
+                uint32_t w3;
+                const bool ok = gg_attempt(s, s.offset + (uint64_t)i, attempt, gam, w3);
+                if (have && ok) gg_store(out, i, gg_finish(s, gam, w3_first));
+                const bool again = have && !ok;
+                const uint64_t m = __ballot(again);
+                if (again) { const int p = kept + (int)__popcll(m & below); qi[p] = i; qw[p] = w3_first; }
+                kept += (int)__popcll(m);
+            }
+            count = kept;
+        }
+        // every attempt rejected (probability below 1e-80): the mode of the proposal stands in
+        for (int b = 0; b < count; b += 64)
+            if (b + lane < count) gg_store(out, qi[b + lane], gg_finish(s, s.d, qw[b + lane]));
     }
 }
 
@@ -1559,7 +1614,7 @@ int gg_sample(void *out_dev, int dtype, int64_t n, float alpha, float beta, uint
     const double d = (s.boost ? a + 1.0 : a) - 1.0 / 3.0;
     s.alpha = alpha; s.a = (float)a; s.d = (float)d; s.c = (float)(1.0 / sqrt(9.0 * d));
     s.key0 = (uint32_t)seed; s.key1 = (uint32_t)(seed >> 32); s.stream_id = stream_id; s.offset = offset; s.n = n;
-    int64_t blocks = (n + kBlock - 1) / kBlock;
+    int64_t blocks = (n + (int64_t)kWaves * kSampleSpan - 1) / ((int64_t)kWaves * kSampleSpan);
     if (blocks > 256 * 16) blocks = 256 * 16;
     hipStream_t st = (hipStream_t)stream;
     if (dtype == GG_F32) hipLaunchKernelGGL(k_sample<float>, dim3((unsigned)blocks), dim3(kBlock), 0, st, (float *)out_dev, s);
