@@ -1225,7 +1225,7 @@ static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hip
         rs = RunSplit{g.n_chunks * a.parts, 1};
     }
     else if (lds > 0) rs = split_runs(g.n_chunks, resident_blocks(k_quant<T, MODE, RATE, PEN, EXTRA, FIT>, lds, GG_HIST_BLOCKS_PER_CU));
-    else if (PEN) rs = split_runs(g.n_chunks, GG_RATE_PEN_RUNS_PER_CU);
+    else if (PEN || a.symbols) rs = split_runs(g.n_chunks, GG_RATE_PEN_RUNS_PER_CU);   // a written stream
     else rs = split_runs(g.n_chunks, GG_RATE_RUNS_PER_CU);
     if (RATE && (rs.blocks > kMaxRuns || !a.pieces)) return GG_ERR_WORKSPACE;
     a.chunks_per_block = rs.chunks_per_block;
