@@ -115,18 +115,21 @@ __device__ __forceinline__ double log_rho(double b, double &g1_minus_g3) {
 }
 __device__ __forceinline__ double log_rho(double b) { double unused; return log_rho(b, unused); }
 
-// cubic Lagrange through (xs[k], ys[k]), k = 0..3, evaluated at x: one division per node
+// cubic Lagrange through (xs[k], ys[k]), k = 0..3, evaluated at x, over the common denominator: one division.
+// The node differences here are 1e-5 .. 1 (table values a grid step apart), so the products stay far inside
+// the fp64 range.
 __device__ __forceinline__ double lagrange4(const double (&xs)[4], const double (&ys)[4], double x) {
-    double acc = 0.0;
+    double num[4], den[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        double num = ys[k], den = 1.0;
+        num[k] = ys[k]; den[k] = 1.0;
 #pragma unroll
         for (int m = 0; m < 4; ++m)
-            if (m != k) { num *= x - xs[m]; den *= xs[k] - xs[m]; }
-        acc += num / den;
+            if (m != k) { num[k] *= x - xs[m]; den[k] *= xs[k] - xs[m]; }
     }
-    return acc;
+    const double d01 = den[0] * den[1], d23 = den[2] * den[3];
+    const double top = (num[0] * den[1] + num[1] * den[0]) * d23 + (num[2] * den[3] + num[3] * den[2]) * d01;
+    return top / (d01 * d23);
 }
 
 // the same for equally spaced nodes x0, x0 + h, x0 + 2h, x0 + 3h: the denominators are -6, 2, -2, 6 times h^3
