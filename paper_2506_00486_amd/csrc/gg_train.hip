@@ -300,20 +300,37 @@ __global__ __launch_bounds__(kBlock) void k_eg_tile_bits(Src src, int64_t n, int
 }
 
 // Exclusive scan of the tile sizes: tile_off[i] = sizes[0] + ... + sizes[i-1], the total to tile_off[nb] and
-// *total_out.  A workgroup owns kEgScanSeg consecutive tiles; it first adds up everything before its
-// segment (coalesced reads of an array that stays in cache), so the groups need not wait for each other.
+// *total_out.  A workgroup owns kEgScanSeg consecutive tiles; what lies before its segment it adds up from
+// the per-group sums a first small kernel leaves (one group: nothing to add), so the groups need not wait
+// for each other and the work stays linear in the number of tiles.
 constexpr int kEgScanSeg = 8192;                    // 1024 lanes x 8 tiles
 
-__global__ __launch_bounds__(1024) void k_eg_scan(const uint64_t *__restrict__ sizes, uint64_t *__restrict__ tile_off, int64_t nb,
+__global__ __launch_bounds__(1024) void k_eg_group_sums(const uint64_t *__restrict__ sizes, int64_t nb, uint64_t *__restrict__ group_sums) {
+    __shared__ uint64_t wsum[16];
+    const int tid = threadIdx.x;
+    const int64_t i0 = (int64_t)blockIdx.x * kEgScanSeg + (int64_t)tid * 8;
+    uint64_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) mine += i0 + j < nb ? sizes[i0 + j] : 0;
+    mine = wave_reduce(mine, OpAdd());
+    if ((tid & 63) == 0) wsum[tid >> 6] = mine;
+    __syncthreads();
+    if (tid == 0) {
+        uint64_t all = 0;
+        for (int w = 0; w < 16; ++w) all += wsum[w];
+        group_sums[blockIdx.x] = all;
+    }
+}
+
+__global__ __launch_bounds__(1024) void k_eg_scan(const uint64_t *__restrict__ sizes, const uint64_t *__restrict__ group_sums,
+                                                  uint64_t *__restrict__ tile_off, int64_t nb,
                                                   uint64_t *__restrict__ index_end, uint64_t *__restrict__ total_out) {
     __shared__ uint64_t wsum[2][16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t seg0 = (int64_t)blockIdx.x * kEgScanSeg;
-    uint64_t p0 = 0, p1 = 0, p2 = 0, p3 = 0;
-    int64_t i = tid;
-    for (; i + 3072 < seg0; i += 4096) { p0 += sizes[i]; p1 += sizes[i + 1024]; p2 += sizes[i + 2048]; p3 += sizes[i + 3072]; }
-    for (; i < seg0; i += 1024) p0 += sizes[i];
-    const uint64_t before_w = wave_reduce((p0 + p1) + (p2 + p3), OpAdd());
+    uint64_t before = 0;
+    for (int64_t g = tid; g < (int64_t)blockIdx.x; g += 1024) before += group_sums[g];
+    const uint64_t before_w = wave_reduce(before, OpAdd());
     if (lane == 0) wsum[0][wave] = before_w;
 
     const int64_t i0 = seg0 + (int64_t)tid * 8;
@@ -656,7 +673,8 @@ static UnitCoef host_coef(float delta, int64_t n_rate, float scale) {
     return uc;
 }
 
-// workspace: decoding index (T + 1 entries, T = ceil(n / GG_EG_TILE)) | packing-tile offsets (P + 1) | tile sizes (P)
+// workspace: decoding index (T + 1 entries, T = ceil(n / GG_EG_TILE)) | packing-tile offsets (P + 1) | tile sizes (P) |
+// sums of the scan groups (ceil(P / kEgScanSeg))
 static int64_t eg_index_tiles(int64_t n) { return (n + GG_EG_TILE - 1) / GG_EG_TILE; }
 static int64_t eg_pack_tiles(int64_t n) { return (n + kEgBlock - 1) / kEgBlock; }
 
@@ -675,8 +693,13 @@ static int eg_encode_launch(const Src &src, int64_t n, int eg_k, uint8_t *stream
         if ((rc = check_launch()) != GG_OK) return rc;
     }
     const int64_t groups = nb > 0 ? (nb + kEgScanSeg - 1) / kEgScanSeg : 1;
-    hipLaunchKernelGGL(k_eg_scan, dim3((unsigned)groups), dim3(1024), 0, st, sizes, tile_off, nb, block_offsets_dev + T,
-                       total_bits_dev);
+    uint64_t *group_sums = sizes + nb;
+    if (groups > 1) {
+        hipLaunchKernelGGL(k_eg_group_sums, dim3((unsigned)groups), dim3(1024), 0, st, sizes, nb, group_sums);
+        if ((rc = check_launch()) != GG_OK) return rc;
+    }
+    hipLaunchKernelGGL(k_eg_scan, dim3((unsigned)groups), dim3(1024), 0, st, sizes, group_sums, tile_off, nb,
+                       block_offsets_dev + T, total_bits_dev);
     if ((rc = check_launch()) != GG_OK) return rc;
     if (nb > 0) {   // also without room for any stream: this kernel writes the index
         hipLaunchKernelGGL(k_eg_encode<Src>, dim3((unsigned)((nb + kEgTilesPerBlock - 1) / kEgTilesPerBlock)), dim3(kBlock), 0,
@@ -778,7 +801,8 @@ int gg_gct_update_segmented(float *w_dev, const float *g_dev, float *ghat_prev_d
 
 int gg_eg_workspace_bytes(int64_t n, size_t *bytes_out_host) {
     if (!bytes_out_host || n < 0) return GG_ERR_INVALID_ARG;
-    *bytes_out_host = (size_t)(eg_index_tiles(n) + 2 * eg_pack_tiles(n) + 2) * sizeof(uint64_t);
+    const int64_t P = eg_pack_tiles(n);
+    *bytes_out_host = (size_t)(eg_index_tiles(n) + 2 * P + 2 + (P + kEgScanSeg - 1) / kEgScanSeg) * sizeof(uint64_t);
     return GG_OK;
 }
 

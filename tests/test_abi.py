@@ -156,7 +156,7 @@ def test_huffman_mean_bits_host_helper():
     h = rng.integers(0, 1000, size=5000).astype(np.uint64)
     assert gg.gg_huffman_mean_bits(h) == pytest.approx(oracle.huffman_mean_bits(h), rel=1e-12)
     out = C.c_size_t(0)
-    assert gg.lib().gg_eg_workspace_bytes(4097, C.byref(out)) == 0 and out.value == (17 + 2 * 3 + 2) * 8   # 17 index tiles + 1, 3 packing tiles: offsets + 1 and sizes
+    assert gg.lib().gg_eg_workspace_bytes(4097, C.byref(out)) == 0 and out.value == (17 + 2 * 3 + 2 + 1) * 8   # 17 index tiles + 1, 3 packing tiles: offsets + 1 and sizes, one scan group
 
 
 def test_empty_calls_are_ok_without_gpu_work():
