@@ -185,8 +185,8 @@ __device__ __forceinline__ uint32_t eg_len(uint32_t v, int eg_k) {   // v = u + 
 // on the fly with the rate sweep's arithmetic (one fp32 product, NaN -> 0, clamp to +-2^30, floor or
 // nearest-even), so that a tensor goes to its bit stream without a symbol array in between.
 // A source also says which elements share one set of parameters: `begin(i)` gives the context of element
-// i, `covers(ctx, end)` tells whether it holds unchanged up to element `end`, `one(i, ctx)` moves it on
-// as needed (i must not decrease).  Only the bucket source has more than one context.
+// i, `covers(ctx, end)` tells whether it holds unchanged up to element `end`, `seek(ctx, i)` and `one(i, ctx)`
+// move it on as needed (i must not decrease).  Only the bucket source has more than one context.
 struct NoCtx {};
 
 struct SymbolArray {
@@ -195,6 +195,7 @@ struct SymbolArray {
     using Ctx = NoCtx;
     __device__ __forceinline__ Ctx begin(int64_t) const { return {}; }
     __device__ __forceinline__ bool covers(const Ctx &, int64_t) const { return true; }
+    __device__ __forceinline__ void seek(Ctx &, int64_t) const {}
     __device__ __forceinline__ raw4 load4(int64_t i) const { return load_vec<gg_i4, true>(reinterpret_cast<const gg_i4 *>(q + i)); }
     __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o, const Ctx &) const { o[0] = r.x; o[1] = r.y; o[2] = r.z; o[3] = r.w; }
     __device__ __forceinline__ int32_t one(int64_t i, Ctx &) const { return q[i]; }
@@ -233,6 +234,7 @@ template <typename T, bool NEAREST> struct QuantisedTensor {
     using Ctx = NoCtx;
     __device__ __forceinline__ Ctx begin(int64_t) const { return {}; }
     __device__ __forceinline__ bool covers(const Ctx &, int64_t) const { return true; }
+    __device__ __forceinline__ void seek(Ctx &, int64_t) const {}
     __device__ __forceinline__ raw4 load4(int64_t i) const { return Quad<T>::load(x + i); }
     __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o, const Ctx &) const {
         float v[4];
@@ -257,6 +259,11 @@ template <typename T, bool NEAREST> struct QuantisedBucket {
         return Ctx{lo, off[lo + 1], units[lo].inv_delta};
     }
     __device__ __forceinline__ bool covers(const Ctx &c, int64_t end) const { return end <= c.end; }
+    // move a context forward to element i >= its unit's start: a few steps of walking, else a fresh search
+    __device__ __forceinline__ void seek(Ctx &c, int64_t i) const {
+        for (int step = 0; step < 8 && i >= c.end; ++step) { ++c.unit; c.end = off[c.unit + 1]; c.inv_delta = units[c.unit].inv_delta; }
+        if (i >= c.end) c = begin(i);
+    }
     __device__ __forceinline__ raw4 load4(int64_t i) const { return Quad<T>::load(x + i); }
     __device__ __forceinline__ void conv4(const raw4 &r, int32_t *o, const Ctx &c) const {
         float v[4];
@@ -410,11 +417,11 @@ __global__ __launch_bounds__(kBlock) void k_eg_encode(Src src, int64_t n, int64_
 
     EgSymbols sym[kEgTilesPerBlock];
     uint64_t off[kEgTilesPerBlock + 1];
+    typename Src::Ctx tile_ctx = src.begin(tile_first * kEgBlock);      // one search per workgroup; the rest moves on from it
 #pragma unroll
     for (int t = 0; t < kEgTilesPerBlock; ++t) {
         const int64_t tile_base = (tile_first + t) * kEgBlock;
-        typename Src::Ctx tile_ctx{};
-        if (tile_base < n) tile_ctx = src.begin(tile_base);
+        if (tile_base < n) src.seek(tile_ctx, tile_base);
         sym[t] = eg_load(src, tile_ctx, tile_base + (int64_t)tid * kEgPerLane, n);   // all zero past n
     }
 #pragma unroll
@@ -423,7 +430,7 @@ __global__ __launch_bounds__(kBlock) void k_eg_encode(Src src, int64_t n, int64_
     const int64_t peek_i = (tile_first + tiles) * kEgBlock + tid;
     const bool peek_live = tid < 32 && peek_i < n;
     int32_t peek_q = 0;
-    if (peek_live) { typename Src::Ctx c = src.begin(peek_i); peek_q = src.one(peek_i, c); }
+    if (peek_live) { typename Src::Ctx c = tile_ctx; src.seek(c, peek_i); peek_q = src.one(peek_i, c); }
     for (int i = tid; i < kEgLdsWords; i += kBlock) buf[i] = 0;
     uint32_t carry = 0;       // held by the lane that copied out a tile's last word: bits to start the next tile with
     bool carried = false;     // uniform: the previous tile left its last word to this one
