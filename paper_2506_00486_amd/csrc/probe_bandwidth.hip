@@ -6,6 +6,8 @@
 //            plain and non-temporal loads
 //   reread : the same reader over a 64 / 128 / 256 MiB window, eight times (Infinity-Cache sized)
 //   widen  : bf16 -> fp32 widening copy (2 B read + 4 B written per element)
+//   copy   : fp32 y = c x (4 B read + 4 B written) as resident runs, one 64 / 16 KiB piece per block,
+//            grid-strided 256 KiB tiles; write-only fill; the runtime's own device copy
 //   spread : finish-time spread of resident blocks with equal contiguous shares
 // Usage: probe_bandwidth [elements]   (default 1543655424).  Prints one line per experiment.
 #include <hip/hip_runtime.h>
@@ -106,6 +108,41 @@ __global__ __launch_bounds__(kBlock) void k_widen(const vu2 *__restrict__ x, vf4
     }
 }
 
+// y = c x over [0, nvec) vectors: block b takes `vpb` consecutive vectors, or (stride > 0) tiles b, b + grid, ...
+template <bool NTS>
+__global__ __launch_bounds__(kBlock) void k_copy(const vf4 *__restrict__ x, vf4 *__restrict__ y, long nvec, long vpb, int strided, float c) {
+    constexpr int U = 4;
+    const long ntiles = (nvec + vpb - 1) / vpb;
+    for (long t = blockIdx.x; t < ntiles; t += strided ? gridDim.x : ntiles) {
+        const long base = t * vpb;
+        long end = vpb;
+        if (base + end > nvec) end = nvec - base;
+        const vf4 *p = x + base;
+        vf4 *q = y + base;
+        long i = threadIdx.x;
+        for (; i + (U - 1) * kBlock < end; i += U * kBlock) {
+            vf4 r[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) r[u] = __builtin_nontemporal_load(p + i + u * kBlock);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const vf4 o = r[u] * c;
+                if (NTS) __builtin_nontemporal_store(o, q + i + u * kBlock); else q[i + u * kBlock] = o;
+            }
+        }
+        for (; i < end; i += kBlock) q[i] = p[i] * c;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_fill(vf4 *__restrict__ y, long nvec, long vpb, float c) {
+    const long base = (long)blockIdx.x * vpb;
+    if (base >= nvec) return;
+    long end = vpb;
+    if (base + end > nvec) end = nvec - base;
+    const vf4 o = {c, c, c, c};
+    for (long i = threadIdx.x; i < end; i += kBlock) __builtin_nontemporal_store(o, y + base + i);
+}
+
 __global__ void k_init(float *x, long n) {
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) x[i] = (float)(i & 1023) * 1e-3f;
 }
@@ -174,6 +211,25 @@ int main(int argc, char **argv) {
         const long G2 = 131072, vpb2 = (nv + G2 - 1) / G2;
         ms = timeit([&] { k_widen<<<G2, kBlock>>>((const vu2 *)x, (vf4 *)y, nv, vpb2); }, 5);
         printf("widen bf16->fp32, 131072 short blocks                         %.3f ms %7.1f GB/s\n", ms, ne * 6.0 / 1e9 / ms * 1e3);
+    }
+    {
+        const double gb2 = n * 8.0 / 1e9;
+        const long G = 2048, vpb = ((nvec + G - 1) / G + 255) / 256 * 256;
+        ms = timeit([&] { k_copy<true><<<G, kBlock>>>((const vf4 *)x, (vf4 *)y, nvec, vpb, 0, 1.5f); }, 5);
+        printf("copy  fp32, 2048 resident blocks, contiguous runs             %.3f ms %7.1f GB/s\n", ms, gb2 / ms * 1e3);
+        ms = timeit([&] { k_copy<false><<<G, kBlock>>>((const vf4 *)x, (vf4 *)y, nvec, vpb, 0, 1.5f); }, 5);
+        printf("copy  fp32, 2048 resident blocks, plain stores                %.3f ms %7.1f GB/s\n", ms, gb2 / ms * 1e3);
+        ms = timeit([&] { k_copy<true><<<G, kBlock>>>((const vf4 *)x, (vf4 *)y, nvec, 16384, 1, 1.5f); }, 5);
+        printf("copy  fp32, 2048 blocks grid-strided over 256 KiB tiles       %.3f ms %7.1f GB/s\n", ms, gb2 / ms * 1e3);
+        for (long piece : {4096L, 1024L}) {
+            const long nb = (nvec + piece - 1) / piece;
+            ms = timeit([&] { k_copy<true><<<nb, kBlock>>>((const vf4 *)x, (vf4 *)y, nvec, piece, 0, 1.5f); }, 5);
+            printf("copy  fp32, one %2ld KiB piece per block (%ld blocks)        %.3f ms %7.1f GB/s\n", piece * 16 / 1024, nb, ms, gb2 / ms * 1e3);
+        }
+        ms = timeit([&] { CK(hipMemcpyAsync(y, x, n * 4, hipMemcpyDeviceToDevice, 0)); }, 5);
+        printf("copy  the runtime's device-to-device copy                     %.3f ms %7.1f GB/s\n", ms, gb2 / ms * 1e3);
+        ms = timeit([&] { k_fill<<<G, kBlock>>>((vf4 *)y, nvec, vpb, 2.f); }, 5);
+        printf("fill  fp32, 2048 resident blocks (write only)                 %.3f ms %7.1f GB/s\n", ms, gb / ms * 1e3);
     }
     {
         const int G = 2048, cpb = (int)((nchunks + G - 1) / G);
