@@ -43,10 +43,18 @@ __device__ __forceinline__ ChunkLoc locate(const SegView &sv, int64_t chunk) {
         const int64_t rest = sv.cols - L.c * kChunk;
         L.len = (int32_t)(rest < kChunk ? rest : kChunk);
     } else {
-        int lo = 0, hi = sv.S;  // largest s with cpre[s] <= chunk (skips empty units)
+        // Largest s with cpre[s] <= chunk (skips empty units).  Every lane of the wave asks for the same chunk
+        // (the callers are uniform over the block), so the wave probes 64 places at once: two dependent loads
+        // for a few thousand units instead of a dozen -- a block's first load waits for this.
+        const int lane = threadIdx.x & 63;
+        int lo = 0, hi = sv.S;
         while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (sv.cpre[mid] <= chunk) lo = mid; else hi = mid;
+            const int step = (hi - lo + 63) >> 6;
+            const int idx = lo + (lane + 1) * step;
+            const bool le = idx < hi && sv.cpre[idx] <= chunk;
+            const int cnt = (int)__popcll(__ballot(le));     // the probes not above the chunk are a prefix of the lanes
+            lo += cnt * step;
+            hi = lo + step < hi ? lo + step : hi;
         }
         L.seg = lo;
         L.c = chunk - sv.cpre[lo];
