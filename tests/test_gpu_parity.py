@@ -84,6 +84,37 @@ def test_fit_segmented_ragged_bucket(gg, dtype):
         check_fit(rec[s], oracle.fit(hb[off[s]:off[s + 1]]), segs[s].name)
 
 
+def test_bucket_of_thousands_of_small_units(gg):
+    # 6000 units of 0 .. 40,000 elements (many shorter than a chunk, some empty, a few spanning several runs):
+    # the many-unit finalisations (one lane per unit) and the unit search of the sweeps
+    rng = np.random.default_rng(12)
+    sizes = rng.integers(0, 600, size=6000)
+    sizes[rng.integers(0, 6000, size=300)] = 0
+    sizes[rng.integers(0, 6000, size=40)] = rng.integers(17_000, 40_000, size=40)
+    sizes[:3] = (0, 1, 2)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    x = make(n, 0.01, 0.9, seed=77)
+    ws = gg.Workspace(n, len(sizes))
+    res = gg.gg_fused_segmented(x, off, ws, delta_div=16.0, want_symbols=True)
+    frec, rrec = gg.fit_records(res["fit"]), gg.rate_records(res["rate"])
+    sym = res["symbols"].cpu().numpy()
+    hb = host_bits(x)
+    picks = list(range(0, 12)) + list(rng.integers(0, 6000, size=150)) + list(np.flatnonzero(sizes > 16_384)[:10]) + [5999]
+    for s in picks:
+        lo, hi = int(off[s]), int(off[s + 1])
+        o = oracle.fit(hb[lo:hi])
+        check_fit(frec[s], o, f"unit {s} ({hi - lo} elements)")
+        d = float(rrec[s]["delta"])
+        if hi == lo or not (d > 0 and np.isfinite(d)):
+            assert int(rrec[s]["eg_bits"]) == 0
+            continue
+        r, _, osym = oracle.quantize_rate(hb[lo:hi], d, want_symbols=True)
+        check_rate(rrec[s], r, f"unit {s}", entropy=False)
+        assert np.array_equal(sym[lo:hi], osym)
+    assert int(rrec["n"].astype(np.int64).sum()) == n
+
+
 @pytest.mark.parametrize("rows,cols", [(7, 4096), (64, 1000), (3, 40_000), (1, 5), (5, 16384)])
 def test_fit_rows_and_total(gg, rows, cols):
     x = make(rows * cols, 0.5, 0.8, seed=rows, dtype=torch.bfloat16)
