@@ -8,6 +8,8 @@
 //   widen  : bf16 -> fp32 widening copy (2 B read + 4 B written per element)
 //   copy   : fp32 y = c x (4 B read + 4 B written) as resident runs, one 64 / 16 KiB piece per block,
 //            grid-strided 256 KiB tiles; write-only fill; the runtime's own device copy
+//   publish: the same reader with Σ|x| and Σx² combined per block and stored (one barrier pair), or stored
+//            per wave (no barrier), at 8 .. 368 runs per compute unit
 //   spread : finish-time spread of resident blocks with equal contiguous shares
 // Usage: probe_bandwidth [elements]   (default 1543655424).  Prints one line per experiment.
 #include <hip/hip_runtime.h>
@@ -58,6 +60,24 @@ __global__ __launch_bounds__(kBlock) void k_runs(const vf4 *__restrict__ x, long
         __syncthreads();
         if (threadIdx.x == 0) { stamps[2 * blockIdx.x] = t0; stamps[2 * blockIdx.x + 1] = wall_clock64(); }
     }
+}
+
+// the reader with a result per block: EPI 0 nothing stored, 1 block reduction + one store, 2 one store per wave
+template <int EPI>
+__global__ __launch_bounds__(kBlock) void k_publish(const vf4 *__restrict__ x, long nchunks, long nvec, int cpb, double *out) {
+    __shared__ double red[4];
+    const long first = (long)blockIdx.x * cpb;
+    long last = first + cpb;
+    if (last > nchunks) last = nchunks;
+    double acc = 0;
+    for (long c = first; c < last; ++c) acc += chunk_sum<8, true>(x + c * kChunkVec, chunk_len(c, nvec));
+    if (EPI == 0) { if (acc == 123.456) out[blockIdx.x] = acc; return; }
+    for (int d = 32; d; d >>= 1) acc += __shfl_xor(acc, d, 64);
+    if (EPI == 2) { if ((threadIdx.x & 63) == 0) out[4 * first + (threadIdx.x >> 6)] = acc; return; }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) out[first] = (red[0] + red[1]) + (red[2] + red[3]);
+    __syncthreads();
 }
 
 // resident blocks pulling items of `item_chunks` chunks through an atomic ticket
@@ -163,7 +183,7 @@ static float timeit(F f, int reps) {
 int main(int argc, char **argv) {
     const long n = argc > 1 ? atol(argv[1]) : 1543655424L;
     float *x, *y; double *out; unsigned *ctr; long long *stamps;
-    CK(hipMalloc(&x, n * 4)); CK(hipMalloc(&y, n * 4)); CK(hipMalloc(&out, 1 << 22)); CK(hipMalloc(&ctr, 256));
+    CK(hipMalloc(&x, n * 4)); CK(hipMalloc(&y, n * 4)); CK(hipMalloc(&out, (size_t)(n / 4 / kChunkVec + 8) * 4 * sizeof(double))); CK(hipMalloc(&ctr, 256));
     CK(hipMalloc(&stamps, 1 << 20));
     k_init<<<4096, 256>>>(x, n);
     CK(hipDeviceSynchronize());
@@ -230,6 +250,16 @@ int main(int argc, char **argv) {
         printf("copy  the runtime's device-to-device copy                     %.3f ms %7.1f GB/s\n", ms, gb2 / ms * 1e3);
         ms = timeit([&] { k_fill<<<G, kBlock>>>((vf4 *)y, nvec, vpb, 2.f); }, 5);
         printf("fill  fp32, 2048 resident blocks (write only)                 %.3f ms %7.1f GB/s\n", ms, gb / ms * 1e3);
+    }
+    for (int rpc : {8, 32, 64, 128, 368}) {
+        const long G = 256L * rpc;
+        const int cpb = (int)((nchunks + G - 1) / G);
+        const long blocks = (nchunks + cpb - 1) / cpb;
+        const float t0 = timeit([&] { k_publish<0><<<blocks, kBlock>>>((const vf4 *)x, nchunks, nvec, cpb, out); }, reps);
+        const float t1 = timeit([&] { k_publish<1><<<blocks, kBlock>>>((const vf4 *)x, nchunks, nvec, cpb, out); }, reps);
+        const float t2 = timeit([&] { k_publish<2><<<blocks, kBlock>>>((const vf4 *)x, nchunks, nvec, cpb, out); }, reps);
+        printf("publish %3d runs/CU (%6ld blocks x %2d chunks): nothing stored %.3f ms | per block %.3f ms | per wave %.3f ms\n", rpc,
+               blocks, cpb, t0, t1, t2);
     }
     {
         const int G = 2048, cpb = (int)((nchunks + G - 1) / G);
