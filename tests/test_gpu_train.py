@@ -290,6 +290,26 @@ def test_eg_stream_of_a_bucket_with_a_step_per_unit(gg, dtype):
         assert np.array_equal(gg.gg_eg_decode(s_new, i_new, n, eg_k=k).cpu().numpy(), osym)
 
 
+def test_bucket_round_trip_reconstructs_within_one_step(gg):
+    # fit -> steps -> one stream for the bucket -> decode -> q * Delta: the floor quantiser leaves 0 <= x - q Delta < Delta
+    # (up to the fp32 rounding of x / Delta), and the stream is as long as the pass said
+    segs = gg_inputs.scaled_layout(gg_inputs.gradient_bucket_1p5b()[:19], 211)
+    flat, off, _, _ = gg_inputs.make_bucket(segs, seed=9, device=DEV)
+    n, S = flat.numel(), len(segs)
+    ws = gg.Workspace(n, S)
+    res = gg.gg_fused_segmented(flat, off, ws, delta_div=16.0)
+    rrec = gg.rate_records(res["rate"])
+    delta = gg.gg_delta_from_fit(res["fit"], S, 16.0)
+    stream, index, total = gg.gg_eg_encode_segmented(flat, off, delta, ws)
+    assert total == int(rrec["eg_bits"].astype(np.uint64).sum())
+    q = gg.gg_eg_decode(stream, index, n)
+    per_elem = torch.repeat_interleave(delta, torch.tensor(np.diff(off), device=DEV))
+    err = flat.double() - q.double() * per_elem.double()
+    tol = 4e-7 * flat.abs().double()                      # x * (1/Delta) is rounded twice in fp32
+    assert bool((err >= -tol).all()) and bool((err < per_elem.double() + tol).all())
+    assert float(total) / n < 32.0                        # and it does compress an fp32 gradient
+
+
 def test_eg_stream_of_longest_codes(gg):
     # every symbol takes 63 bits (k = 0): the decoder's buffered words run out within a step and are topped up
     n = 5000
