@@ -502,6 +502,7 @@ struct QuantBody {
     // outputs
     int32_t *symbols; float *grad; int accumulate;
     uint32_t *lds_hist; uint64_t *ghist; uint32_t last_bin, lbins;
+    uint32_t fast_lim = 0;     // min(lbins, last_bin) while a histogram is live, else 0: symbols below it need no further test
     // per-lane accumulators
     uint32_t clz_sum = 0, u_max = 0, n_clamped = 0, n_last = 0;
     bool nan_seen = false;
@@ -541,6 +542,17 @@ struct QuantBody {
         return best;
     }
 
+    // Symbols past the block-private bins go straight to the unit's histogram, except the last bin: it
+    // collects every clamped symbol, and atomics of many blocks on that one address serialise, so each lane
+    // counts its hits and the block adds them once.
+    __device__ __forceinline__ void hist_rare(uint32_t u) {
+        const uint32_t bin = u < last_bin ? u : last_bin;
+        n_clamped += u > last_bin ? 1u : 0u;
+        if (bin < lbins) atomicAdd(&lds_hist[bin], 1u);
+        else if (bin == last_bin) n_last += 1u;
+        else atomicAdd(reinterpret_cast<unsigned long long *>(&ghist[bin]), 1ull);
+    }
+
     __device__ __forceinline__ int32_t quant(float x) {
         const float t = x * inv_delta;                 // the one fp32 rounding of the quantiser
         nan_seen |= (t != t);
@@ -554,16 +566,11 @@ struct QuantBody {
         clz_sum += (uint32_t)__builtin_clz(u + eg_add);
         u_max = u > u_max ? u : u_max;
         if constexpr (EXTRA) {
-            if (hist_live) {
-                const uint32_t bin = u < last_bin ? u : last_bin;
-                n_clamped += u > last_bin ? 1u : 0u;
-                // Symbols past the block-private bins go straight to the unit's histogram, except the
-                // last bin: it collects every clamped symbol, and atomics of many blocks on that one
-                // address serialise, so each lane counts its hits and the block adds them once.
-                if (bin < lbins) atomicAdd(&lds_hist[bin], 1u);
-                else if (bin == last_bin) n_last += 1u;
-                else atomicAdd(reinterpret_cast<unsigned long long *>(&ghist[bin]), 1ull);
-            }
+            // Common case first: the symbol is its own bin (not clamped) and the bin is block-private -- one
+            // compare and one LDS increment.  Everything else (clamping bin, bins beyond the private ones)
+            // is rare and handled apart, so that the common path carries no further tests.
+            if (u < fast_lim) atomicAdd(&lds_hist[u], 1u);
+            else if (hist_live) hist_rare(u);
         }
         return -m;
     }
@@ -794,6 +801,7 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
             body.inv_delta = P.inv_delta; body.inv_alpha = P.inv_alpha; body.beta_m1 = P.beta_m1;
             body.pen_coef = P.pen_coef; body.pen_live = !(P.flags & kPenZero);
             body.hist_live = want_hist && rate_live;
+            body.fast_lim = body.hist_live ? (body.lbins < body.last_bin ? body.lbins : body.last_bin) : 0u;
             body.ghist = want_hist ? a.hist + (int64_t)piece_seg * a.nbins : nullptr;
         }
         // kernels that write one 4-byte output per element read bf16 eight bytes per lane (see ElemBf16x4)
