@@ -35,6 +35,12 @@
 #ifndef GG_U_QUANT
 #define GG_U_QUANT 4
 #endif
+#ifndef GG_ROW_BATCH
+#define GG_ROW_BATCH 2            // rows of a matrix a wave fits with one solve (wave-per-row pass)
+#endif
+#ifndef GG_ROW_BATCH_BYTES
+#define GG_ROW_BATCH_BYTES 16384  // and the bytes of rows it may hold in cache between its two sweeps
+#endif
 
 namespace gg {
 
@@ -296,6 +302,40 @@ __device__ __forceinline__ void solve_fit_table_wave(double s1, double s2, uint6
     } else {
         finish_from_table(table, coarse + c2 - 1, target, m2, f);
     }
+}
+
+// A batch of up to kRowBatch units per wave, lane r holding the sums of unit r (r < nr).  Only the search of
+// the interval needs the whole wave (two table probes per unit, the first probe shared by the batch);
+// the fp64 work in front of it (logarithm of the moment ratio) and behind it (interpolation, Eq. 2) is done
+// once, lane r working for unit r.  Must be called by all 64 lanes.
+constexpr int kRowBatch = GG_ROW_BATCH;
+__device__ __forceinline__ void solve_fit_table_batch(double s1, double s2, uint64_t n, int nr, const SolveConst &sc,
+                                                      const double2 *__restrict__ table, gg_fit_t &f) {
+    static_assert(kSolveTable == 64 * 64, "two 64-way rounds cover the table");
+    const int lane = threadIdx.x & 63;
+    double target = 0.0, m2 = 0.0;
+    bool search = false;
+    if (lane < nr) search = fit_head(s1, s2, n, sc, f, target, m2);
+    const double probe = table[64 * lane].x;
+    double tr[kRowBatch];
+    int coarse[kRowBatch];
+    double fine[kRowBatch];
+#pragma unroll
+    for (int r = 0; r < kRowBatch; ++r) {      // any target, even a NaN of an idle lane, stays inside the table
+        tr[r] = __shfl(target, r, 64);
+        int c1 = __popcll(__ballot(probe <= tr[r]));
+        c1 = c1 < 1 ? 1 : c1;
+        coarse[r] = 64 * (c1 - 1);
+        fine[r] = table[coarse[r] + lane].x;
+    }
+    int j = 0;
+#pragma unroll
+    for (int r = 0; r < kRowBatch; ++r) {
+        int c2 = __popcll(__ballot(fine[r] <= tr[r]));
+        c2 = c2 < 1 ? 1 : c2;
+        if (lane == r) j = coarse[r] + c2 - 1;
+    }
+    if (search) finish_from_table(table, j, target, m2, f);
 }
 
 // where the step and the penalty parameters of a unit come from
@@ -823,11 +863,13 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
 
 // ---------------------------------------------------------------------------------------------
 // wave-per-row pass.  For matrices whose rows fit a few cache lines per lane (activations: one row
-// per token) a wave owns a row outright: it sums the moments, solves the fit with its 64 lanes,
-// derives the row's step and immediately quantises the row again while it is still in cache.  No
-// workspace, no atomics, no second kernel; HBM sees each element once.
+// per token) a wave owns a row outright: it sums the moments, solves the fit, derives the row's
+// step and immediately quantises the row again while it is still in cache.  Short rows are taken
+// two at a time, so that the fp64 part of the solve runs once for both (lane r works for row r).
+// No workspace, no atomics, no second kernel; HBM sees each element once.
 // ---------------------------------------------------------------------------------------------
 constexpr int64_t kRowWaveMax = 16384;   // elements per row this path takes
+constexpr int64_t kRowBatchBytes = GG_ROW_BATCH_BYTES; // bytes of rows a wave holds in cache between its two sweeps
 
 struct RowsArgs {
     int64_t rows, cols;
@@ -838,6 +880,7 @@ struct RowsArgs {
     uint32_t eg_add, eg_const;
     int32_t *symbols; float *grad; int accumulate;
     int do_fit;
+    int batch;                // rows per wave and solve, 1..kRowBatch (set by the launcher)
     SolveConst sc;
     const double2 *table;     // tabulated moment-ratio curve (see k_build_solve_table)
 };
@@ -847,56 +890,77 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
     const int lane = threadIdx.x & 63;
     const int64_t n_waves = (int64_t)gridDim.x * kWaves;
     const int len = (int)a.cols;
-    for (int64_t row = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6); row < a.rows; row += n_waves) {
-        const int64_t start = row * a.cols;
+    const int batch = a.batch;       // rows a wave takes at a time, 1..kRowBatch: one lane-parallel solve per batch
+    for (int64_t row0 = ((int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * batch; row0 < a.rows; row0 += n_waves * batch) {
+        const int nr = a.rows - row0 < batch ? (int)(a.rows - row0) : batch;
+        // lane r < nr works for row row0 + r from here to the second sweep
         float alpha = 0.f, beta = 0.f;
         if (a.do_fit) {
-            FitBody fb;
-            // cached loads: the row is read again a few microseconds later by this same wave
-            process_chunk<Elem<T, !(RATE || PEN)>, 4, FitBody, 64>(x, start, len, fb);
-            double s1 = ((double)fb.s1[0] + (double)fb.s1[1]) + ((double)fb.s1[2] + (double)fb.s1[3]);
-            double s2 = ((double)fb.s2[0] + (double)fb.s2[1]) + ((double)fb.s2[2] + (double)fb.s2[3]);
-            s1 = wave_reduce(s1, OpAdd());
-            s2 = wave_reduce(s2, OpAdd());
+            double my_s1 = 0.0, my_s2 = 0.0;
+#pragma unroll
+            for (int r = 0; r < kRowBatch; ++r) {
+                if (r >= nr) break;
+                FitBody fb;
+                // cached loads: the row is read again a few microseconds later by this same wave
+                process_chunk<Elem<T, !(RATE || PEN)>, 4, FitBody, 64>(x, (row0 + r) * a.cols, len, fb);
+                double s1 = ((double)fb.s1[0] + (double)fb.s1[1]) + ((double)fb.s1[2] + (double)fb.s1[3]);
+                double s2 = ((double)fb.s2[0] + (double)fb.s2[1]) + ((double)fb.s2[2] + (double)fb.s2[3]);
+                s1 = wave_reduce(s1, OpAdd());
+                s2 = wave_reduce(s2, OpAdd());
+                if (lane == r) { my_s1 = s1; my_s2 = s2; }
+            }
             gg_fit_t f;
-            solve_fit_table_wave(s1, s2, (uint64_t)len, a.sc, a.table, f);
-            if (lane == 0) a.fit[row] = f;
-            alpha = f.alpha; beta = f.beta;
+            solve_fit_table_batch(my_s1, my_s2, (uint64_t)len, nr, a.sc, a.table, f);
+            if (lane < nr) { a.fit[row0 + lane] = f; alpha = f.alpha; beta = f.beta; }
         }
         if constexpr (RATE || PEN) {
+            // the per-row constants of the second sweep, again one lane per row
             float delta = 0.f;
-            if constexpr (RATE) delta = a.delta_div > 0.f ? (float)((double)alpha / (double)a.delta_div) : a.delta_dev[row];
+            if constexpr (RATE)
+                if (lane < nr) delta = a.delta_div > 0.f ? (float)((double)alpha / (double)a.delta_div) : a.delta_dev[row0 + lane];
             const bool ok = delta > 0.f && isfinite(delta);
-            QuantBody<MODE, RATE, PEN, EXTRA> body;
-            body.eg_add = a.eg_add;
-            body.symbols = a.symbols; body.grad = a.grad; body.accumulate = a.accumulate;
-            body.lds_hist = nullptr; body.ghist = nullptr; body.last_bin = 0; body.lbins = 0; body.hist_live = false;
-            body.inv_delta = ok ? (float)(1.0 / (double)delta) : 0.f;
-            body.pen_live = PEN && alpha > 0.f && isfinite(alpha) && isfinite(beta);
-            body.inv_alpha = body.pen_live ? (float)(1.0 / (double)alpha) : 0.f;
-            body.pen_coef = body.pen_live ? (float)((double)a.lambda * (double)beta / (double)alpha) : 0.f;
-            body.beta_m1 = body.pen_live ? beta - 1.0f : 0.f;
-            if constexpr (sizeof(T) == 2 && (PEN || EXTRA))
-                process_chunk<ElemBf16x4, 8, decltype(body), 64>(x, start, len, body);
-            else
-                process_chunk<Elem<T>, 4, decltype(body), 64>(x, start, len, body);
-            if constexpr (RATE) {
-                constexpr bool kExp0 = decltype(body)::kExp0;
-                const uint64_t lsum = wave_reduce((uint64_t)(kExp0 ? body.exp_sum : body.clz_sum), OpAdd());
-                const uint32_t um = wave_reduce(kExp0 ? body.exp0_u_max() : body.u_max, OpMax());
-                const uint32_t nan = wave_reduce((uint32_t)body.nan_seen, OpOr());
-                if (lane == 0) {
-                    gg_rate_t r;
-                    r.n = (uint64_t)len; r.n_clamped = 0; r.entropy_bits = 0.0; r.delta = delta;
-                    if (ok) {
-                        r.eg_bits = kExp0 ? 2ull * lsum - 251ull * (uint64_t)len : (uint64_t)len * a.eg_const - 2ull * lsum;
-                        r.u_max = um;
-                        r.fl_bits = um ? 32u - (uint32_t)__builtin_clz(um) : 1u;
-                        r.flags = (nan ? GG_F_NONFINITE : 0u) | (um >= 2147483647u ? GG_F_SATURATED : 0u);
-                    } else {
-                        r.eg_bits = 0; r.u_max = 0; r.fl_bits = 0; r.flags = GG_F_DEGENERATE;
+            const float inv_delta = ok ? (float)(1.0 / (double)delta) : 0.f;
+            const bool pen_live = PEN && alpha > 0.f && isfinite(alpha) && isfinite(beta);
+            const float inv_alpha = pen_live ? (float)(1.0 / (double)alpha) : 0.f;
+            const float pen_coef = pen_live ? (float)((double)a.lambda * (double)beta / (double)alpha) : 0.f;
+            const float beta_m1 = pen_live ? beta - 1.0f : 0.f;
+#pragma unroll
+            for (int r = 0; r < kRowBatch; ++r) {
+                if (r >= nr) break;
+                const int64_t row = row0 + r, start = row * a.cols;
+                const float delta_r = __shfl(delta, r, 64);
+                const bool ok_r = __shfl((int)ok, r, 64) != 0;
+                QuantBody<MODE, RATE, PEN, EXTRA> body;
+                body.eg_add = a.eg_add;
+                body.symbols = a.symbols; body.grad = a.grad; body.accumulate = a.accumulate;
+                body.lds_hist = nullptr; body.ghist = nullptr; body.last_bin = 0; body.lbins = 0; body.hist_live = false;
+                body.inv_delta = __shfl(inv_delta, r, 64);
+                body.pen_live = __shfl((int)pen_live, r, 64) != 0;
+                body.inv_alpha = __shfl(inv_alpha, r, 64);
+                body.pen_coef = __shfl(pen_coef, r, 64);
+                body.beta_m1 = __shfl(beta_m1, r, 64);
+                if constexpr (sizeof(T) == 2 && (PEN || EXTRA))
+                    process_chunk<ElemBf16x4, 8, decltype(body), 64>(x, start, len, body);
+                else
+                    process_chunk<Elem<T>, 4, decltype(body), 64>(x, start, len, body);
+                if constexpr (RATE) {
+                    constexpr bool kExp0 = decltype(body)::kExp0;
+                    const uint64_t lsum = wave_reduce((uint64_t)(kExp0 ? body.exp_sum : body.clz_sum), OpAdd());
+                    const uint32_t um = wave_reduce(kExp0 ? body.exp0_u_max() : body.u_max, OpMax());
+                    const uint32_t nan = wave_reduce((uint32_t)body.nan_seen, OpOr());
+                    if (lane == 0) {
+                        gg_rate_t rr;
+                        rr.n = (uint64_t)len; rr.n_clamped = 0; rr.entropy_bits = 0.0; rr.delta = delta_r;
+                        if (ok_r) {
+                            rr.eg_bits = kExp0 ? 2ull * lsum - 251ull * (uint64_t)len : (uint64_t)len * a.eg_const - 2ull * lsum;
+                            rr.u_max = um;
+                            rr.fl_bits = um ? 32u - (uint32_t)__builtin_clz(um) : 1u;
+                            rr.flags = (nan ? GG_F_NONFINITE : 0u) | (um >= 2147483647u ? GG_F_SATURATED : 0u);
+                        } else {
+                            rr.eg_bits = 0; rr.u_max = 0; rr.fl_bits = 0; rr.flags = GG_F_DEGENERATE;
+                        }
+                        a.rate[row] = rr;
                     }
-                    a.rate[row] = r;
                 }
             }
         }
@@ -1307,10 +1371,17 @@ static int launch_seg_prepare(const Geometry &g, const PrepArgs &p, hipStream_t 
 
 // wave-per-row launch: enough blocks to fill the machine, each wave strides over rows
 template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
-static int launch_rows_inst(const void *x, const RowsArgs &a, hipStream_t st) {
+static int launch_rows_inst(const void *x, RowsArgs a, hipStream_t st) {
     const int bpc = resident_blocks(k_rows<T, MODE, RATE, PEN, EXTRA>, 0, 8);
-    int64_t blocks = (a.rows + kWaves - 1) / kWaves;
     const int64_t cap = (int64_t)kComputeUnits * bpc;
+    // Rows of a batch are read again from cache after the solve: keep a batch within kRowBatchBytes, and
+    // batch only while every resident wave still gets one.
+    int batch = 1;
+    while (batch < kRowBatch && a.cols * (int64_t)sizeof(T) * (2 * batch) <= kRowBatchBytes && a.rows >= cap * kWaves * (2 * batch))
+        batch *= 2;
+    a.batch = batch;
+    const int64_t per_block = (int64_t)kWaves * batch;
+    int64_t blocks = (a.rows + per_block - 1) / per_block;
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL((k_rows<T, MODE, RATE, PEN, EXTRA>), dim3((unsigned)blocks), dim3(kBlock), 0, st,
                        static_cast<const T *>(x), a);

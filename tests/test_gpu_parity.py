@@ -448,6 +448,37 @@ def test_fused_rows_activation_like(gg):
     assert np.array_equal(hist.cpu().numpy().view(np.uint64), ohist)
 
 
+@pytest.mark.parametrize("dtype,cols", [(torch.bfloat16, 100), (torch.float32, 67)])
+def test_fused_rows_taken_two_at_a_time(gg, dtype, cols):
+    """Matrices of many short rows: a wave takes two rows per turn and one lane per row solves the fit.
+    The odd row count leaves a last turn with a single row; the row length is no multiple of a vector."""
+    rows = 16387
+    x = make(rows * cols, 0.3, 1.2, seed=31, dtype=dtype)
+    # a constant row (no usable step) and a zero row in the middle of pairs
+    x.view(rows, cols)[5] = 0.25
+    x.view(rows, cols)[8] = 0.0
+    ws = gg.Workspace(rows * cols, rows)
+    grad = torch.zeros(rows * cols, device=DEV)
+    res = gg.gg_fused_rows(x, rows, cols, ws, delta_div=8.0, lam=1e-3, grad=grad, want_symbols=True)
+    frec, rrec = gg.fit_records(res["fit"]), gg.rate_records(res["rate"])
+    sym, g = res["symbols"].cpu().numpy(), res["grad"].cpu().numpy()
+    hb = host_bits(x)
+    picks = sorted(set([0, 1, 2, 3, 4, 5, 6, 7, 8, 9, rows - 3, rows - 2, rows - 1]) | set(range(11, rows, 997)))
+    for r_ in picks:
+        xs = hb[r_ * cols:(r_ + 1) * cols]
+        check_fit(frec[r_], oracle.fit(xs), f"row {r_}")
+        if r_ == 8:
+            assert int(rrec[r_]["flags"]) & gg.GG_F_DEGENERATE
+            continue
+        r, _, osym = oracle.quantize_rate(xs, float(rrec[r_]["delta"]), want_symbols=True)
+        check_rate(rrec[r_], r, f"row {r_}", entropy=False)
+        assert np.array_equal(sym[r_ * cols:(r_ + 1) * cols], osym)
+        check_penalty(g[r_ * cols:(r_ + 1) * cols], oracle.penalty_grad(xs, frec[r_]["alpha"], frec[r_]["beta"], 1e-3), f"row {r_}")
+    # every row, against the sums the records themselves must satisfy
+    assert np.all(frec["n"] == cols)
+    assert int(rrec["n"].astype(np.int64).sum()) == rows * cols
+
+
 def test_fit_only_and_penalty_only_fused_modes(gg):
     segs = gg_inputs.scaled_layout(gg_inputs.weights_7b()[:9], 2003)
     flat, off, _, _ = gg_inputs.make_bucket(segs, seed=4, device=DEV, dtype=torch.bfloat16, alpha_range=(0.005, 0.03),
