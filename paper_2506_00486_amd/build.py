@@ -22,6 +22,12 @@ PROBE = os.path.join(HERE, "probe_bandwidth")   # stand-alone measurement tool, 
 
 
 def build(verbose: bool = False) -> str:
+    sys.path.insert(0, CSRC)
+    try:
+        import gen_solve_curve
+    finally:
+        sys.path.pop(0)
+    gen_solve_curve.generate()                 # csrc/gg_solve_curve.inc, included by gg_kernels.hip
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
     cmd = [HIPCC] + FLAGS + ["-I", os.path.join(os.path.dirname(HERE), "include"), "-o", LIB] + srcs
     if verbose:

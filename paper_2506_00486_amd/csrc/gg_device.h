@@ -229,18 +229,6 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// ln Gamma(x) for x > 0 in fp64: push the argument above 7 with Gamma(x) = Gamma(x+1)/x, then the
-// Stirling series  (x-1/2) ln x - x + ln(2 pi)/2 + sum_k B_2k / (2k (2k-1) x^(2k-1)).
-// Truncation error at x >= 7 is below 7e-15 (first dropped term 0.0296 / x^15).
-__host__ __device__ __forceinline__ double lgamma_pos(double x) {
-    double prod = 1.0;
-    while (x < 7.0) { prod *= x; x += 1.0; }
-    const double xi = 1.0 / x, y = xi * xi;
-    const double series = xi * (1.0 / 12.0 - y * (1.0 / 360.0 - y * (1.0 / 1260.0 - y * (1.0 / 1680.0 -
-                          y * (1.0 / 1188.0 - y * (691.0 / 360360.0 - y * (1.0 / 156.0)))))));
-    return (x - 0.5) * log(x) - x + 0.91893853320467274178 + series - log(prod);
-}
-
 // top 23 bits of a word -> uniform in (0,1), exact in fp32
 __device__ __forceinline__ float unit_open(uint32_t w) {
     return ((float)(w >> 9) + 0.5f) * 0x1p-23f;

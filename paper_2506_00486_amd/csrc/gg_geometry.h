@@ -147,7 +147,7 @@ static __global__ void k_fill_u64(uint64_t *p, int64_t n) {
 // =============================================================================================
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-constexpr int kSolveTable = 4096;   // intervals of the tabulated moment-ratio curve (many-unit solves)
+constexpr int kSolveTable = 4096;   // intervals of the tabulated moment-ratio curve (gen_solve_curve.py reads this line)
 
 // What one run contributes to the rate record of a unit that several runs share; a later kernel folds the
 // slots into the record, so the sweep needs no atomics on a record that hundreds of blocks finish on at the
@@ -161,8 +161,8 @@ static_assert(sizeof(RatePiece) == 32, "two 16-byte stores");
 constexpr int64_t kMaxRuns = 256 * 512;  // most blocks a reducing sweep is split into
 
 struct WsLayout {
-    size_t off_bytes, params_bytes, partials_bytes, pieces_bytes, table_bytes, total;   // off_bytes: offsets + chunk prefix
-    size_t off_at, params_at, partials_at, pieces_at, table_at;
+    size_t off_bytes, params_bytes, partials_bytes, pieces_bytes, total;   // off_bytes: offsets + chunk prefix
+    size_t off_at, params_at, partials_at, pieces_at;
 };
 
 static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
@@ -177,9 +177,7 @@ static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
     w.partials_at = w.params_at + w.params_bytes;
     w.pieces_bytes = align_up((size_t)(max_chunks < (size_t)kMaxRuns ? max_chunks : (size_t)kMaxRuns) * 2 * sizeof(RatePiece), 256);   // runs <= chunks
     w.pieces_at = w.partials_at + w.partials_bytes;
-    w.table_bytes = align_up((size_t)(kSolveTable + 1) * sizeof(double2), 256);
-    w.table_at = w.pieces_at + w.pieces_bytes;
-    w.total = w.table_at + w.table_bytes;
+    w.total = w.pieces_at + w.pieces_bytes;
     return w;
 }
 
@@ -202,7 +200,6 @@ struct Geometry {
     SegParam *params() const { return reinterpret_cast<SegParam *>(ws + wl.params_at); }
     double2 *partials() const { return reinterpret_cast<double2 *>(ws + wl.partials_at); }
     RatePiece *rate_pieces() const { return reinterpret_cast<RatePiece *>(ws + wl.pieces_at); }
-    double2 *solve_table() const { return reinterpret_cast<double2 *>(ws + wl.table_at); }
 };
 
 static int geometry_uniform(int64_t rows, int64_t cols, void *ws, size_t ws_bytes, bool need_ws, Geometry &g) {

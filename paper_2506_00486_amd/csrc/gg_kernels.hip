@@ -112,15 +112,6 @@ __global__ __launch_bounds__(kBlock) void k_fit_partials(SegView sv, const T *__
     flush(piece_first);
 }
 
-// log of the moment ratio rho(b) = Gamma(2/b)^2 / (Gamma(1/b) Gamma(3/b)) of a GGD (from Eq. 1, 3)
-__device__ __forceinline__ double log_rho(double b, double &g1_minus_g3) {
-    const double r = 1.0 / b;
-    const double g1 = lgamma_pos(r), g3 = lgamma_pos(3.0 * r);
-    g1_minus_g3 = g1 - g3;      // the log of the scale factor of Eq. 2 comes for free
-    return 2.0 * lgamma_pos(2.0 * r) - g1 - g3;
-}
-__device__ __forceinline__ double log_rho(double b) { double unused; return log_rho(b, unused); }
-
 // cubic Lagrange through (xs[k], ys[k]), k = 0..3, evaluated at x, over the common denominator: one division.
 // The node differences here are 1e-5 .. 1 (table values a grid step apart), so the products stay far inside
 // the fp64 range.
@@ -146,75 +137,17 @@ __device__ __forceinline__ double lagrange4_uniform(double x0, double h, const d
            ys[3] * (t0 * t1 * t2) * (1.0 / 6.0);
 }
 
-// log_rho at the ends of the supported shape range, evaluated once on the host
-struct SolveConst { double lrho_min, lrho_max; };
-
-// Wave-cooperative fit from the moments.  The root of log_rho(b) = log(rho_hat) is bracketed by
-// evaluating 64 log-spaced shapes at once (one per lane); each round shrinks the bracket 65-fold.
-// Must be called by all 64 lanes of a wave with identical arguments.
-__device__ __forceinline__ void solve_fit(double s1, double s2, uint64_t n, const SolveConst &sc, gg_fit_t &f) {
-    const int lane = threadIdx.x & 63;
-    f.sum_abs = s1; f.sum_sq = s2; f.n = n; f.beta = 0.f; f.alpha = 0.f; f.flags = 0; f._pad = 0;
-    if (n == 0) { f.flags = GG_F_EMPTY; return; }
-    if (!isfinite(s1) || !isfinite(s2)) { f.flags = GG_F_NONFINITE; f.beta = 2.f; return; }
-    if (s2 == 0.0) { f.flags = GG_F_DEGENERATE; f.beta = 2.f; return; }
-    const double m1 = s1 / (double)n, m2 = s2 / (double)n;
-    const double target = log(m1 * m1 / m2);
-    double b;
-    if (!(target > sc.lrho_min)) {
-        b = GG_BETA_MIN; f.flags = GG_F_BETA_CLAMPED_LO;
-    } else if (!(target < sc.lrho_max)) {
-        b = GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI;
-    } else {
-        // Two rounds of 64 log-spaced candidates shrink the bracket in l = ln b to ln(400)/65^2 = 1.4e-3;
-        // the four candidates of the second round around the root then give l by inverse cubic
-        // interpolation (7e-12 relative in b at this spacing) and, through the same points, the log of
-        // the scale factor of Eq. 2.
-        double llo = log(GG_BETA_MIN), lhi = log(GG_BETA_MAX);
-        double cand = 0.0, fv = 0.0, a13 = 0.0;
-        int cnt = 0;
-        for (int round = 0; round < 2; ++round) {
-            const double step = (lhi - llo) * (1.0 / 65.0);
-            cand = llo + step * (double)(lane + 1);
-            fv = log_rho(exp(cand), a13) - target;             // rho increases with b
-            cnt = __popcll(__ballot(fv < 0.0));                // candidates below the root: lanes 0..cnt-1
-            if (round == 0) {
-                const double c_lo = __shfl(cand, cnt > 0 ? cnt - 1 : 0, 64), c_hi = __shfl(cand, cnt < 64 ? cnt : 63, 64);
-                if (cnt > 0) llo = c_lo;
-                if (cnt < 64) lhi = c_hi;
-            }
-        }
-        int j0 = cnt - 2;
-        j0 = j0 < 0 ? 0 : (j0 > 60 ? 60 : j0);
-        double ls[4], fs[4], as[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            ls[k] = __shfl(cand, j0 + k, 64); fs[k] = __shfl(fv, j0 + k, 64); as[k] = __shfl(a13, j0 + k, 64);
-        }
-        const double l = lagrange4(fs, ls, 0.0);
-        f.beta = (float)exp(l);
-        f.alpha = (float)sqrt(m2 * exp(lagrange4_uniform(ls[0], ls[1] - ls[0], as, l)));   // Eq. 2 with sigma^2 = m2
-        return;
-    }
-    const double r = 1.0 / b;
-    f.beta = (float)b;
-    f.alpha = (float)sqrt(m2 * exp(lgamma_pos(r) - lgamma_pos(3.0 * r)));   // Eq. 2 with sigma^2 = m2
-}
-
-// Buffers cut into thousands of units (rows of an activation matrix) make the solve itself the
-// bottleneck: 64 fp64 lgamma-based evaluations per round and unit are ~2500 fp64 instructions per
-// wave.  For those the moment-ratio curve is tabulated once per call on a uniform grid in l = ln b,
-//   table[j] = { log_rho(b_j), lgamma(1/b_j) - lgamma(3/b_j) },  b_j = exp(l_min + j h),  j = 0..kSolveTable,
-// and a unit's root is found by locating its interval and inverse cubic interpolation through the
-// four surrounding points (error 7e-12 relative in b, 2e-10 in the log of the scale factor).
-__global__ void k_build_solve_table(double2 *__restrict__ table) {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j > kSolveTable) return;
-    const double l_min = log(GG_BETA_MIN), h = (log(GG_BETA_MAX) - l_min) / (double)kSolveTable;
-    const double r = 1.0 / exp(l_min + h * (double)j);
-    const double g1 = lgamma_pos(r), g3 = lgamma_pos(3.0 * r);
-    table[j] = make_double2(2.0 * lgamma_pos(2.0 * r) - g1 - g3, g1 - g3);
-}
+// The moment ratio of a GGD is rho(b) = Gamma(2/b)^2 / (Gamma(1/b) Gamma(3/b)) (from Eq. 1, 3).  Its curve is
+// tabulated at build time (gen_solve_curve.py) on a uniform grid in l = ln b,
+//   kSolveCurve[j] = { ln rho(b_j), lgamma(1/b_j) - lgamma(3/b_j) },  b_j = exp(l_min + j h),  j = 0..kSolveTable,
+// and a unit's root is found by locating its interval (two 64-way probes by a wave, or a binary search by a
+// lane) and inverse cubic interpolation through the four surrounding points: error 7e-12 relative in b,
+// 2e-10 in the log of the scale factor of Eq. 2.  No launch, no workspace and no run-time state: the curve
+// is part of the code object.
+struct alignas(16) CurvePoint { double x, y; };
+__device__ const CurvePoint kSolveCurve[kSolveTable + 1] = {
+#include "gg_solve_curve.inc"
+};
 
 // beta and alpha from four consecutive table points j0 .. j0+3 around the root
 __device__ __forceinline__ void finish_from_points(int j0, const double (&fs)[4], const double (&as)[4], double target, double m2,
@@ -234,21 +167,19 @@ __device__ __forceinline__ int first_point(int j) {
     return j0 < 0 ? 0 : (j0 > kSolveTable - 3 ? kSolveTable - 3 : j0);
 }
 
-__device__ __forceinline__ void finish_from_table(const double2 *__restrict__ table, int j, double target, double m2,
-                                                  gg_fit_t &f) {
+__device__ __forceinline__ void finish_from_table(int j, double target, double m2, gg_fit_t &f) {
     const int j0 = first_point(j);
     double fs[4], as[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const double2 t = table[j0 + k];
+        const CurvePoint t = kSolveCurve[j0 + k];
         fs[k] = t.x; as[k] = t.y;
     }
     finish_from_points(j0, fs, as, target, m2, f);
 }
 
 // common head of the table solvers; returns true when the root has to be searched
-__device__ __forceinline__ bool fit_head(double s1, double s2, uint64_t n, const SolveConst &sc, gg_fit_t &f,
-                                         double &target, double &m2) {
+__device__ __forceinline__ bool fit_head(double s1, double s2, uint64_t n, gg_fit_t &f, double &target, double &m2) {
     f.sum_abs = s1; f.sum_sq = s2; f.n = n; f.beta = 0.f; f.alpha = 0.f; f.flags = 0; f._pad = 0;
     if (n == 0) { f.flags = GG_F_EMPTY; return false; }
     if (!isfinite(s1) || !isfinite(s2)) { f.flags = GG_F_NONFINITE; f.beta = 2.f; return false; }
@@ -256,41 +187,39 @@ __device__ __forceinline__ bool fit_head(double s1, double s2, uint64_t n, const
     const double m1 = s1 / (double)n;
     m2 = s2 / (double)n;
     target = log(m1 * m1 / m2);
-    double b = 0.0;
-    if (!(target > sc.lrho_min)) { b = GG_BETA_MIN; f.flags = GG_F_BETA_CLAMPED_LO; }
-    else if (!(target < sc.lrho_max)) { b = GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI; }
+    // outside the curve the shape is clamped to the end of the supported range; Eq. 2 then takes that end's factor
+    int end;
+    if (!(target > kSolveCurve[0].x)) { end = 0; f.beta = (float)GG_BETA_MIN; f.flags = GG_F_BETA_CLAMPED_LO; }
+    else if (!(target < kSolveCurve[kSolveTable].x)) { end = kSolveTable; f.beta = (float)GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI; }
     else return true;
-    const double r = 1.0 / b;
-    f.beta = (float)b;
-    f.alpha = (float)sqrt(m2 * exp(lgamma_pos(r) - lgamma_pos(3.0 * r)));
+    f.alpha = (float)sqrt(m2 * exp(kSolveCurve[end].y));
     return false;
 }
 
 // one lane per unit: binary search of the interval
-__device__ __forceinline__ void solve_fit_table_lane(double s1, double s2, uint64_t n, const SolveConst &sc,
-                                                     const double2 *__restrict__ table, gg_fit_t &f) {
+__device__ __forceinline__ void solve_fit_lane(double s1, double s2, uint64_t n, gg_fit_t &f) {
+    const CurvePoint *__restrict__ table = kSolveCurve;
     double target, m2;
-    if (!fit_head(s1, s2, n, sc, f, target, m2)) return;
+    if (!fit_head(s1, s2, n, f, target, m2)) return;
     int lo = 0, hi = kSolveTable;            // table[lo].x <= target < table[hi].x
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (table[mid].x <= target) lo = mid; else hi = mid;
     }
-    finish_from_table(table, lo, target, m2, f);
+    finish_from_table(lo, target, m2, f);
 }
 
 // one wave per unit (all 64 lanes, identical arguments): two rounds of 64 probes locate the interval
-__device__ __forceinline__ void solve_fit_table_wave(double s1, double s2, uint64_t n, const SolveConst &sc,
-                                                     const double2 *__restrict__ table, gg_fit_t &f) {
+__device__ __forceinline__ void solve_fit_wave(double s1, double s2, uint64_t n, gg_fit_t &f) {
     static_assert(kSolveTable == 64 * 64, "two 64-way rounds cover the table");
+    const CurvePoint *__restrict__ table = kSolveCurve;
     const int lane = threadIdx.x & 63;
     double target, m2;
-    if (!fit_head(s1, s2, n, sc, f, target, m2)) return;
-    // table[0].x < target by fit_head up to rounding of the two lgamma implementations: clamp the counts
+    if (!fit_head(s1, s2, n, f, target, m2)) return;
     int c1 = __popcll(__ballot(table[64 * lane].x <= target));
     c1 = c1 < 1 ? 1 : c1;
     const int coarse = 64 * (c1 - 1);
-    const double2 t2 = table[coarse + lane];
+    const CurvePoint t2 = table[coarse + lane];
     int c2 = __popcll(__ballot(t2.x <= target));
     c2 = c2 < 1 ? 1 : c2;
     const int j0 = first_point(coarse + c2 - 1);
@@ -300,7 +229,7 @@ __device__ __forceinline__ void solve_fit_table_wave(double s1, double s2, uint6
         for (int k = 0; k < 4; ++k) { fs[k] = __shfl(t2.x, j0 - coarse + k, 64); as[k] = __shfl(t2.y, j0 - coarse + k, 64); }
         finish_from_points(j0, fs, as, target, m2, f);
     } else {
-        finish_from_table(table, coarse + c2 - 1, target, m2, f);
+        finish_from_table(coarse + c2 - 1, target, m2, f);
     }
 }
 
@@ -309,13 +238,13 @@ __device__ __forceinline__ void solve_fit_table_wave(double s1, double s2, uint6
 // the fp64 work in front of it (logarithm of the moment ratio) and behind it (interpolation, Eq. 2) is done
 // once, lane r working for unit r.  Must be called by all 64 lanes.
 constexpr int kRowBatch = GG_ROW_BATCH;
-__device__ __forceinline__ void solve_fit_table_batch(double s1, double s2, uint64_t n, int nr, const SolveConst &sc,
-                                                      const double2 *__restrict__ table, gg_fit_t &f) {
+__device__ __forceinline__ void solve_fit_batch(double s1, double s2, uint64_t n, int nr, gg_fit_t &f) {
     static_assert(kSolveTable == 64 * 64, "two 64-way rounds cover the table");
+    const CurvePoint *__restrict__ table = kSolveCurve;
     const int lane = threadIdx.x & 63;
     double target = 0.0, m2 = 0.0;
     bool search = false;
-    if (lane < nr) search = fit_head(s1, s2, n, sc, f, target, m2);
+    if (lane < nr) search = fit_head(s1, s2, n, f, target, m2);
     const double probe = table[64 * lane].x;
     double tr[kRowBatch];
     int coarse[kRowBatch];
@@ -335,7 +264,7 @@ __device__ __forceinline__ void solve_fit_table_batch(double s1, double s2, uint
         c2 = c2 < 1 ? 1 : c2;
         if (lane == r) j = coarse[r] + c2 - 1;
     }
-    if (search) finish_from_table(table, j, target, m2, f);
+    if (search) finish_from_table(j, target, m2, f);
 }
 
 // where the step and the penalty parameters of a unit come from
@@ -381,7 +310,7 @@ __device__ __forceinline__ void prepare_unit(const PrepArgs &a, int seg, int64_t
 
 __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *__restrict__ partials,
                                                      int32_t chunks_per_block, gg_fit_t *__restrict__ out,
-                                                     SolveConst sc, PrepArgs prep, int do_prep) {
+                                                     PrepArgs prep, int do_prep) {
     const int seg = blockIdx.x, lane = threadIdx.x;
     const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
     double s1 = 0.0, s2 = 0.0;
@@ -399,7 +328,7 @@ __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *
     s2 = wave_reduce(s2, OpAdd());
     const int64_t n = unit_len(sv, seg);
     gg_fit_t f;
-    solve_fit(s1, s2, (uint64_t)n, sc, f);
+    solve_fit_wave(s1, s2, (uint64_t)n, f);
     if (lane == 0) {
         out[seg] = f;
         if (do_prep) prepare_unit(prep, seg, n, f.alpha, f.beta);
@@ -409,7 +338,6 @@ __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *
 // the same finalisation with one lane per unit (many small units)
 __global__ __launch_bounds__(64) void k_fit_finalize_lanes(SegView sv, const double2 *__restrict__ partials,
                                                            int32_t chunks_per_block, gg_fit_t *__restrict__ out,
-                                                           SolveConst sc, const double2 *__restrict__ table,
                                                            PrepArgs prep, int do_prep) {
     const int seg = blockIdx.x * 64 + threadIdx.x;
     if (seg >= sv.S) return;
@@ -425,7 +353,7 @@ __global__ __launch_bounds__(64) void k_fit_finalize_lanes(SegView sv, const dou
     }
     const int64_t n = unit_len(sv, seg);
     gg_fit_t f;
-    solve_fit_table_lane(s1, s2, (uint64_t)n, sc, table, f);
+    solve_fit_lane(s1, s2, (uint64_t)n, f);
     out[seg] = f;
     if (do_prep) prepare_unit(prep, seg, n, f.alpha, f.beta);
 }
@@ -434,8 +362,7 @@ __global__ __launch_bounds__(64) void k_fit_finalize_lanes(SegView sv, const dou
 // block, solve by the first wave
 constexpr int kTotalThreads = 1024;
 __global__ __launch_bounds__(kTotalThreads) void k_fit_total(const gg_fit_t *__restrict__ rows, int64_t n_rows,
-                                                             gg_fit_t *__restrict__ out, SolveConst sc,
-                                                             const double2 *__restrict__ table) {
+                                                             gg_fit_t *__restrict__ out) {
     __shared__ double red1[kTotalThreads / 64], red2[kTotalThreads / 64];
     __shared__ uint64_t redn[kTotalThreads / 64];
     const int tid = threadIdx.x;
@@ -451,8 +378,7 @@ __global__ __launch_bounds__(kTotalThreads) void k_fit_total(const gg_fit_t *__r
         s1 = 0.0; s2 = 0.0; n = 0;
         for (int w = 0; w < kTotalThreads / 64; ++w) { s1 += red1[w]; s2 += red2[w]; n += redn[w]; }
         gg_fit_t f;
-        if (table) solve_fit_table_wave(s1, s2, n, sc, table, f);   // the caller has tabulated the curve already
-        else solve_fit(s1, s2, n, sc, f);
+        solve_fit_wave(s1, s2, n, f);
         if (tid == 0) out[0] = f;
     }
 }
@@ -881,8 +807,6 @@ struct RowsArgs {
     int32_t *symbols; float *grad; int accumulate;
     int do_fit;
     int batch;                // rows per wave and solve, 1..kRowBatch (set by the launcher)
-    SolveConst sc;
-    const double2 *table;     // tabulated moment-ratio curve (see k_build_solve_table)
 };
 
 template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
@@ -910,7 +834,7 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
                 if (lane == r) { my_s1 = s1; my_s2 = s2; }
             }
             gg_fit_t f;
-            solve_fit_table_batch(my_s1, my_s2, (uint64_t)len, nr, a.sc, a.table, f);
+            solve_fit_batch(my_s1, my_s2, (uint64_t)len, nr, f);
             if (lane < nr) { a.fit[row0 + lane] = f; alpha = f.alpha; beta = f.beta; }
         }
         if constexpr (RATE || PEN) {
@@ -1200,11 +1124,6 @@ __global__ __launch_bounds__(kBlock) void k_philox_words(uint32_t *__restrict__ 
 // =============================================================================================
 // host side
 // =============================================================================================
-static SolveConst solve_const() {
-    auto lrho = [](double b) { return 2.0 * lgamma(2.0 / b) - lgamma(1.0 / b) - lgamma(3.0 / b); };
-    return SolveConst{lrho(GG_BETA_MIN), lrho(GG_BETA_MAX)};
-}
-
 // Runs (blocks) per compute unit of the sweeps that reduce.  With no atomics in their epilogues (fit: one
 // slot per piece; rate: records or run slots) several waves of blocks per compute unit balance the finish
 // times better than one resident wave: 32-96 measured 1.5 % faster than 8 on the 1.5 G-element bucket, 128
@@ -1230,12 +1149,11 @@ static int launch_fit_finalize(const Geometry &g, int32_t chunks_per_block, gg_f
     PrepArgs p{};
     if (prep) p = *prep;
     if (g.S >= kManyUnits) {
-        hipLaunchKernelGGL(k_build_solve_table, dim3((kSolveTable + 256) / 256), dim3(256), 0, st, g.solve_table());
         hipLaunchKernelGGL(k_fit_finalize_lanes, dim3((unsigned)((g.S + 63) / 64)), dim3(64), 0, st, g.sv, g.partials(),
-                           chunks_per_block, out, solve_const(), g.solve_table(), p, prep ? 1 : 0);
+                           chunks_per_block, out, p, prep ? 1 : 0);
     } else {
         hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(), chunks_per_block, out,
-                           solve_const(), p, prep ? 1 : 0);
+                           p, prep ? 1 : 0);
     }
     return check_launch();
 }
@@ -1405,12 +1323,7 @@ static bool rows_take_wave_path(int64_t rows, int64_t cols) { return rows > 0 &&
 
 static int launch_rows(const Geometry &g, const void *x, int dtype, RowsArgs a, int eg_k, int round_mode, bool rate, bool pen,
                        hipStream_t st) {
-    a.eg_add = 1u << eg_k; a.eg_const = 63u - (uint32_t)eg_k; a.sc = solve_const();
-    if (a.do_fit) {
-        a.table = g.solve_table();
-        hipLaunchKernelGGL(k_build_solve_table, dim3((kSolveTable + 256) / 256), dim3(256), 0, st, g.solve_table());
-        if (check_launch() != GG_OK) return GG_ERR_HIP;
-    }
+    a.eg_add = 1u << eg_k; a.eg_const = 63u - (uint32_t)eg_k;
     const bool extra = a.symbols != nullptr;
     return by_dtype(dtype, [&](auto *tag) {
         using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
@@ -1463,16 +1376,14 @@ static int fused_common(Geometry &g, const void *x, int dtype, float delta_div, 
         if ((rc = run_second_sweep(g, x, dtype, o, st)) != GG_OK) return rc;
         if ((rc = launch_fit_finalize(g, o.chunks_per_block_out, fit, nullptr, st)) != GG_OK) return rc;
         if (total_fit) {
-            hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit, (int64_t)g.S, total_fit, solve_const(),
-                               (const double2 *)(g.S >= kManyUnits ? g.solve_table() : nullptr));
+            hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit, (int64_t)g.S, total_fit);
             return check_launch();
         }
         return GG_OK;
     }
     if ((rc = launch_fit(g, x, dtype, fit, &p, st)) != GG_OK) return rc;
     if (total_fit) {
-        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit, (int64_t)g.S, total_fit, solve_const(),
-                           (const double2 *)(g.S >= kManyUnits ? g.solve_table() : nullptr));
+        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit, (int64_t)g.S, total_fit);
         if ((rc = check_launch()) != GG_OK) return rc;
     }
     QuantOpts o;
@@ -1564,8 +1475,7 @@ int gg_fit_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, gg_fit
     }
     if (rc != GG_OK) return rc;
     if (total_out_dev) {
-        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, out_dev, rows, total_out_dev, solve_const(),
-                           (const double2 *)((rows_take_wave_path(rows, cols) || rows >= kManyUnits) ? g.solve_table() : nullptr));
+        hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, out_dev, rows, total_out_dev);
         return check_launch();
     }
     return GG_OK;
@@ -1773,8 +1683,7 @@ int gg_fused_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, floa
         a.do_fit = 1;
         if ((rc = launch_rows(g, x_dev, dtype, a, eg_k, round_mode, rate_dev != nullptr, grad_dev != nullptr, st)) != GG_OK) return rc;
         if (total_fit_dev) {
-            hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit_dev, rows, total_fit_dev, solve_const(),
-                               (const double2 *)g.solve_table());
+            hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit_dev, rows, total_fit_dev);
             return check_launch();
         }
         return GG_OK;
