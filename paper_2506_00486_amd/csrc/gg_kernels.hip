@@ -985,9 +985,17 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, 
     if (live) {
         const uint64_t *g = hist + (int64_t)seg * nbins;
         const double inv_n = 1.0 / (double)n;
-        for (int b = tid; b < nbins; b += kFinalizeThreads) {   // ascending bins per lane, fixed tree above
-            const uint64_t c = g[b];
-            if (c) { const double p = (double)c * inv_n; h -= p * log2(p); }
+        // ascending bins per lane, fixed tree above; eight loads in flight, the terms still added in bin order
+        for (int b0 = tid; b0 < nbins; b0 += 8 * kFinalizeThreads) {
+            uint64_t c[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int b = b0 + k * kFinalizeThreads;
+                c[k] = b < nbins ? g[b] : 0;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (c[k]) { const double p = (double)c[k] * inv_n; h -= p * log2(p); }
         }
     }
     h = wave_reduce(h, OpAdd());
