@@ -23,8 +23,8 @@ ALGO_BYTES_PER_ELEM = 8.0      # fp32 bucket: 4 B read by the moment sweep + 4 B
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this same command, scaled by a plain-copy calibration; the summaries live under profiles/.
 # None until measured for the kernel that currently ships.
-MEASURED_TRAFFIC_BYTES = 6174872986 + 510259   # k_quant on the 1,543,655,424-element bucket: FETCH_SIZE 3015074.7 x 2 KiB
-#                                                (factor from a 1 GiB copy) + WRITE_SIZE 498.3 KiB; profiles/k_quant_c4_bucket.md
+MEASURED_TRAFFIC_BYTES = 6174859674 + 510157   # k_quant on the 1,543,655,424-element bucket: FETCH_SIZE 3015068.2 x 2 KiB
+#                                                (factor from a 1 GiB copy) + WRITE_SIZE 498.2 KiB; profiles/k_quant_c4_bucket.md
 
 
 def parse():
