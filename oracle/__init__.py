@@ -39,57 +39,65 @@ class Rate(C.Structure):
 _lib = None
 
 
+def load(path: str):
+    """Opens a build of gg_oracle.c and declares its signatures (the tests also load altered builds this way)."""
+    L = C.CDLL(path)
+    vp, i32, i64, u32, u64, f32, f64 = (C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64,
+                                        C.c_float, C.c_double)
+    L.orc_rho.restype = f64
+    L.orc_rho.argtypes = [f64]
+    L.orc_solve_beta.restype = f64
+    L.orc_solve_beta.argtypes = [f64, C.POINTER(u32)]
+    L.orc_alpha_from_m2.restype = f64
+    L.orc_alpha_from_m2.argtypes = [f64, f64]
+    L.orc_init_alpha.restype = f64
+    L.orc_init_alpha.argtypes = [i64, f64, f64]
+    L.orc_moments.restype = None
+    L.orc_moments.argtypes = [vp, C.c_int, i64, C.POINTER(f64), C.POINTER(f64)]
+    L.orc_fit_from_moments.restype = None
+    L.orc_fit_from_moments.argtypes = [f64, f64, u64, C.POINTER(Fit)]
+    L.orc_fit.restype = None
+    L.orc_fit.argtypes = [vp, C.c_int, i64, C.POINTER(Fit)]
+    L.orc_quantize_one.restype = i32
+    L.orc_quantize_one.argtypes = [f32, f32, C.c_int, C.POINTER(u32)]
+    L.orc_map.restype = u32
+    L.orc_map.argtypes = [i32]
+    L.orc_eg_len.restype = u32
+    L.orc_eg_len.argtypes = [u32, C.c_int]
+    L.orc_quantize_rate.restype = None
+    L.orc_quantize_rate.argtypes = [vp, C.c_int, i64, f32, C.c_int, C.c_int, i32, vp, vp, C.POINTER(Rate)]
+    L.orc_penalty_grad.restype = None
+    L.orc_penalty_grad.argtypes = [vp, C.c_int, i64, f32, f32, f32, vp, C.c_int]
+    L.orc_philox4x32_10.restype = None
+    L.orc_philox4x32_10.argtypes = [C.POINTER(u32), C.POINTER(u32), C.POINTER(u32)]
+    L.orc_sample.restype = None
+    L.orc_sample.argtypes = [vp, C.c_int, i64, f32, f32, u64, u32, u64]
+    L.orc_round_bf16.restype = None
+    L.orc_round_bf16.argtypes = [vp, i64, vp]
+    L.orc_sample_attempts.restype = u64
+    L.orc_sample_attempts.argtypes = [i64, f32, u64, u32, u64]
+    L.orc_fused_segmented.restype = None
+    L.orc_fused_segmented.argtypes = [vp, C.c_int, vp, i32, f32, vp, C.c_int, C.c_int, f32, vp, C.c_int,
+                                      C.POINTER(Fit), C.POINTER(Rate)]
+    L.orc_gct_update.restype = None
+    L.orc_gct_update.argtypes = [vp, vp, vp, i64, f32, f32, f32, f32, C.c_int, i64, C.c_int]
+    L.orc_eg_encode.restype = u64
+    L.orc_eg_encode.argtypes = [vp, i64, C.c_int, vp, u64]
+    L.orc_eg_decode.restype = i64
+    L.orc_eg_decode.argtypes = [vp, u64, C.c_int, vp, i64]
+    L.orc_huffman_mean_bits.restype = f64
+    L.orc_huffman_mean_bits.argtypes = [vp, i32]
+    L.orc_rate_grad.restype = None
+    L.orc_rate_grad.argtypes = [vp, C.c_int, i64, f32, C.c_int, i64, f32, vp, C.c_int]
+    L.orc_compression_ratio.restype = f64
+    L.orc_compression_ratio.argtypes = [f64, f64]
+    return L
+
+
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
-        L = C.CDLL(path)
-        vp, i32, i64, u32, u64, f32, f64 = (C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64,
-                                            C.c_float, C.c_double)
-        L.orc_rho.restype = f64
-        L.orc_rho.argtypes = [f64]
-        L.orc_solve_beta.restype = f64
-        L.orc_solve_beta.argtypes = [f64, C.POINTER(u32)]
-        L.orc_alpha_from_m2.restype = f64
-        L.orc_alpha_from_m2.argtypes = [f64, f64]
-        L.orc_init_alpha.restype = f64
-        L.orc_init_alpha.argtypes = [i64, f64, f64]
-        L.orc_moments.restype = None
-        L.orc_moments.argtypes = [vp, C.c_int, i64, C.POINTER(f64), C.POINTER(f64)]
-        L.orc_fit_from_moments.restype = None
-        L.orc_fit_from_moments.argtypes = [f64, f64, u64, C.POINTER(Fit)]
-        L.orc_fit.restype = None
-        L.orc_fit.argtypes = [vp, C.c_int, i64, C.POINTER(Fit)]
-        L.orc_quantize_one.restype = i32
-        L.orc_quantize_one.argtypes = [f32, f32, C.c_int, C.POINTER(u32)]
-        L.orc_map.restype = u32
-        L.orc_map.argtypes = [i32]
-        L.orc_eg_len.restype = u32
-        L.orc_eg_len.argtypes = [u32, C.c_int]
-        L.orc_quantize_rate.restype = None
-        L.orc_quantize_rate.argtypes = [vp, C.c_int, i64, f32, C.c_int, C.c_int, i32, vp, vp, C.POINTER(Rate)]
-        L.orc_penalty_grad.restype = None
-        L.orc_penalty_grad.argtypes = [vp, C.c_int, i64, f32, f32, f32, vp, C.c_int]
-        L.orc_philox4x32_10.restype = None
-        L.orc_philox4x32_10.argtypes = [C.POINTER(u32), C.POINTER(u32), C.POINTER(u32)]
-        L.orc_sample.restype = None
-        L.orc_sample.argtypes = [vp, C.c_int, i64, f32, f32, u64, u32, u64]
-        L.orc_fused_segmented.restype = None
-        L.orc_fused_segmented.argtypes = [vp, C.c_int, vp, i32, f32, vp, C.c_int, C.c_int, f32, vp, C.c_int,
-                                          C.POINTER(Fit), C.POINTER(Rate)]
-        L.orc_gct_update.restype = None
-        L.orc_gct_update.argtypes = [vp, vp, vp, i64, f32, f32, f32, f32, C.c_int, i64, C.c_int]
-        L.orc_eg_encode.restype = u64
-        L.orc_eg_encode.argtypes = [vp, i64, C.c_int, vp, u64]
-        L.orc_eg_decode.restype = i64
-        L.orc_eg_decode.argtypes = [vp, u64, C.c_int, vp, i64]
-        L.orc_huffman_mean_bits.restype = f64
-        L.orc_huffman_mean_bits.argtypes = [vp, i32]
-        L.orc_rate_grad.restype = None
-        L.orc_rate_grad.argtypes = [vp, C.c_int, i64, f32, C.c_int, i64, f32, vp, C.c_int]
-        L.orc_compression_ratio.restype = f64
-        L.orc_compression_ratio.argtypes = [f64, f64]
-        _lib = L
+        _lib = load(_build.build(force=False))
     return _lib
 
 
@@ -203,6 +211,19 @@ def sample(n: int, alpha: float, beta: float, seed: int, stream: int = 0, offset
     lib().orc_sample(_ptr(out), dtype, n, _f32(alpha), _f32(beta), int(seed), int(stream),
                      int(offset))
     return out
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns of fp32 values, as sample(dtype=BF16) rounds them."""
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    out = np.empty(x.size, dtype=np.uint16)
+    lib().orc_round_bf16(_ptr(x), x.size, _ptr(out))
+    return out
+
+
+def sample_attempts(n: int, beta: float, seed: int, stream: int = 0, offset: int = 0) -> int:
+    """Attempts the rejection step takes over the n draws that sample() makes with the same arguments."""
+    return int(lib().orc_sample_attempts(n, _f32(beta), int(seed), int(stream), int(offset)))
 
 
 def fused_segmented(x: np.ndarray, offsets, delta_div: float = 16.0, delta: np.ndarray = None,

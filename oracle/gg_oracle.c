@@ -40,6 +40,12 @@ static uint16_t to_bf16(float f)
     return (uint16_t)(bits >> 16);
 }
 
+/* the rounding the sampler applies to its bf16 outputs, on an array (for the tests) */
+void orc_round_bf16(const float *x, int64_t n, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = to_bf16(x[i]);
+}
+
 /* ------------------------------------------------------------------------- */
 /* GG statistics                                                              */
 /* ------------------------------------------------------------------------- */
@@ -318,35 +324,54 @@ static double unit_open(uint32_t w)
  *   counter = {attempt, stream, lo(index), hi(index)}, key = {lo(seed), hi(seed)}:
  * words 0,1 -> Box-Muller normal, word 2 -> acceptance uniform; word 3 of
  * attempt 0 gives the sign (bit 0) and the boost uniform (top 23 bits). */
+
+/* Shape a = 1/beta of the Gamma variate and the constants of its generator; returns whether the
+ * draw is made at shape a + 1 and boosted down (a < 1). */
+static int gamma_constants(float beta, double *a, double *d, double *c)
+{
+    *a = 1.0 / (double)beta;
+    int boost = *a < 1.0;
+    *d = (boost ? *a + 1.0 : *a) - 1.0 / 3.0;
+    *c = 1.0 / sqrt(9.0 * *d);
+    return boost;
+}
+
+/* The attempts of element `idx`: returns d*v of the accepted attempt (d if all ORC_MAX_ATTEMPTS are
+ * rejected: probability < 1e-80), word 3 of attempt 0 in *w3_first, the attempts used in *used. */
+static double gamma_by_attempts(double d, double c, uint64_t idx, uint32_t stream, const uint32_t key[2],
+                                uint32_t *w3_first, uint32_t *used)
+{
+    const double two_pi = 6.283185307179586476925286766559;
+    *w3_first = 0;
+    for (uint32_t attempt = 0; attempt < ORC_MAX_ATTEMPTS; ++attempt) {
+        uint32_t ctr[4] = {attempt, stream, (uint32_t)idx, (uint32_t)(idx >> 32)};
+        uint32_t w[4];
+        orc_philox4x32_10(ctr, key, w);
+        if (attempt == 0) *w3_first = w[3];
+        double z = sqrt(-2.0 * log(unit_open(w[0]))) * cos(two_pi * unit_open(w[1]));
+        double t = 1.0 + c * z;
+        double v = t * t * t;
+        if (v <= 0.0) continue;
+        double lu = log(unit_open(w[2]));
+        if (lu < 0.5 * z * z + d - d * v + d * log(v)) {
+            *used = attempt + 1;
+            return d * v;
+        }
+    }
+    *used = ORC_MAX_ATTEMPTS;
+    return d;
+}
+
 void orc_sample(void *out, int dtype, int64_t n, float alpha, float beta,
                 uint64_t seed, uint32_t stream, uint64_t offset)
 {
-    const double two_pi = 6.283185307179586476925286766559;
-    double a = 1.0 / (double)beta;
-    int boost = a < 1.0;
-    double d = (boost ? a + 1.0 : a) - 1.0 / 3.0;
-    double c = 1.0 / sqrt(9.0 * d);
+    double a, d, c;
+    int boost = gamma_constants(beta, &a, &d, &c);
     uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
 
     for (int64_t i = 0; i < n; ++i) {
-        uint64_t idx = offset + (uint64_t)i;
-        double gam = d; /* fallback if every attempt is rejected (probability < 1e-80) */
-        uint32_t w3_first = 0;
-        for (uint32_t attempt = 0; attempt < ORC_MAX_ATTEMPTS; ++attempt) {
-            uint32_t ctr[4] = {attempt, stream, (uint32_t)idx, (uint32_t)(idx >> 32)};
-            uint32_t w[4];
-            orc_philox4x32_10(ctr, key, w);
-            if (attempt == 0) w3_first = w[3];
-            double z = sqrt(-2.0 * log(unit_open(w[0]))) * cos(two_pi * unit_open(w[1]));
-            double t = 1.0 + c * z;
-            double v = t * t * t;
-            if (v <= 0.0) continue;
-            double lu = log(unit_open(w[2]));
-            if (lu < 0.5 * z * z + d - d * v + d * log(v)) {
-                gam = d * v;
-                break;
-            }
-        }
+        uint32_t w3_first, used;
+        double gam = gamma_by_attempts(d, c, offset + (uint64_t)i, stream, key, &w3_first, &used);
         /* G^(1/beta) = G^a; with the boost G = G' U^(1/a) so G^a = G'^a U */
         double mag = pow(gam, a);
         if (boost) mag *= unit_open(w3_first);
@@ -358,6 +383,21 @@ void orc_sample(void *out, int dtype, int64_t n, float alpha, float beta,
         else
             ((float *)out)[i] = xf;
     }
+}
+
+/* Attempts the same n draws take in total (the efficiency of the rejection step; no sample is formed). */
+uint64_t orc_sample_attempts(int64_t n, float beta, uint64_t seed, uint32_t stream, uint64_t offset)
+{
+    double a, d, c;
+    (void)gamma_constants(beta, &a, &d, &c);
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint64_t total = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        uint32_t w3_first, used;
+        (void)gamma_by_attempts(d, c, offset + (uint64_t)i, stream, key, &w3_first, &used);
+        total += used;
+    }
+    return total;
 }
 
 /* ------------------------------------------------------------------------- */

@@ -90,8 +90,12 @@ void orc_penalty_grad(const void *w, int dtype, int64_t n, float alpha, float be
 /* ---- counter-based RNG and GG sampler ---------------------------------- */
 void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 /* element i uses counter {attempt, stream, lo(offset+i), hi(offset+i)}, key {lo(seed), hi(seed)} */
+/* fp32 -> bf16 bits, round to nearest even, NaN kept quiet (what orc_sample stores for ORC_BF16) */
+void orc_round_bf16(const float *x, int64_t n, uint16_t *out);
 void orc_sample(void *out, int dtype, int64_t n, float alpha, float beta,
                 uint64_t seed, uint32_t stream, uint64_t offset);
+/* total attempts of the rejection step over the same n draws */
+uint64_t orc_sample_attempts(int64_t n, float beta, uint64_t seed, uint32_t stream, uint64_t offset);
 
 /* ---- whole pass over a segmented flat buffer --------------------------- */
 /* offsets[S+1] element offsets; per segment: fit, Delta = (float)alpha / delta_div (or delta[s]

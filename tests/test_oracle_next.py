@@ -55,6 +55,22 @@ def test_gct_step_by_hand():
     assert w[0] == pytest.approx(1.0 - 0.5 * ghat, rel=1e-6)
 
 
+def test_gct_eps_guards_a_vanished_previous_gradient():
+    # ghat_prev = 0: the secant curvature is (1/eta)(1 - g/eps), finite only through eps (Algorithm 2)
+    w = np.array([0.5], dtype=np.float32)
+    g = np.array([-5.0 / 256], dtype=np.float32)
+    gp = np.zeros(1, dtype=np.float32)
+    lam, N, eps = 0.125, 4, 2.0 ** -6
+    oracle.gct_update(w, g, gp, eta=0.25, lam=lam, eps=eps, inv_delta=256.0, eg_k=1, n_rate=N, first_step=False)
+    h = (1 / 0.25) * (1 - (-5 / 256) / eps)                        # = 4 * (1 + 1.25) = 9
+    u = 2 * 5                                                      # floor(-5) = -5 -> Map = 10
+    dR = 4 * 256 / (N * math.log(2)) * -1.0 / (u + 2)              # k = 1
+    ghat = -5 / 256 + lam * dR * h
+    assert h == 9.0
+    assert gp[0] == pytest.approx(ghat, rel=1e-6)
+    assert w[0] == pytest.approx(0.5 - 0.25 * ghat, rel=1e-6)
+
+
 def test_gct_rate_gradient_is_slope_of_smoothed_eg_length():
     # d/dg of (1/N) * 2 log2(2 |g| 2^n + 2^k) at large |g| approaches the oracle's dR (u ~ 2|q|)
     n, k, N = 12, 0, 1000

@@ -98,6 +98,30 @@ def test_sampler_general_shape_transforms_to_gamma(beta):
     assert stats.kstest(x, "gennorm", args=(beta, 0.0, float(np.float32(alpha)))).pvalue > 1e-3
 
 
+@pytest.mark.parametrize("beta", [0.1, 0.5, 1.0, 2.0, 4.0])
+def test_sampler_rejection_step_has_the_published_efficiency(beta):
+    """Marsaglia & Tsang (2000): with c = 1/sqrt(9 d) the normal envelope touches the transformed Gamma
+    density exp(d ln v - d v + d), v = (1 + c z)^3, at z = 0 and lies above it elsewhere, so an attempt is
+    accepted with probability P = (2 pi)^(-1/2) * integral of that density over 1 + c z > 0: above 0.95 for
+    every shape >= 1.  A wrong c or d, or a wrong acceptance test, leaves the distribution tests above a chance
+    (any envelope above the target still samples exactly) but not this count."""
+    from scipy import integrate
+    a = 1.0 / beta
+    d = (a + 1.0 if a < 1.0 else a) - 1.0 / 3.0
+    c = 1.0 / math.sqrt(9.0 * d)
+    area, _ = integrate.quad(lambda z: math.exp(d * (3.0 * math.log1p(c * z) - (1.0 + c * z) ** 3 + 1.0)),
+                             -1.0 / c, np.inf)
+    p_accept = area / math.sqrt(2.0 * math.pi)
+    assert 0.95 < p_accept < 1.0
+    n = 200_000
+    mean_attempts = oracle.sample_attempts(n, beta, seed=21) / n
+    sigma = math.sqrt(1.0 - p_accept) / p_accept / math.sqrt(n)      # geometric number of attempts
+    assert abs(mean_attempts - 1.0 / p_accept) < 5.0 * sigma
+    # the draws are the ones sample() makes: the count does not depend on alpha, and is additive over ranges
+    assert oracle.sample_attempts(1000, beta, seed=21) + oracle.sample_attempts(n - 1000, beta, seed=21, offset=1000) \
+        == oracle.sample_attempts(n, beta, seed=21)
+
+
 def test_sampler_fit_round_trip_and_variance_eq3():
     for alpha, beta in [(0.02, 1.0), (0.015, 1.5), (0.5, 0.8)]:
         x = oracle.sample(2_000_000, alpha, beta, seed=8)
@@ -124,6 +148,29 @@ def test_sampler_bf16_is_rounded_fp32():
     a = oracle.sample(5000, 0.1, 1.2, seed=1)
     b = oracle.sample(5000, 0.1, 1.2, seed=1, dtype=oracle.BF16)
     assert np.array_equal(b, gg_inputs.f32_to_bf16_bits(a))
+
+
+def test_bf16_rounding_is_nearest_even():
+    """Ties go to the even mantissa, in both directions; otherwise nearest; checked against the hand cases and
+    against torch's own conversion on random values, ties, infinities and denormals."""
+    import torch
+    hand = {1.0 + 2.0 ** -8: 0x3F80,            # tie between 1.0 (even) and 1.0078125 -> down
+            1.0 + 3 * 2.0 ** -8: 0x3F82,        # tie between 1.0078125 (odd) and 1.015625 -> up
+            1.0 + 2.0 ** -8 + 2.0 ** -20: 0x3F81,   # just above the tie -> up
+            -(1.0 + 2.0 ** -8): 0xBF80, 0.0: 0x0000, float("inf"): 0x7F80,
+            3.3895314e38: 0x7F7F,               # the largest bf16 stays
+            3.4028235e38: 0x7F80}               # the largest fp32 rounds up to infinity
+    got = oracle.round_bf16(np.array(list(hand), dtype=np.float32))
+    assert [int(v) for v in got] == list(hand.values())
+    rng = np.random.default_rng(0)
+    bits = rng.integers(0, 1 << 32, size=200_000, dtype=np.uint64).astype(np.uint32)
+    bits[:50_000] = (bits[:50_000] & np.uint32(0xFFFF0000)) | np.uint32(0x8000)      # exact ties
+    x = bits.view(np.float32)
+    x = x[np.isfinite(x)]
+    ref = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oracle.round_bf16(x), ref)
+    nan = oracle.round_bf16(np.array([np.nan], dtype=np.float32))[0]
+    assert (nan & 0x7F80) == 0x7F80 and (nan & 0x007F) != 0
 
 
 def test_gg_init_sampling_has_he_variance():

@@ -239,12 +239,15 @@ def test_laplace_closed_form_entropy_and_eg_rate():
 
 
 # ---- segmented pass = per-segment calls ---------------------------------------------------------
-def test_fused_segmented_equals_per_segment_calls():
+@pytest.mark.parametrize("bf16", [False, True])
+def test_fused_segmented_equals_per_segment_calls(bf16):
     sizes = [0, 17, 4096, 1, 3000, 0, 999]
     off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
     parts = [gg_inputs.gg_numpy(s, 10.0 ** (-2 - i % 3), 0.6 + 0.2 * i, seed=30 + i) for i, s in enumerate(sizes)]
     x = np.concatenate(parts).astype(np.float32)
-    grad = np.zeros_like(x)
+    if bf16:
+        x = gg_inputs.f32_to_bf16_bits(x)              # uint16 bit patterns: element offsets are 2-byte strides
+    grad = np.zeros(x.size, dtype=np.float32)
     fits, rates = oracle.fused_segmented(x, off, delta_div=16.0, lam=1e-4, grad=grad)
     for s, sz in enumerate(sizes):
         xs = x[off[s]:off[s + 1]]
