@@ -562,6 +562,30 @@ def test_fused_pass_is_graph_capturable(gg):
         assert got == (e_fit.cpu().numpy().tobytes(), e_rate.cpu().numpy().tobytes(), e_grad.cpu().numpy().tobytes()), rep
 
 
+def test_two_streams_with_their_own_workspaces_do_not_interfere(gg):
+    """The library keeps no state between calls: passes over different buffers, enqueued on two streams
+    (default priority) so that they overlap, give what each gives alone."""
+    segs = gg_inputs.scaled_layout(gg_inputs.gradient_bucket_1p5b()[:40], 53)
+    jobs = []
+    for seed in (41, 42):
+        flat, off, _, _ = gg_inputs.make_bucket(segs, seed=seed, device=DEV)
+        ws = gg.Workspace(flat.numel(), len(segs))
+        alone = gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, nbins=512)
+        torch.cuda.synchronize()
+        jobs.append((flat, off, ws, [alone[k].cpu().numpy().tobytes() for k in ("fit", "rate", "hist")]))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    outs = [None, None]
+    for rep in range(4):                                   # interleaved submission
+        for i, (flat, off, ws, _) in enumerate(jobs):
+            with torch.cuda.stream(streams[i]):
+                outs[i] = gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, nbins=512)
+    torch.cuda.synchronize()
+    for i, (_, _, _, alone) in enumerate(jobs):
+        assert [outs[i][k].cpu().numpy().tobytes() for k in ("fit", "rate", "hist")] == alone, i
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_fused_one_sweep_mode_with_given_steps(gg, dtype):
     """Steps handed in (no dependence on this call's fit): moments and rate from one read of x."""
