@@ -562,6 +562,117 @@ def test_fused_pass_is_graph_capturable(gg):
         assert got == (e_fit.cpu().numpy().tobytes(), e_rate.cpu().numpy().tobytes(), e_grad.cpu().numpy().tobytes()), rep
 
 
+@pytest.mark.parametrize("seed", range(48))
+def test_random_buckets_and_options_against_the_oracle(gg, seed):
+    """Seeded random unit layouts (empty, tiny, sizes around the chunk of 16384 elements, a few large) with
+    random dtype, rounding, order k, bins, symbols and penalty mode: every unit against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    S = int(rng.integers(1, 40))
+    kinds = rng.integers(0, 6, size=S)
+    sizes = np.where(kinds == 0, 0,
+            np.where(kinds == 1, rng.integers(1, 9, size=S),
+            np.where(kinds == 2, 16384 * rng.integers(1, 4, size=S) + rng.integers(-2, 3, size=S),
+            np.where(kinds == 3, rng.integers(9, 5000, size=S),
+            np.where(kinds == 4, rng.integers(5000, 70_000, size=S), 4 * rng.integers(1, 2000, size=S))))))
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    dtype = torch.bfloat16 if rng.integers(2) else torch.float32
+    mode = int(rng.integers(2))
+    k = int(rng.choice([0, 0, 1, 2, 5]))
+    nbins = int(rng.choice([0, 2, 64, 1000, 20000]))
+    want_symbols = bool(rng.integers(2))
+    lam = float(rng.choice([0.0, 1e-4]))
+    accumulate = bool(rng.integers(2))
+    div = float(rng.choice([4.0, 16.0, 64.0]))
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(2000 + seed)
+    parts = [gg_inputs.gg_torch(int(sz), float(10.0 ** rng.uniform(-4, 0)), float(rng.uniform(0.4, 2.5)), gen, DEV, dtype)
+             for sz in sizes]
+    flat = torch.cat(parts) if n else torch.empty(0, device=DEV, dtype=dtype)
+    if n and S > 2 and sizes[1] > 0:
+        flat[int(off[1]):int(off[2])] = 0                   # a unit of zeros: no step, no penalty
+    g0 = (torch.randn(n, device=DEV, generator=gen) * 1e-3) if lam > 0 else None
+    grad = g0.clone() if lam > 0 else None
+    ws = gg.Workspace(n, S)
+    res = gg.gg_fused_segmented(flat, off, ws, delta_div=div, eg_k=k, round_mode=mode, nbins=nbins,
+                                want_symbols=want_symbols, lam=lam, grad=grad, accumulate=accumulate)
+    torch.cuda.synchronize()
+    what = f"seed {seed}: S={S} n={n} {dtype} mode={mode} k={k} nbins={nbins} sym={want_symbols} lam={lam} acc={accumulate}"
+    frec, rrec = gg.fit_records(res["fit"]), gg.rate_records(res["rate"])
+    hb = host_bits(flat)
+    hist = res["hist"].cpu().numpy().view(np.uint64).reshape(S, nbins) if nbins else None
+    sym = res["symbols"].cpu().numpy() if want_symbols else None
+    gout = grad.cpu().numpy() if lam > 0 else None
+    g0h = g0.cpu().numpy() if lam > 0 else None
+    for u in range(S):
+        lo, hi = int(off[u]), int(off[u + 1])
+        xs = hb[lo:hi]
+        where = f"{what}, unit {u} [{lo}, {hi})"
+        check_fit(frec[u], oracle.fit(xs), where)
+        if hi == lo:
+            assert int(rrec[u]["flags"]) & gg.GG_F_EMPTY and int(rrec[u]["eg_bits"]) == 0, where
+            continue
+        if float(frec[u]["alpha"]) == 0.0:
+            assert int(rrec[u]["flags"]) == gg.GG_F_DEGENERATE and int(rrec[u]["eg_bits"]) == 0, where
+            if lam > 0:
+                assert np.array_equal(gout[lo:hi], g0h[lo:hi] if accumulate else np.zeros(hi - lo, np.float32)), where
+            continue
+        r, ohist, osym = oracle.quantize_rate(xs, float(rrec[u]["delta"]), eg_k=k, round_mode=mode, nbins=nbins,
+                                              want_symbols=want_symbols)
+        check_rate(rrec[u], r, where, entropy=nbins > 0)
+        if nbins:
+            assert np.array_equal(hist[u], ohist), where
+        if want_symbols:
+            assert np.array_equal(sym[lo:hi], osym), where
+        if lam > 0:
+            bare = oracle.penalty_grad(xs, frec[u]["alpha"], frec[u]["beta"], lam)
+            if accumulate:
+                og = oracle.penalty_grad(xs, frec[u]["alpha"], frec[u]["beta"], lam, grad=g0h[lo:hi].copy(), accumulate=True)
+                check_penalty(gout[lo:hi], og, where, penalty=bare)
+            else:
+                check_penalty(gout[lo:hi], bare, where)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_matrices_by_rows_against_the_oracle(gg, seed):
+    """Seeded random row-shaped inputs (short rows taken by a wave, long rows cut into chunks; with and without
+    symbols, penalty, given steps): sampled rows against the oracle, the whole-matrix fit against all of it."""
+    rng = np.random.default_rng(3000 + seed)
+    cols = int(rng.choice([1, 7, 64, 100, 1000, 4096, 16384, 16385, 40_000]))
+    rows = int(rng.integers(1, max(2, min(3000, 600_000 // cols))))
+    dtype = torch.bfloat16 if rng.integers(2) else torch.float32
+    mode = int(rng.integers(2))
+    k = int(rng.choice([0, 0, 3]))
+    want_symbols = bool(rng.integers(2))
+    lam = float(rng.choice([0.0, 1e-3]))
+    given = bool(rng.integers(3) == 0)                      # steps handed in instead of alpha / div
+    x = make(rows * cols, float(10.0 ** rng.uniform(-3, 0)), float(rng.uniform(0.5, 2.2)), seed=4000 + seed, dtype=dtype)
+    steps = (torch.rand(rows, device=DEV) * 0.05 + 1e-3) if given else None
+    grad = torch.zeros(rows * cols, device=DEV) if lam > 0 else None
+    ws = gg.Workspace(rows * cols, rows)
+    res = gg.gg_fused_rows(x, rows, cols, ws, delta_div=0.0 if given else 8.0, delta=steps, eg_k=k, round_mode=mode,
+                           want_symbols=want_symbols, lam=lam, grad=grad, want_total=True)
+    torch.cuda.synchronize()
+    what = f"seed {seed}: {rows}x{cols} {dtype} mode={mode} k={k} sym={want_symbols} lam={lam} given={given}"
+    frec, rrec, tot = gg.fit_records(res["fit"]), gg.rate_records(res["rate"]), gg.fit_records(res["total"])[0]
+    hb = host_bits(x)
+    check_fit(tot, oracle.fit(hb), what + ", total")
+    sym = res["symbols"].cpu().numpy() if want_symbols else None
+    g = grad.cpu().numpy() if lam > 0 else None
+    for r_ in sorted(set(rng.integers(0, rows, size=min(rows, 12)).tolist()) | {0, rows - 1}):
+        xs = hb[r_ * cols:(r_ + 1) * cols]
+        where = f"{what}, row {r_}"
+        check_fit(frec[r_], oracle.fit(xs), where)
+        if given:
+            assert float(rrec[r_]["delta"]) == float(steps[r_]), where
+        r, _, osym = oracle.quantize_rate(xs, float(rrec[r_]["delta"]), eg_k=k, round_mode=mode, want_symbols=want_symbols)
+        check_rate(rrec[r_], r, where, entropy=False)
+        if want_symbols:
+            assert np.array_equal(sym[r_ * cols:(r_ + 1) * cols], osym), where
+        if lam > 0:
+            check_penalty(g[r_ * cols:(r_ + 1) * cols], oracle.penalty_grad(xs, frec[r_]["alpha"], frec[r_]["beta"], lam), where)
+
+
 def test_two_streams_with_their_own_workspaces_do_not_interfere(gg):
     """The library keeps no state between calls: passes over different buffers, enqueued on two streams
     (default priority) so that they overlap, give what each gives alone."""
