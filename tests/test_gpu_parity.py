@@ -591,6 +591,10 @@ def test_random_buckets_and_options_against_the_oracle(gg, seed):
     flat = torch.cat(parts) if n else torch.empty(0, device=DEV, dtype=dtype)
     if n and S > 2 and sizes[1] > 0:
         flat[int(off[1]):int(off[2])] = 0                   # a unit of zeros: no step, no penalty
+    if S > 4 and sizes[3] > 0:
+        flat[int(off[3]) + int(sizes[3]) // 2] = float("nan")   # moments not finite: no fit, no step
+    if S > 5 and sizes[4] > 1:
+        flat[int(off[4]) + 1] = float("-inf")
     g0 = (torch.randn(n, device=DEV, generator=gen) * 1e-3) if lam > 0 else None
     grad = g0.clone() if lam > 0 else None
     ws = gg.Workspace(n, S)
@@ -647,6 +651,9 @@ def test_random_matrices_by_rows_against_the_oracle(gg, seed):
     lam = float(rng.choice([0.0, 1e-3]))
     given = bool(rng.integers(3) == 0)                      # steps handed in instead of alpha / div
     x = make(rows * cols, float(10.0 ** rng.uniform(-3, 0)), float(rng.uniform(0.5, 2.2)), seed=4000 + seed, dtype=dtype)
+    if rows > 3:
+        x[cols * 1 + cols // 2] = float("nan")              # row 1: moments not finite
+        x[cols * 2] = float("inf")                          # row 2 likewise
     steps = (torch.rand(rows, device=DEV) * 0.05 + 1e-3) if given else None
     grad = torch.zeros(rows * cols, device=DEV) if lam > 0 else None
     ws = gg.Workspace(rows * cols, rows)
@@ -659,10 +666,15 @@ def test_random_matrices_by_rows_against_the_oracle(gg, seed):
     check_fit(tot, oracle.fit(hb), what + ", total")
     sym = res["symbols"].cpu().numpy() if want_symbols else None
     g = grad.cpu().numpy() if lam > 0 else None
-    for r_ in sorted(set(rng.integers(0, rows, size=min(rows, 12)).tolist()) | {0, rows - 1}):
+    for r_ in sorted(set(rng.integers(0, rows, size=min(rows, 12)).tolist()) | {0, rows - 1} | set(range(min(rows, 4)))):
         xs = hb[r_ * cols:(r_ + 1) * cols]
         where = f"{what}, row {r_}"
         check_fit(frec[r_], oracle.fit(xs), where)
+        if not given and float(frec[r_]["alpha"]) == 0.0:   # no fit (zeros, NaN, Inf): no step, nothing coded, no penalty
+            assert int(rrec[r_]["flags"]) == gg.GG_F_DEGENERATE and int(rrec[r_]["eg_bits"]) == 0, where
+            if lam > 0:
+                assert not g[r_ * cols:(r_ + 1) * cols].any(), where
+            continue
         if given:
             assert float(rrec[r_]["delta"]) == float(steps[r_]), where
         r, _, osym = oracle.quantize_rate(xs, float(rrec[r_]["delta"]), eg_k=k, round_mode=mode, want_symbols=want_symbols)
