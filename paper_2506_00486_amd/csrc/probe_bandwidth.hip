@@ -62,6 +62,22 @@ __global__ __launch_bounds__(kBlock) void k_runs(const vf4 *__restrict__ x, long
     }
 }
 
+// The same reader with the block -> run map made XCD-aware: workgroups are dealt to the 8 XCDs round-robin
+// (workgroup b runs on XCD b mod 8), so run = (b mod 8) * (runs / 8) + b / 8 gives every XCD one contiguous
+// eighth of the buffer; the plain map (run = b) interleaves the XCDs run by run.
+__global__ __launch_bounds__(kBlock) void k_runs_xcd(const vf4 *__restrict__ x, long nchunks, long nvec, int cpb, long runs,
+                                                     double *out) {
+    const long per = (runs + 7) / 8;
+    const long run = (long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
+    double acc = 0;
+    const long first = run * cpb;
+    long last = first + cpb;
+    if (last > nchunks) last = nchunks;
+    if ((long)(blockIdx.x >> 3) < per)
+        for (long c = first; c < last; ++c) acc += chunk_sum<8, true>(x + c * kChunkVec, chunk_len(c, nvec));
+    if (acc == 123.456) out[blockIdx.x] = acc;
+}
+
 // the reader with a result per block: EPI 0 nothing stored, 1 block reduction + one store, 2 one store per wave
 template <int EPI>
 __global__ __launch_bounds__(kBlock) void k_publish(const vf4 *__restrict__ x, long nchunks, long nvec, int cpb, double *out) {
@@ -201,6 +217,15 @@ int main(int argc, char **argv) {
         printf("read  %4d resident blocks, contiguous runs, non-temporal   %.3f ms %7.1f GB/s\n", G, ms, gb / ms * 1e3);
         ms = timeit([&] { k_runs<false><<<G, kBlock>>>((const vf4 *)x, nchunks, nvec, cpb, out, nullptr); }, reps);
         printf("read  %4d resident blocks, contiguous runs, plain loads    %.3f ms %7.1f GB/s\n", G, ms, gb / ms * 1e3);
+    }
+    for (int rpc : {8, 32, 128}) {
+        const long G = 256L * rpc;
+        const int cpb = (int)((nchunks + G - 1) / G);
+        const long runs = (nchunks + cpb - 1) / cpb, grid = (runs + 7) / 8 * 8;
+        const float plain = timeit([&] { k_runs<true><<<runs, kBlock>>>((const vf4 *)x, nchunks, nvec, cpb, out, nullptr); }, reps);
+        const float xcd = timeit([&] { k_runs_xcd<<<grid, kBlock>>>((const vf4 *)x, nchunks, nvec, cpb, runs, out); }, reps);
+        printf("read  %3d runs/CU, run = block: %.3f ms %7.1f GB/s | one contiguous eighth per XCD: %.3f ms %7.1f GB/s\n", rpc, plain,
+               gb / plain * 1e3, xcd, gb / xcd * 1e3);
     }
     for (int item : {1, 4, 16}) {
         float tot = 0;
