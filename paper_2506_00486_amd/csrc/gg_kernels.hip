@@ -277,6 +277,8 @@ struct PrepArgs {
     SegParam *params;          // device out
     gg_rate_t *rate;           // device out (cleared) or nullptr
     int want_pen;
+    uint64_t *hist;            // histograms to clear for the sweep that follows (S * nbins counts), or nullptr
+    int32_t nbins;
 };
 
 __device__ __forceinline__ void prepare_unit(const PrepArgs &a, int seg, int64_t n, float alpha, float beta) {
@@ -327,6 +329,10 @@ __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *
     s1 = wave_reduce(s1, OpAdd());
     s2 = wave_reduce(s2, OpAdd());
     const int64_t n = unit_len(sv, seg);
+    if (do_prep && prep.hist) {          // the unit's histogram starts at zero; the stores overlap the solve
+        uint64_t *bins = prep.hist + (int64_t)seg * prep.nbins;
+        for (int b = lane; b < prep.nbins; b += 64) bins[b] = 0;
+    }
     gg_fit_t f;
     solve_fit_wave(s1, s2, (uint64_t)n, f);
     if (lane == 0) {
@@ -385,8 +391,13 @@ __global__ __launch_bounds__(kTotalThreads) void k_fit_total(const gg_fit_t *__r
 
 // parameters for calls that do not fit first (one thread per unit)
 __global__ void k_seg_prepare(SegView sv, PrepArgs prep) {
-    const int seg = blockIdx.x * blockDim.x + threadIdx.x;
-    if (seg >= sv.S) return;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (prep.hist) {                     // the histograms of the sweep that follows start at zero
+        const int64_t words = (int64_t)sv.S * prep.nbins;
+        for (int64_t i = gid; i < words; i += (int64_t)gridDim.x * blockDim.x) prep.hist[i] = 0;
+    }
+    if (gid >= sv.S) return;
+    const int seg = (int)gid;
     float alpha = 0.f, beta = 0.f;
     if (prep.fit) { alpha = prep.fit[seg].alpha; beta = prep.fit[seg].beta; }
     prepare_unit(prep, seg, unit_len(sv, seg), alpha, beta);
@@ -1192,6 +1203,7 @@ struct QuantOpts {
     const SegParam *params = nullptr;
     SegParam single{};
     bool fit_too = false;              // one-sweep mode: the rate sweep also writes moment partials
+    bool hist_cleared = false;         // the kernel that prepared the units has cleared the histograms already
     int32_t chunks_per_block_out = 1;  // the run length the sweep used (the fit finalisation needs it)
 };
 
@@ -1291,7 +1303,13 @@ static int launch_rate_finalize(const Geometry &g, gg_rate_t *rate, const uint64
 
 static int launch_seg_prepare(const Geometry &g, const PrepArgs &p, hipStream_t st) {
     if (g.S == 0) return GG_OK;
-    hipLaunchKernelGGL(k_seg_prepare, dim3((unsigned)((g.S + 255) / 256)), dim3(256), 0, st, g.sv, p);
+    int64_t blocks = (g.S + 255) / 256;
+    if (p.hist) {                        // enough threads to clear the histograms too
+        int64_t want = ((int64_t)g.S * p.nbins + 2047) / 2048;
+        if (want > 2048) want = 2048;
+        if (want > blocks) blocks = want;
+    }
+    hipLaunchKernelGGL(k_seg_prepare, dim3((unsigned)blocks), dim3(256), 0, st, g.sv, p);
     return check_launch();
 }
 
@@ -1356,7 +1374,7 @@ static int check_rate_args(int eg_k, int round_mode, int32_t nbins, const uint64
 // the second sweep and its finalisation, shared by every rate/penalty entry point
 static int run_second_sweep(const Geometry &g, const void *x, int dtype, QuantOpts &o, hipStream_t st) {
     int rc;
-    if (o.rate && o.nbins > 0 && (rc = launch_fill_u64(o.hist, (int64_t)g.S * o.nbins, st)) != GG_OK) return rc;
+    if (o.rate && o.nbins > 0 && !o.hist_cleared && (rc = launch_fill_u64(o.hist, (int64_t)g.S * o.nbins, st)) != GG_OK) return rc;
     if (!o.rate) { o.hist = nullptr; o.symbols = nullptr; o.nbins = 0; }
     if (o.nbins == 0) o.hist = nullptr;
     if (o.rate || o.pen) {
@@ -1374,13 +1392,15 @@ static int fused_common(Geometry &g, const void *x, int dtype, float delta_div, 
     PrepArgs p{};
     p.fit = nullptr; p.delta_dev = delta_dev; p.delta_div = delta_div; p.delta_scalar = 0.f;
     p.lambda = lambda; p.params = g.params(); p.rate = rate; p.want_pen = grad != nullptr;
+    const bool with_hist = rate && nbins > 0 && hist;
+    if (with_hist) { p.hist = hist; p.nbins = nbins; }
     if (rate && !grad && !(delta_div > 0.f) && delta_dev) {
         // One-sweep mode: the steps do not depend on this call's fit (e.g. they come from the previous
         // training step), so moments and rate are taken from a single read of x: 4 B/elem instead of 8.
         if ((rc = launch_seg_prepare(g, p, st)) != GG_OK) return rc;
         QuantOpts o;
         o.rate = true; o.eg_k = eg_k; o.round_mode = round_mode; o.nbins = nbins; o.hist = hist; o.symbols = symbols;
-        o.rate_out = rate; o.params = g.params(); o.fit_too = true;
+        o.rate_out = rate; o.params = g.params(); o.fit_too = true; o.hist_cleared = with_hist;
         if ((rc = run_second_sweep(g, x, dtype, o, st)) != GG_OK) return rc;
         if ((rc = launch_fit_finalize(g, o.chunks_per_block_out, fit, nullptr, st)) != GG_OK) return rc;
         if (total_fit) {
@@ -1398,6 +1418,7 @@ static int fused_common(Geometry &g, const void *x, int dtype, float delta_div, 
     o.rate = rate != nullptr; o.pen = grad != nullptr; o.eg_k = eg_k; o.round_mode = round_mode;
     o.nbins = nbins; o.hist = hist; o.symbols = symbols; o.grad = grad; o.accumulate = accumulate;
     o.rate_out = rate; o.params = g.params();
+    o.hist_cleared = with_hist && g.S < kManyUnits;     // the wave-per-unit finalisation clears; the lane-per-unit one does not
     return run_second_sweep(g, x, dtype, o, st);
 }
 
@@ -1502,10 +1523,11 @@ int gg_quantize_rate(const void *x_dev, int dtype, int64_t n, float delta, int e
     hipStream_t st = (hipStream_t)stream;
     PrepArgs p{};
     p.delta_div = 0.f; p.delta_scalar = delta; p.params = g.params(); p.rate = out_dev; p.want_pen = 0;
+    if (nbins > 0) { p.hist = hist_dev; p.nbins = nbins; }
     if ((rc = launch_seg_prepare(g, p, st)) != GG_OK) return rc;
     QuantOpts o;
     o.rate = true; o.eg_k = eg_k; o.round_mode = round_mode; o.nbins = nbins; o.hist = hist_dev;
-    o.symbols = symbols_dev; o.rate_out = out_dev; o.params = g.params();
+    o.symbols = symbols_dev; o.rate_out = out_dev; o.params = g.params(); o.hist_cleared = nbins > 0;
     return run_second_sweep(g, x_dev, dtype, o, st);
 }
 
@@ -1523,10 +1545,11 @@ int gg_quantize_rate_segmented(const void *x_dev, int dtype, const int64_t *offs
     if ((rc = upload_geometry(g, st)) != GG_OK) return rc;
     PrepArgs p{};
     p.delta_dev = delta_dev; p.delta_div = 0.f; p.params = g.params(); p.rate = out_dev; p.want_pen = 0;
+    if (nbins > 0) { p.hist = hist_dev; p.nbins = nbins; }
     if ((rc = launch_seg_prepare(g, p, st)) != GG_OK) return rc;
     QuantOpts o;
     o.rate = true; o.eg_k = eg_k; o.round_mode = round_mode; o.nbins = nbins; o.hist = hist_dev;
-    o.symbols = symbols_dev; o.rate_out = out_dev; o.params = g.params();
+    o.symbols = symbols_dev; o.rate_out = out_dev; o.params = g.params(); o.hist_cleared = nbins > 0 && S > 0;
     return run_second_sweep(g, x_dev, dtype, o, st);
 }
 
