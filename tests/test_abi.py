@@ -136,6 +136,33 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.gg_huffman_mean_bits(None, 4, C.byref(out)) == -1
 
 
+def test_sizes_beyond_the_limits_are_rejected_without_overflow():
+    """Element counts whose product, chunk count or table size would not fit are refused by the host checks
+    (none of these calls reaches a launch)."""
+    gg = _lib()
+    L = gg.lib()
+    P = 0x10000
+    ws_bytes = gg.workspace_bytes(1 << 20, 4)
+    assert L.gg_fit_rows(P, 0, 1 << 24, 1 << 40, P, None, P, ws_bytes, None) == -1            # rows * cols overflows int64
+    assert L.gg_fit_rows(P, 0, (1 << 24) + 1, 4, P, None, P, ws_bytes, None) == -1            # more rows than units allowed
+    assert L.gg_fit_rows(P, 0, 1 << 24, 1 << 38, P, None, P, ws_bytes, None) == -1            # more chunks than an int32 counts
+    far = np.array([0, 1 << 62], dtype=np.int64)
+    assert L.gg_fit_segmented(P, 0, far.ctypes.data, 1, P, P, ws_bytes, None) == -3           # likewise for a bucket
+    assert L.gg_fused_segmented(P, 0, far.ctypes.data, 1, 16.0, None, 0, 0, 0, None, None, 0.0, None, 0, P, P, P,
+                                ws_bytes, None) == -3
+    big = np.array([0, 1 << 40], dtype=np.int64)                                              # a legal size: the workspace is what is missing
+    assert L.gg_fit_segmented(P, 0, big.ctypes.data, 1, P, P, ws_bytes, None) == -4
+    out = C.c_size_t(0)
+    assert L.gg_workspace_bytes(-1, 1, 0, C.byref(out)) == -1
+    assert L.gg_workspace_bytes(1 << 20, -1, 0, C.byref(out)) == -1
+    assert L.gg_workspace_bytes(1 << 20, 1, 0, None) == -1
+    assert L.gg_workspace_bytes(1 << 40, 1 << 20, 0, C.byref(out)) == 0 and out.value > (1 << 40) // 16384 * 16
+    assert L.gg_eg_workspace_bytes(-1, C.byref(out)) == -1
+    assert L.gg_sample(P, 0, -1, 0.1, 1.0, 1, 0, 0, None) == -1
+    assert L.gg_quantize_rate(P, 0, -1, 0.1, 0, 0, 0, None, None, P, P, ws_bytes, None) == -1
+    assert L.gg_eg_encode(P, -1, 0, P, 1024, P, None, None) == -1
+
+
 def test_host_helpers_match_paper_special_cases():
     gg = _lib()
     # Eq. 5 at shape 2 is He initialisation: alpha = sqrt(2 xi / d_in)
