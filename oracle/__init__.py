@@ -85,6 +85,8 @@ def load(path: str):
     L.orc_eg_encode.argtypes = [vp, i64, C.c_int, vp, u64]
     L.orc_eg_decode.restype = i64
     L.orc_eg_decode.argtypes = [vp, u64, C.c_int, vp, i64]
+    L.orc_dequantize.restype = None
+    L.orc_dequantize.argtypes = [vp, i64, f32, vp, C.c_int]
     L.orc_huffman_mean_bits.restype = f64
     L.orc_huffman_mean_bits.argtypes = [vp, i32]
     L.orc_rate_grad.restype = None
@@ -268,6 +270,16 @@ def eg_decode(buf: np.ndarray, n_bits: int, eg_k: int, max_n: int) -> np.ndarray
     if cnt < 0:
         raise ValueError("truncated Exp-Golomb stream")
     return out[:cnt]
+
+
+def dequantize(q: np.ndarray, delta: float, out: np.ndarray = None, accumulate: bool = False) -> np.ndarray:
+    """out (=|+=) q * delta in fp32."""
+    q = np.ascontiguousarray(q, dtype=np.int32).reshape(-1)
+    if out is None:
+        out = np.zeros(q.size, dtype=np.float32)
+    assert out.dtype == np.float32 and out.size == q.size and out.flags.c_contiguous
+    lib().orc_dequantize(_ptr(q), q.size, _f32(delta), _ptr(out), int(bool(accumulate)))
+    return out
 
 
 def huffman_mean_bits(hist: np.ndarray) -> float:

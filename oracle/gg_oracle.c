@@ -537,6 +537,22 @@ int64_t orc_eg_decode(const uint8_t *in, uint64_t n_bits, int eg_k, uint32_t *u,
     return cnt;
 }
 
+/* What a symbol of the uniform quantiser of Sec. 4.2 stands for: q * Delta, one fp32 product (the
+ * quantiser's floor makes it the lower end of the cell: q Delta <= x < (q + 1) Delta).  With accumulate the
+ * value is added to what is there (one fp32 add): the receiving side of a sum of coded tensors. */
+void orc_dequantize(const int32_t *q, int64_t n, float delta, float *out, int accumulate)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float v = (float)q[i] * delta;
+        if (accumulate) {
+            volatile float sum = out[i] + v;
+            out[i] = sum;
+        } else {
+            out[i] = v;
+        }
+    }
+}
+
 /* ------------------------------------------------------------------------- */
 /* Huffman mean code length (the HM column of the paper's tables): repeatedly */
 /* merge the two least frequent nodes; the sum of all merged weights is the   */

@@ -119,6 +119,8 @@ void orc_rate_grad(const void *x, int dtype, int64_t n, float inv_delta, int eg_
 /* returns number of bits written; out must hold (bits+7)/8 bytes, zero-initialised by callee */
 uint64_t orc_eg_encode(const uint32_t *u, int64_t n, int eg_k, uint8_t *out, uint64_t out_bytes);
 int64_t orc_eg_decode(const uint8_t *in, uint64_t n_bits, int eg_k, uint32_t *u, int64_t max_n);
+/* out[i] (=|+=) q[i] * delta in fp32: the reconstruction level of the quantiser of Sec. 4.2 */
+void orc_dequantize(const int32_t *q, int64_t n, float delta, float *out, int accumulate);
 
 /* ---- compression ratio against fixed-length coding (Sec. 5.1): 1 - mean_bits / fl_bits ---- */
 double orc_compression_ratio(double mean_bits, double fl_bits);

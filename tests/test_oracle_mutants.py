@@ -148,6 +148,10 @@ MUTANTS = [
      "test_oracle_next", "test_eg_stream_round_trip_and_length", (1,)),
     ("EG decoder: subtracts 1 instead of 2^k", "u[cnt++] = (uint32_t)(v - ((uint64_t)1 << eg_k));", "u[cnt++] = (uint32_t)(v - 1);",
      "test_oracle_next", "test_eg_stream_round_trip_and_length", (3,)),
+    ("reconstruction at the middle of the cell", "volatile float v = (float)q[i] * delta;", "volatile float v = ((float)q[i] + 0.5f) * delta;",
+     "test_oracle_next", "test_dequantize_gives_the_lower_end_of_the_quantiser_cell", ()),
+    ("reconstruction: accumulate overwrites", "volatile float sum = out[i] + v;\n            out[i] = sum;", "out[i] = v;",
+     "test_oracle_next", "test_dequantize_gives_the_lower_end_of_the_quantiser_cell", ()),
     ("Huffman: a single symbol costs 0 bits", "if (m == 1) return 1.0;", "if (m == 1) return 0.0;",
      "test_oracle_next", "test_huffman_textbook_and_bounds", ()),
     ("Huffman: merges the larger of the two queues' heads", "leaf[li] <= node[ni]))", "leaf[li] > node[ni]))",

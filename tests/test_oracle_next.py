@@ -118,6 +118,27 @@ def heap_huffman_mean(counts):
     return coded / total
 
 
+def test_dequantize_gives_the_lower_end_of_the_quantiser_cell():
+    # hand values; the product is one fp32 rounding
+    assert oracle.dequantize(np.array([-3, 0, 5, -(1 << 30)]), 0.25).tolist() == [-0.75, 0.0, 1.25, -float(1 << 28)]
+    third = np.float32(1.0 / 3.0)
+    assert oracle.dequantize(np.array([7]), float(third))[0] == np.float32(7) * third
+    assert oracle.dequantize(np.array([16777217]), 2.0)[0] == 2.0 * 16777216.0          # q itself rounds to fp32 first
+    # with the floor quantiser of Sec. 4.2 and an exact (power of two) step: q Delta <= x < (q + 1) Delta
+    x = gg_inputs.gg_numpy(20_000, 0.02, 0.9, seed=4).astype(np.float32)
+    delta = 2.0 ** -9
+    _, _, q = oracle.quantize_rate(x, delta, want_symbols=True)
+    lo = oracle.dequantize(q, delta)
+    assert np.all(lo <= x) and np.all(x < lo + np.float32(delta))
+    # nearest mode: within half a step
+    _, _, qn = oracle.quantize_rate(x, delta, round_mode=oracle.ROUND_NEAREST_EVEN, want_symbols=True)
+    assert np.all(np.abs(oracle.dequantize(qn, delta) - x) <= np.float32(delta / 2))
+    # accumulate: one fp32 add onto what is there
+    base = np.linspace(-1, 1, q.size, dtype=np.float32)
+    acc = oracle.dequantize(q, delta, out=base.copy(), accumulate=True)
+    assert np.array_equal(acc, base + lo)
+
+
 def test_huffman_textbook_and_bounds():
     assert oracle.huffman_mean_bits(np.array([1, 1, 2, 4], dtype=np.uint64)) == pytest.approx((3 + 3 + 2 * 2 + 4) / 8)
     assert oracle.huffman_mean_bits(np.array([5, 5, 5, 5], dtype=np.uint64)) == 2.0
