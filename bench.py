@@ -291,7 +291,15 @@ def main():
         extra["eg_encode_tensor"] = {"elements": m, "ms": round(ms_t, 4), "Gelem/s": round(m / ms_t / 1e6, 2)}
         extra["eg_encode"] = {"symbols": m, "stream_bits": bits, "ms": round(ms_e, 4), "Gsymbols/s": round(m / ms_e / 1e6, 2)}
         extra["eg_decode"] = {"symbols": m, "ms": round(ms_d, 4), "Gsymbols/s": round(m / ms_d / 1e6, 2)}
-        del back, stream_e, index_e, bufs
+        xhat = torch.zeros(m, device=dev)
+
+        def step_dec_v():
+            gg.gg_eg_decode_dequant(stream_e, index_e, m, d_enc, 0, out=xhat, accumulate=True)
+
+        step_dec_v()
+        _, ms_v = time_steps(step_dec_v, 10, torch)
+        extra["eg_decode_dequant_accumulate"] = {"symbols": m, "ms": round(ms_v, 4), "Gsymbols/s": round(m / ms_v / 1e6, 2)}
+        del back, stream_e, index_e, bufs, xhat
         del sym
         # the whole bucket, each segment with its own step, straight to one bit stream (what a compressed
         # gradient exchange would send): its length must be the sum of the segments' eg_bits of the pass

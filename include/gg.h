@@ -220,6 +220,12 @@ int gg_eg_encode(const int32_t *symbols_dev, int64_t n, int eg_k, uint8_t *strea
                  uint64_t *block_offsets_dev, uint64_t *total_bits_dev, void *stream);
 int gg_eg_decode(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, int64_t n, int eg_k,
                  int32_t *symbols_dev, void *stream);
+/* Decoding straight to values: out[i] (=|+=) q_i * delta in fp32, q_i the decoded symbol -- the lower end of the
+ * quantiser's cell (Sec. 4.2: q = floor(x / delta), so q delta <= x < (q + 1) delta), one fp32 product, and with
+ * accumulate != 0 one fp32 add onto the existing value (summing the coded tensors of several senders).  No symbol
+ * array in memory.  delta > 0 and finite; out_dev fp32, 16-byte aligned; the rest as for gg_eg_decode. */
+int gg_eg_decode_dequant(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, int64_t n, int eg_k, float delta,
+                         float *out_dev, int accumulate, void *stream);
 /* The same stream straight from a tensor: symbol i is the quantised x_i (the rate sweep's arithmetic: one
  * fp32 product with 1/delta, NaN -> 0, clamp to +-2^30, GG_FLOOR or GG_NEAREST_EVEN), so the stream is bit for
  * bit what gg_quantize_rate's symbols would give and its length the eg_bits of that call, with no symbol

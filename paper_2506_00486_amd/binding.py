@@ -78,6 +78,7 @@ def lib():
             "gg_eg_encode_tensor": (ci, [vp, ci, i64, f32, ci, ci, vp, u64, vp, vp, vp]),
             "gg_eg_encode_segmented": (ci, [vp, ci, vp, i32, vp, ci, ci, vp, u64, vp, vp, vp, sz, vp]),
             "gg_eg_decode": (ci, [vp, vp, i64, ci, vp, vp]),
+            "gg_eg_decode_dequant": (ci, [vp, vp, i64, ci, f32, vp, ci, vp]),
             "gg_huffman_mean_bits": (ci, [vp, i32, C.POINTER(f64)]),
         }
         for name, (res, args) in sig.items():
@@ -389,6 +390,17 @@ def gg_eg_decode(stream: torch.Tensor, index: torch.Tensor, n: int, eg_k: int = 
     if out is None:
         out = torch.empty(n, dtype=torch.int32, device=stream.device)
     _check(lib().gg_eg_decode(_dev(stream), _dev(index), n, eg_k, _dev(out), _stream()), "gg_eg_decode")
+    return out
+
+
+def gg_eg_decode_dequant(stream: torch.Tensor, index: torch.Tensor, n: int, delta: float, eg_k: int = 0,
+                         out: Optional[torch.Tensor] = None, accumulate: bool = False) -> torch.Tensor:
+    if out is None:
+        if accumulate:
+            raise ValueError("accumulate needs the tensor to add to")
+        out = torch.empty(n, dtype=torch.float32, device=stream.device)
+    _check(lib().gg_eg_decode_dequant(_dev(stream), _dev(index), n, eg_k, _f32(delta), _dev(out), int(bool(accumulate)),
+                                      _stream()), "gg_eg_decode_dequant")
     return out
 
 

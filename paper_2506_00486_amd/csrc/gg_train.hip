@@ -551,8 +551,12 @@ static_assert(kEgStepWords + kEgTopUp <= kEgRing && GG_EG_TILE % kEgDecRow == 0 
               "ring holds a step and a top-up");
 typedef unsigned int EgWords4 __attribute__((ext_vector_type(4), aligned(4)));   // four stream words at any word address
 
+// DEQ: instead of the symbols the kernel writes what they stand for, q * delta in fp32 (or adds it to what is
+// there): the receiving side of a sum of coded tensors needs no symbol array in memory.
+template <bool DEQ>
 __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ stream, const uint64_t *__restrict__ index,
-                                                  int64_t n, int64_t tiles, int eg_k, int32_t *__restrict__ q) {
+                                                  int64_t n, int64_t tiles, int eg_k, int32_t *__restrict__ q,
+                                                  float *__restrict__ xhat, float delta, int accumulate) {
     __shared__ uint32_t ring[kEgRing][64];
     __shared__ int32_t stage[64][kEgDecRow + 1];
     const int lane = threadIdx.x;
@@ -644,7 +648,21 @@ __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ s
         for (int r = 0; r < 4; ++r) {
             const int row = r * 16 + (lane >> 2), c = (lane & 3) * 4;
             const int64_t g = (tile0 + row) * GG_EG_TILE + s0 + c;
-            if (g + 4 <= n) {
+            if constexpr (DEQ) {
+                if (g + 4 <= n) {
+                    gg_f4 val = {(float)stage[row][c] * delta, (float)stage[row][c + 1] * delta, (float)stage[row][c + 2] * delta,
+                                 (float)stage[row][c + 3] * delta};
+                    gg_f4 *dst = reinterpret_cast<gg_f4 *>(xhat + g);
+                    if (accumulate) val += *dst;
+                    *dst = val;
+                } else {
+                    for (int x = 0; x < 4; ++x)
+                        if (g + x < n) {
+                            const float val = (float)stage[row][c + x] * delta;
+                            xhat[g + x] = accumulate ? xhat[g + x] + val : val;
+                        }
+                }
+            } else if (g + 4 <= n) {
                 const gg_i4 val = {stage[row][c], stage[row][c + 1], stage[row][c + 2], stage[row][c + 3]};
                 *reinterpret_cast<gg_i4 *>(q + g) = val;
             } else {
@@ -891,8 +909,25 @@ int gg_eg_decode(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, i
         return GG_ERR_INVALID_ARG;
     const int64_t T = eg_index_tiles(n);
     if ((T + 63) / 64 > 2147483647LL) return GG_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(k_eg_decode, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
-                       reinterpret_cast<const uint32_t *>(stream_dev), block_offsets_dev, n, T, eg_k, symbols_dev);
+    hipLaunchKernelGGL(k_eg_decode<false>, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
+                       reinterpret_cast<const uint32_t *>(stream_dev), block_offsets_dev, n, T, eg_k, symbols_dev,
+                       (float *)nullptr, 0.f, 0);
+    return check_launch();
+}
+
+int gg_eg_decode_dequant(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, int64_t n, int eg_k, float delta,
+                         float *out_dev, int accumulate, void *stream) {
+    if (n < 0 || eg_k < 0 || eg_k > GG_MAX_EG_K) return GG_ERR_INVALID_ARG;
+    if (!(delta > 0.f) || !std::isfinite(delta)) return GG_ERR_INVALID_ARG;
+    if (n == 0) return GG_OK;
+    if (!stream_dev || (reinterpret_cast<uintptr_t>(stream_dev) & 3u) || !block_offsets_dev || !aligned8(block_offsets_dev) ||
+        !out_dev || !aligned16(out_dev))
+        return GG_ERR_INVALID_ARG;
+    const int64_t T = eg_index_tiles(n);
+    if ((T + 63) / 64 > 2147483647LL) return GG_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_eg_decode<true>, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
+                       reinterpret_cast<const uint32_t *>(stream_dev), block_offsets_dev, n, T, eg_k, (int32_t *)nullptr,
+                       out_dev, delta, accumulate ? 1 : 0);
     return check_launch();
 }
 

@@ -132,6 +132,12 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.gg_eg_decode(P + 1, P, 100, 0, P, None) == -1                                         # misaligned stream
     assert L.gg_eg_decode(P, P, 100, 0, P + 4, None) == -1                                         # misaligned output
     assert L.gg_eg_decode(P, P, 0, 0, None, None) == 0                                             # nothing to decode
+    assert L.gg_eg_decode_dequant(P, P, 100, 0, 0.0, P, 0, None) == -1                            # step 0
+    assert L.gg_eg_decode_dequant(P, P, 100, 0, float("inf"), P, 0, None) == -1
+    assert L.gg_eg_decode_dequant(P, P, 100, 0, 0.1, P + 4, 0, None) == -1                        # misaligned output
+    assert L.gg_eg_decode_dequant(P, P, 100, 16, 0.1, P, 0, None) == -1
+    assert L.gg_eg_decode_dequant(P, None, 100, 0, 0.1, P, 0, None) == -1
+    assert L.gg_eg_decode_dequant(P, P, 0, 0, 0.1, None, 0, None) == 0                             # nothing to decode
     out = C.c_double(0)
     assert L.gg_huffman_mean_bits(None, 4, C.byref(out)) == -1
 

@@ -310,6 +310,25 @@ def test_bucket_round_trip_reconstructs_within_one_step(gg):
     assert float(total) / n < 32.0                        # and it does compress an fp32 gradient
 
 
+@pytest.mark.parametrize("n,k", [(1, 0), (255, 0), (4099, 1), (300_001, 0), (1 << 20, 3)])
+def test_eg_stream_decoded_straight_to_values(gg, n, k):
+    """Decode + reconstruct in one kernel: q * delta per element, written or added to what is there."""
+    x = make(n, 0.02, 0.9, seed=60 + k)
+    delta = 0.02 / 16
+    stream, index, total = gg.gg_eg_encode_tensor(x, delta, eg_k=k)
+    hb = host_bits(x)
+    _, _, q = oracle.quantize_rate(hb, delta, eg_k=k, want_symbols=True)
+    want = oracle.dequantize(q, delta)
+    got = gg.gg_eg_decode_dequant(stream, index, n, delta, eg_k=k)
+    assert np.array_equal(got.cpu().numpy(), want)
+    base = torch.linspace(-1, 1, n, device=DEV)
+    acc = gg.gg_eg_decode_dequant(stream, index, n, delta, eg_k=k, out=base.clone(), accumulate=True)
+    assert np.array_equal(acc.cpu().numpy(), oracle.dequantize(q, delta, out=base.cpu().numpy().copy(), accumulate=True))
+    # and it agrees with decoding to symbols first
+    sym = gg.gg_eg_decode(stream, index, n, eg_k=k)
+    assert np.array_equal(sym.cpu().numpy(), q)
+
+
 def test_eg_stream_of_longest_codes(gg):
     # every symbol takes 63 bits (k = 0): the decoder's buffered words run out within a step and are topped up
     n = 5000
