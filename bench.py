@@ -316,7 +316,17 @@ def main():
         extra["eg_encode_segmented_bucket"] = {"elements": n, "stream_bits": bucket_bits, "ms": round(ms_b, 4),
                                                "Gelem/s": round(n / ms_b / 1e6, 2),
                                                "bits_per_element": round(bucket_bits / n, 3)}
-        del bbufs
+        # and back: the stream decoded straight to values, each unit with its step, added to an fp32 buffer
+        tiles = (n + gg.GG_EG_TILE - 1) // gg.GG_EG_TILE
+        xsum = torch.zeros(n, device=dev)
+
+        def step_dec_b():
+            gg.gg_eg_decode_dequant_segmented(bbufs[0], bbufs[1][: tiles + 1], off, delta, ws, 0, out=xsum, accumulate=True)
+
+        step_dec_b()
+        _, ms_db = time_steps(step_dec_b, 5, torch)
+        extra["eg_decode_dequant_segmented_bucket"] = {"elements": n, "ms": round(ms_db, 4), "Gelem/s": round(n / ms_db / 1e6, 2)}
+        del bbufs, xsum
         if args.all:
             extra.update(other_configs(gg, gg_inputs, torch, dev, args))
         out["extra"] = extra

@@ -226,6 +226,12 @@ int gg_eg_decode(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, i
  * array in memory.  delta > 0 and finite; out_dev fp32, 16-byte aligned; the rest as for gg_eg_decode. */
 int gg_eg_decode_dequant(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, int64_t n, int eg_k, float delta,
                          float *out_dev, int accumulate, void *stream);
+/* The same for the stream of a flat bucket (gg_eg_encode_segmented): element i of unit s becomes q_i * delta_dev[s];
+ * a unit without a positive finite step was coded as zeros and decodes to zeros.  n is offsets_host[S]; offsets
+ * and ws_dev as in gg_fit_segmented (the workspace receives the unit table). */
+int gg_eg_decode_dequant_segmented(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, const int64_t *offsets_host,
+                                   int32_t S, int eg_k, const float *delta_dev, float *out_dev, int accumulate, void *ws_dev,
+                                   size_t ws_bytes, void *stream);
 /* The same stream straight from a tensor: symbol i is the quantised x_i (the rate sweep's arithmetic: one
  * fp32 product with 1/delta, NaN -> 0, clamp to +-2^30, GG_FLOOR or GG_NEAREST_EVEN), so the stream is bit for
  * bit what gg_quantize_rate's symbols would give and its length the eg_bits of that call, with no symbol

@@ -79,6 +79,7 @@ def lib():
             "gg_eg_encode_segmented": (ci, [vp, ci, vp, i32, vp, ci, ci, vp, u64, vp, vp, vp, sz, vp]),
             "gg_eg_decode": (ci, [vp, vp, i64, ci, vp, vp]),
             "gg_eg_decode_dequant": (ci, [vp, vp, i64, ci, f32, vp, ci, vp]),
+            "gg_eg_decode_dequant_segmented": (ci, [vp, vp, vp, i32, ci, vp, vp, ci, vp, sz, vp]),
             "gg_huffman_mean_bits": (ci, [vp, i32, C.POINTER(f64)]),
         }
         for name, (res, args) in sig.items():
@@ -401,6 +402,20 @@ def gg_eg_decode_dequant(stream: torch.Tensor, index: torch.Tensor, n: int, delt
         out = torch.empty(n, dtype=torch.float32, device=stream.device)
     _check(lib().gg_eg_decode_dequant(_dev(stream), _dev(index), n, eg_k, _f32(delta), _dev(out), int(bool(accumulate)),
                                       _stream()), "gg_eg_decode_dequant")
+    return out
+
+
+def gg_eg_decode_dequant_segmented(stream: torch.Tensor, index: torch.Tensor, offsets, delta: torch.Tensor, ws: Workspace,
+                                   eg_k: int = 0, out: Optional[torch.Tensor] = None, accumulate: bool = False) -> torch.Tensor:
+    off = _offsets(offsets)
+    n = int(off[-1])
+    if out is None:
+        if accumulate:
+            raise ValueError("accumulate needs the tensor to add to")
+        out = torch.empty(n, dtype=torch.float32, device=stream.device)
+    _check(lib().gg_eg_decode_dequant_segmented(_dev(stream), _dev(index), off.ctypes.data, off.size - 1, eg_k, _dev(delta),
+                                                _dev(out), int(bool(accumulate)), ws.ptr, ws.bytes, _stream()),
+           "gg_eg_decode_dequant_segmented")
     return out
 
 

@@ -237,7 +237,7 @@ static int geometry_segmented(const int64_t *offsets, int32_t S, void *ws, size_
     }
     cpre[S] = (int32_t)chunks;
     g.n_chunks = chunks;
-    g.n_total = offsets[S];   // elements of the buffer the units index into
+    g.n_total = S > 0 ? offsets[S] : 0;   // elements of the buffer the units index into (none without units)
     g.wl = ws_layout(g.n_total, S > 0 ? S : 1);
     if (!ws || ws_bytes < g.wl.total || !aligned16(ws)) return GG_ERR_WORKSPACE;
     g.ws = static_cast<char *>(ws);

@@ -551,18 +551,47 @@ static_assert(kEgStepWords + kEgTopUp <= kEgRing && GG_EG_TILE % kEgDecRow == 0 
               "ring holds a step and a top-up");
 typedef unsigned int EgWords4 __attribute__((ext_vector_type(4), aligned(4)));   // four stream words at any word address
 
-// DEQ: instead of the symbols the kernel writes what they stand for, q * delta in fp32 (or adds it to what is
-// there): the receiving side of a sum of coded tensors needs no symbol array in memory.
-template <bool DEQ>
+// OUT 0: the symbols.  OUT 1, 2: what they stand for instead, q * delta in fp32, written or added to what is
+// there (the receiving side of a sum of coded tensors needs no symbol array in memory) -- 1 with one step for
+// the whole stream, 2 with the step of the unit an element lies in (a flat bucket as gg_eg_encode_segmented
+// codes it; a unit without a positive finite step was coded as zeros and decodes to zeros).
+struct EgUnits { const int64_t *off; const float *delta; int32_t S; };
+
+// the unit that holds element i (the largest u with off[u] <= i; unit 0 for anything before the first)
+__device__ __forceinline__ int eg_unit_of(const EgUnits &un, int64_t i) {
+    int lo = 0, hi = un.S;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (un.off[mid] <= i) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+// move u forward to the unit of element i >= the start of u: a few steps of walking, else a fresh search
+__device__ __forceinline__ void eg_unit_seek(const EgUnits &un, int &u, int64_t i) {
+    for (int step = 0; step < 8 && u + 1 < un.S && un.off[u + 1] <= i; ++step) ++u;
+    if (u + 1 < un.S && un.off[u + 1] <= i) u = eg_unit_of(un, i);
+}
+__device__ __forceinline__ float eg_unit_step(const EgUnits &un, int u) {
+    const float d = un.delta[u];
+    return d > 0.f && isfinite(d) ? d : 0.f;
+}
+
+template <int OUT>
 __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ stream, const uint64_t *__restrict__ index,
                                                   int64_t n, int64_t tiles, int eg_k, int32_t *__restrict__ q,
-                                                  float *__restrict__ xhat, float delta, int accumulate) {
+                                                  float *__restrict__ xhat, float delta, int accumulate, EgUnits un) {
+    __shared__ int tile_unit[64];
     __shared__ uint32_t ring[kEgRing][64];
     __shared__ int32_t stage[64][kEgDecRow + 1];
     const int lane = threadIdx.x;
     const int64_t tile0 = (int64_t)blockIdx.x * 64;
     const int64_t tile = tile0 + lane;
     const bool live = tile < tiles;
+    if constexpr (OUT == 2) {            // read after the first barrier below
+        const int64_t e = tile * GG_EG_TILE;
+        tile_unit[lane] = live && e < n ? eg_unit_of(un, e) : 0;
+    }
+    int row_unit[4] = {-1, -1, -1, -1};  // OUT 2: the units the four rows this lane writes have reached
     const uint64_t pos = live ? index[tile] : 0;
     const uint64_t end = live ? index[tile + 1] : 0;
     const uint32_t *src = stream + (pos >> 5);                              // the lane's words, counted from its first
@@ -648,17 +677,32 @@ __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ s
         for (int r = 0; r < 4; ++r) {
             const int row = r * 16 + (lane >> 2), c = (lane & 3) * 4;
             const int64_t g = (tile0 + row) * GG_EG_TILE + s0 + c;
-            if constexpr (DEQ) {
+            if constexpr (OUT != 0) {
+                float d[4] = {delta, delta, delta, delta};
+                if constexpr (OUT == 2) {
+                    if (g < n) {
+                        if (row_unit[r] < 0) row_unit[r] = tile_unit[row];
+                        int u = row_unit[r];
+                        eg_unit_seek(un, u, g);
+                        row_unit[r] = u;
+                        d[0] = eg_unit_step(un, u);
+                        if (u + 1 >= un.S || g + 4 <= un.off[u + 1]) {
+                            d[1] = d[0]; d[2] = d[0]; d[3] = d[0];          // the four elements share a unit
+                        } else {
+                            for (int x = 1; x < 4; ++x) { eg_unit_seek(un, u, g + x); d[x] = eg_unit_step(un, u); }
+                        }
+                    }
+                }
                 if (g + 4 <= n) {
-                    gg_f4 val = {(float)stage[row][c] * delta, (float)stage[row][c + 1] * delta, (float)stage[row][c + 2] * delta,
-                                 (float)stage[row][c + 3] * delta};
+                    gg_f4 val = {(float)stage[row][c] * d[0], (float)stage[row][c + 1] * d[1], (float)stage[row][c + 2] * d[2],
+                                 (float)stage[row][c + 3] * d[3]};
                     gg_f4 *dst = reinterpret_cast<gg_f4 *>(xhat + g);
                     if (accumulate) val += *dst;
                     *dst = val;
                 } else {
                     for (int x = 0; x < 4; ++x)
                         if (g + x < n) {
-                            const float val = (float)stage[row][c + x] * delta;
+                            const float val = (float)stage[row][c + x] * d[x];
                             xhat[g + x] = accumulate ? xhat[g + x] + val : val;
                         }
                 }
@@ -909,9 +953,9 @@ int gg_eg_decode(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, i
         return GG_ERR_INVALID_ARG;
     const int64_t T = eg_index_tiles(n);
     if ((T + 63) / 64 > 2147483647LL) return GG_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(k_eg_decode<false>, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(k_eg_decode<0>, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
                        reinterpret_cast<const uint32_t *>(stream_dev), block_offsets_dev, n, T, eg_k, symbols_dev,
-                       (float *)nullptr, 0.f, 0);
+                       (float *)nullptr, 0.f, 0, EgUnits{nullptr, nullptr, 0});
     return check_launch();
 }
 
@@ -925,9 +969,31 @@ int gg_eg_decode_dequant(const uint8_t *stream_dev, const uint64_t *block_offset
         return GG_ERR_INVALID_ARG;
     const int64_t T = eg_index_tiles(n);
     if ((T + 63) / 64 > 2147483647LL) return GG_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(k_eg_decode<true>, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(k_eg_decode<1>, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
                        reinterpret_cast<const uint32_t *>(stream_dev), block_offsets_dev, n, T, eg_k, (int32_t *)nullptr,
-                       out_dev, delta, accumulate ? 1 : 0);
+                       out_dev, delta, accumulate ? 1 : 0, EgUnits{nullptr, nullptr, 0});
+    return check_launch();
+}
+
+int gg_eg_decode_dequant_segmented(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, const int64_t *offsets_host,
+                                   int32_t S, int eg_k, const float *delta_dev, float *out_dev, int accumulate, void *ws_dev,
+                                   size_t ws_bytes, void *stream) {
+    if (eg_k < 0 || eg_k > GG_MAX_EG_K) return GG_ERR_INVALID_ARG;
+    Geometry g;
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    if (rc != GG_OK) return rc;
+    const int64_t n = g.n_total;
+    if (n == 0) return GG_OK;
+    if (!stream_dev || (reinterpret_cast<uintptr_t>(stream_dev) & 3u) || !block_offsets_dev || !aligned8(block_offsets_dev) ||
+        !delta_dev || !out_dev || !aligned16(out_dev))
+        return GG_ERR_INVALID_ARG;
+    const int64_t T = eg_index_tiles(n);
+    if ((T + 63) / 64 > 2147483647LL) return GG_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = upload_geometry(g, st)) != GG_OK) return rc;
+    hipLaunchKernelGGL(k_eg_decode<2>, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, st,
+                       reinterpret_cast<const uint32_t *>(stream_dev), block_offsets_dev, n, T, eg_k, (int32_t *)nullptr,
+                       out_dev, 0.f, accumulate ? 1 : 0, EgUnits{g.sv.off, delta_dev, S});
     return check_launch();
 }
 

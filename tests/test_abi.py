@@ -138,6 +138,11 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.gg_eg_decode_dequant(P, P, 100, 16, 0.1, P, 0, None) == -1
     assert L.gg_eg_decode_dequant(P, None, 100, 0, 0.1, P, 0, None) == -1
     assert L.gg_eg_decode_dequant(P, P, 0, 0, 0.1, None, 0, None) == 0                             # nothing to decode
+    assert L.gg_eg_decode_dequant_segmented(P, P, off.ctypes.data, 3, 0, P, P, 0, P, ws_bytes, None) == -3     # decreasing offsets
+    assert L.gg_eg_decode_dequant_segmented(P, P, ok_off.ctypes.data, 3, 0, None, P, 0, P, ws_bytes, None) == -1  # no steps
+    assert L.gg_eg_decode_dequant_segmented(P, P, ok_off.ctypes.data, 3, 0, P, P, 0, None, 0, None) == -4         # no workspace
+    assert L.gg_eg_decode_dequant_segmented(P, P, ok_off.ctypes.data, 3, 16, P, P, 0, P, ws_bytes, None) == -1
+    assert L.gg_eg_decode_dequant_segmented(P, P, ok_off.ctypes.data, 0, 0, None, None, 0, P, ws_bytes, None) == 0 # no units
     out = C.c_double(0)
     assert L.gg_huffman_mean_bits(None, 4, C.byref(out)) == -1
 

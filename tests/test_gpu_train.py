@@ -329,6 +329,39 @@ def test_eg_stream_decoded_straight_to_values(gg, n, k):
     assert np.array_equal(sym.cpu().numpy(), q)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_bucket_stream_decoded_straight_to_values_with_a_step_per_unit(gg, dtype):
+    """Bucket -> one stream -> values: every element comes back as q * (its unit's step), bit for bit what the
+    oracle's symbols and steps give; units of zeros (no step) come back as zeros; accumulate adds."""
+    sizes = [5000, 0, 3, 1, 40_000, 0, 0, 257, 16384, 2, 70_001, 255]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    S, n = len(sizes), int(off[-1])
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(77)
+    flat = torch.cat([gg_inputs.gg_torch(sz, 10.0 ** (-1 - (i % 3)), 0.6 + 0.15 * i, gen, DEV, dtype) for i, sz in enumerate(sizes)])
+    flat[int(off[7]):int(off[8])] = 0                      # a unit of zeros: its fit gives no step
+    ws = gg.Workspace(n, S)
+    fit = gg.gg_fit_segmented(flat, off, ws)
+    steps = gg.gg_delta_from_fit(fit, S, 16.0)
+    stream, index, total = gg.gg_eg_encode_segmented(flat, off, steps, ws, eg_k=1)
+    got = gg.gg_eg_decode_dequant_segmented(stream, index, off, steps, ws, eg_k=1).cpu().numpy()
+    base = torch.linspace(-2, 2, n, device=DEV)
+    acc = gg.gg_eg_decode_dequant_segmented(stream, index, off, steps, ws, eg_k=1, out=base.clone(), accumulate=True).cpu().numpy()
+    hb, st, b0 = host_bits(flat), steps.cpu().numpy(), base.cpu().numpy()
+    for u in range(S):
+        lo, hi = int(off[u]), int(off[u + 1])
+        if hi == lo:
+            continue
+        if not (st[u] > 0 and np.isfinite(st[u])):
+            assert u == 7 and not got[lo:hi].any() and np.array_equal(acc[lo:hi], b0[lo:hi])
+            continue
+        _, _, q = oracle.quantize_rate(hb[lo:hi], float(st[u]), eg_k=1, want_symbols=True)
+        assert np.array_equal(got[lo:hi], oracle.dequantize(q, float(st[u]))), u
+        assert np.array_equal(acc[lo:hi], oracle.dequantize(q, float(st[u]), out=b0[lo:hi].copy(), accumulate=True)), u
+        x = hb[lo:hi] if dtype == torch.float32 else gg_inputs.bf16_bits_to_f32(hb[lo:hi])
+        assert np.all(np.abs(x - got[lo:hi]) <= st[u] * (1 + 1e-5))       # within one step of the input
+
+
 def test_eg_stream_of_longest_codes(gg):
     # every symbol takes 63 bits (k = 0): the decoder's buffered words run out within a step and are topped up
     n = 5000
