@@ -543,11 +543,20 @@ __global__ __launch_bounds__(kBlock) void k_eg_encode(Src src, int64_t n, int64_
 // Sixteen symbols per lane are collected in LDS and written as one 64-byte piece per tile.  Reads stay
 // below the word that holds the tile's last bit, whatever the stream contains.
 constexpr int kEgDecStep = 4;      // symbols between top-ups
-constexpr int kEgDecRow = 16;      // symbols per lane between writes
+// Symbols a lane decodes between writes (ROW of k_eg_decode).  32 symbols of a tile are one 128-byte line per
+// store round: 16 was 10 % slower, 8 and 4 25-80 % (partial lines), 64 15 % (LDS leaves room for fewer waves).
+// The per-unit variant, whose writers also track units, does best at 16.
+#ifndef GG_EG_DEC_ROW
+#define GG_EG_DEC_ROW 32
+#endif
+#ifndef GG_EG_DEC_ROW_UNITS
+#define GG_EG_DEC_ROW_UNITS 16
+#endif
 constexpr int kEgRing = 16;        // ring words per lane
 constexpr int kEgTopUp = 4;        // words a lane loads per top-up
 constexpr int kEgStepWords = 10;   // a step takes at most 4 x 63 bits < 8 words, plus the look-ahead word and slack
-static_assert(kEgStepWords + kEgTopUp <= kEgRing && GG_EG_TILE % kEgDecRow == 0 && kEgDecRow % kEgDecStep == 0,
+static_assert(kEgStepWords + kEgTopUp <= kEgRing && GG_EG_TILE % GG_EG_DEC_ROW == 0 && GG_EG_DEC_ROW % kEgDecStep == 0 &&
+              GG_EG_TILE % GG_EG_DEC_ROW_UNITS == 0 && GG_EG_DEC_ROW_UNITS % kEgDecStep == 0,
               "ring holds a step and a top-up");
 typedef unsigned int EgWords4 __attribute__((ext_vector_type(4), aligned(4)));   // four stream words at any word address
 
@@ -576,13 +585,15 @@ __device__ __forceinline__ float eg_unit_step(const EgUnits &un, int u) {
     return d > 0.f && isfinite(d) ? d : 0.f;
 }
 
-template <int OUT>
+template <int OUT, int ROW>
 __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ stream, const uint64_t *__restrict__ index,
                                                   int64_t n, int64_t tiles, int eg_k, int32_t *__restrict__ q,
                                                   float *__restrict__ xhat, float delta, int accumulate, EgUnits un) {
     __shared__ int tile_unit[64];
     __shared__ uint32_t ring[kEgRing][64];
-    __shared__ int32_t stage[64][kEgDecRow + 1];
+    constexpr int kEgLanesPerTile = ROW / 4;          // lanes that write one tile's symbols of a round, 16 bytes each
+    constexpr int kEgTilesPerPass = 64 / kEgLanesPerTile;   // tiles one store instruction of the wave covers
+    __shared__ int32_t stage[64][ROW + 1];
     const int lane = threadIdx.x;
     const int64_t tile0 = (int64_t)blockIdx.x * 64;
     const int64_t tile = tile0 + lane;
@@ -591,7 +602,9 @@ __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ s
         const int64_t e = tile * GG_EG_TILE;
         tile_unit[lane] = live && e < n ? eg_unit_of(un, e) : 0;
     }
-    int row_unit[4] = {-1, -1, -1, -1};  // OUT 2: the units the four rows this lane writes have reached
+    int row_unit[kEgLanesPerTile];       // OUT 2: the units the rows this lane writes have reached
+#pragma unroll
+    for (int r = 0; r < kEgLanesPerTile; ++r) row_unit[r] = -1;
     const uint64_t pos = live ? index[tile] : 0;
     const uint64_t end = live ? index[tile + 1] : 0;
     const uint32_t *src = stream + (pos >> 5);                              // the lane's words, counted from its first
@@ -637,9 +650,9 @@ __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ s
     };
 
     const uint32_t add = 1u << eg_k;
-    for (int s0 = 0; s0 < GG_EG_TILE; s0 += kEgDecRow) {
+    for (int s0 = 0; s0 < GG_EG_TILE; s0 += ROW) {
 #pragma unroll
-        for (int s1 = 0; s1 < kEgDecRow; s1 += kEgDecStep) {
+        for (int s1 = 0; s1 < ROW; s1 += kEgDecStep) {
             while (__any(ld - rd < (uint32_t)kEgStepWords)) {          // rare: only streams with very long codes
                 if (ld - rd < (uint32_t)kEgStepWords) commit4(fetch4());
             }
@@ -672,10 +685,11 @@ __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ s
             if (more) commit4(pre);
         }
         __syncthreads();
-        // four lanes cover one tile's 16 symbols (64 bytes); 16 tiles per instruction, 4 instructions
+        // kEgLanesPerTile lanes cover one tile's symbols of this round (ROW 32: eight lanes write its 128 bytes, a
+        // store instruction of the wave covers 8 tiles, 8 instructions)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = r * 16 + (lane >> 2), c = (lane & 3) * 4;
+        for (int r = 0; r < kEgLanesPerTile; ++r) {
+            const int row = r * kEgTilesPerPass + lane / kEgLanesPerTile, c = (lane % kEgLanesPerTile) * 4;
             const int64_t g = (tile0 + row) * GG_EG_TILE + s0 + c;
             if constexpr (OUT != 0) {
                 float d[4] = {delta, delta, delta, delta};
@@ -953,7 +967,7 @@ int gg_eg_decode(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, i
         return GG_ERR_INVALID_ARG;
     const int64_t T = eg_index_tiles(n);
     if ((T + 63) / 64 > 2147483647LL) return GG_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(k_eg_decode<0>, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL((k_eg_decode<0, GG_EG_DEC_ROW>), dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
                        reinterpret_cast<const uint32_t *>(stream_dev), block_offsets_dev, n, T, eg_k, symbols_dev,
                        (float *)nullptr, 0.f, 0, EgUnits{nullptr, nullptr, 0});
     return check_launch();
@@ -969,7 +983,7 @@ int gg_eg_decode_dequant(const uint8_t *stream_dev, const uint64_t *block_offset
         return GG_ERR_INVALID_ARG;
     const int64_t T = eg_index_tiles(n);
     if ((T + 63) / 64 > 2147483647LL) return GG_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(k_eg_decode<1>, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL((k_eg_decode<1, GG_EG_DEC_ROW>), dim3((unsigned)((T + 63) / 64)), dim3(64), 0, (hipStream_t)stream,
                        reinterpret_cast<const uint32_t *>(stream_dev), block_offsets_dev, n, T, eg_k, (int32_t *)nullptr,
                        out_dev, delta, accumulate ? 1 : 0, EgUnits{nullptr, nullptr, 0});
     return check_launch();
@@ -991,7 +1005,7 @@ int gg_eg_decode_dequant_segmented(const uint8_t *stream_dev, const uint64_t *bl
     if ((T + 63) / 64 > 2147483647LL) return GG_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     if ((rc = upload_geometry(g, st)) != GG_OK) return rc;
-    hipLaunchKernelGGL(k_eg_decode<2>, dim3((unsigned)((T + 63) / 64)), dim3(64), 0, st,
+    hipLaunchKernelGGL((k_eg_decode<2, GG_EG_DEC_ROW_UNITS>), dim3((unsigned)((T + 63) / 64)), dim3(64), 0, st,
                        reinterpret_cast<const uint32_t *>(stream_dev), block_offsets_dev, n, T, eg_k, (int32_t *)nullptr,
                        out_dev, 0.f, accumulate ? 1 : 0, EgUnits{g.sv.off, delta_dev, S});
     return check_launch();
