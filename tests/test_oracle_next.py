@@ -130,6 +130,8 @@ def test_dequantize_gives_the_lower_end_of_the_quantiser_cell():
     _, _, q = oracle.quantize_rate(x, delta, want_symbols=True)
     lo = oracle.dequantize(q, delta)
     assert np.all(lo <= x) and np.all(x < lo + np.float32(delta))
+    _, _, q_again = oracle.quantize_rate(lo, delta, want_symbols=True)
+    assert np.array_equal(q_again, q)                                  # decoding and quantising again is the identity on symbols
     # nearest mode: within half a step
     _, _, qn = oracle.quantize_rate(x, delta, round_mode=oracle.ROUND_NEAREST_EVEN, want_symbols=True)
     assert np.all(np.abs(oracle.dequantize(qn, delta) - x) <= np.float32(delta / 2))
