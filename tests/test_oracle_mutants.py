@@ -201,7 +201,7 @@ def _run(case, source, header, folder):
 
 
 @pytest.fixture(scope="module")
-def verdicts(tmp_path_factory):
+def outcomes(tmp_path_factory):
     """Every case built and run once, eight at a time: name -> None (noticed) or what went wrong."""
     with open(os.path.join(SRC_DIR, "gg_oracle.c")) as f:
         source = f.read()
@@ -214,5 +214,5 @@ def verdicts(tmp_path_factory):
 
 
 @pytest.mark.parametrize("name", [m[0] for m in MUTANTS])
-def test_a_planted_mistake_fails_its_pin(name, verdicts):
-    assert verdicts[name] is None, verdicts[name]
+def test_a_planted_mistake_fails_its_pin(name, outcomes):
+    assert outcomes[name] is None, outcomes[name]
