@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--small", action="store_true", help="1/64-scale bucket (quick functional run)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--extra", action="store_true", help="also time the penalty variant and the sampler")
-    ap.add_argument("--all", action="store_true", help="--extra plus the other BASELINE configurations (C1, C2, C3, C5)")
+    ap.add_argument("--all", action="store_true", help="--extra plus the other benchmark configurations (C1, C2, C3, C5)")
     ap.add_argument("--cpu-sample-elems", type=int, default=380_000_000)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of known size (counter calibration under rocprofv3 --pmc)")
@@ -57,7 +57,7 @@ def time_steps(fn, steps, torch):
 
 
 def other_configs(gg, gg_inputs, torch, dev, args):
-    """The remaining BASELINE configurations, each timed as one whole call (HIP events, 10 calls)."""
+    """The remaining benchmark configurations, each timed as one whole call (HIP events, 10 calls)."""
     res = {}
     reps = 10
 
