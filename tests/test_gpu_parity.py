@@ -709,6 +709,45 @@ def test_two_streams_with_their_own_workspaces_do_not_interfere(gg):
         assert [outs[i][k].cpu().numpy().tobytes() for k in ("fit", "rate", "hist")] == alone, i
 
 
+def test_rows_histogram_coder_and_sampler_are_graph_capturable(gg):
+    """The other launch paths under capture: the wave-per-row pass and the block-private histogram (both ask the
+    runtime for occupancy figures while launching), the coder in both directions, the sampler.  Replays with
+    eager work between them have to give what eager calls give on the same inputs."""
+    rows, cols = 300, 512
+    n = rows * cols
+    x = make(n, 0.3, 1.1, seed=9, dtype=torch.bfloat16)
+    ws, ws1 = gg.Workspace(n, rows), gg.Workspace(n, 1)
+    bufs = gg.eg_buffers(n, None, DEV)
+    tiles = (n + gg.GG_EG_TILE - 1) // gg.GG_EG_TILE
+
+    def work():
+        r = gg.gg_fused_rows(x, rows, cols, ws, delta_div=8.0, want_total=True)
+        rate, hist, sym = gg.gg_quantize_rate(x, 0.01, ws1, nbins=4096, want_symbols=True)
+        gg.gg_eg_encode_tensor(x, 0.01, buffers=bufs)
+        back = gg.gg_eg_decode_dequant(bufs[0], bufs[1][: tiles + 1], n, 0.01)
+        smp = gg.gg_sample(5000, 0.1, 0.7, seed=3)
+        return [r["fit"], r["rate"], r["total"], rate, hist, sym, bufs[2], back, smp]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        work()                                             # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        outs = work()
+    for rep in range(3):
+        x.mul_(1.0 + 0.5 * rep)                            # eager work between replays, new input values
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.cpu().numpy().tobytes() for t in outs]
+        want = [t.cpu().numpy().tobytes() for t in work()]
+        torch.cuda.synchronize()
+        assert got == want, rep
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_fused_one_sweep_mode_with_given_steps(gg, dtype):
     """Steps handed in (no dependence on this call's fit): moments and rate from one read of x."""
