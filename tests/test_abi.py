@@ -204,3 +204,25 @@ def test_empty_calls_are_ok_without_gpu_work():
     assert L.gg_sample(None, 0, 0, 0.1, 1.0, 1, 0, 0, None) == 0
     assert L.gg_philox_words(None, 0, 1, 0, 0, 0, None) == 0
     assert L.gg_delta_from_fit(None, 0, 16.0, None, None) == 0
+
+
+def test_solver_curve_written_at_build_time_matches_scipy():
+    """The moment-ratio curve compiled into the library (csrc/gg_solve_curve.inc, written by gen_solve_curve.py):
+    every point against scipy's log-gamma (an implementation of its own), the grid against the header's range."""
+    from scipy.special import gammaln
+    _lib()                                                   # builds, and with it writes the curve, if absent
+    path = os.path.join(ROOT, "paper_2506_00486_amd", "csrc", "gg_solve_curve.inc")
+    rows = [line.strip(" {},\n").split(",") for line in open(path) if line.startswith("{")]
+    curve = np.array(rows, dtype=np.float64)
+    header = open(os.path.join(ROOT, "include", "gg.h")).read()
+    b_min = float(re.search(r"#define GG_BETA_MIN ([0-9.]+)", header).group(1))
+    b_max = float(re.search(r"#define GG_BETA_MAX ([0-9.]+)", header).group(1))
+    assert curve.shape == (4097, 2)
+    b = np.exp(np.linspace(np.log(b_min), np.log(b_max), 4097))
+    r = 1.0 / b
+    assert np.allclose(curve[:, 0], 2 * gammaln(2 * r) - gammaln(r) - gammaln(3 * r), rtol=1e-12, atol=1e-12)
+    assert np.allclose(curve[:, 1], gammaln(r) - gammaln(3 * r), rtol=1e-12, atol=1e-12)
+    assert np.all(np.diff(curve[:, 0]) > 0)                  # rho grows with the shape: the search relies on it
+    # closed forms on the grid's neighbours of beta = 1 and 2: rho = 1/2 and 2/pi
+    for beta, rho in ((1.0, 0.5), (2.0, 2.0 / np.pi)):
+        assert np.interp(np.log(beta), np.log(b), curve[:, 0]) == pytest.approx(np.log(rho), abs=1e-6)
