@@ -389,6 +389,26 @@ __global__ __launch_bounds__(kTotalThreads) void k_fit_total(const gg_fit_t *__r
     }
 }
 
+// the same from the sums the waves of k_rows leave (fewer and smaller than the row records)
+__global__ __launch_bounds__(kTotalThreads) void k_fit_total_waves(const double2 *__restrict__ sums, int64_t n_waves, uint64_t n_elems,
+                                                                   gg_fit_t *__restrict__ out) {
+    __shared__ double red1[kTotalThreads / 64], red2[kTotalThreads / 64];
+    const int tid = threadIdx.x;
+    double s1 = 0.0, s2 = 0.0;
+    for (int64_t w = tid; w < n_waves; w += kTotalThreads) { s1 += sums[w].x; s2 += sums[w].y; }
+    s1 = wave_reduce(s1, OpAdd());
+    s2 = wave_reduce(s2, OpAdd());
+    if ((tid & 63) == 0) { red1[tid >> 6] = s1; red2[tid >> 6] = s2; }
+    __syncthreads();
+    if (tid < 64) {
+        s1 = 0.0; s2 = 0.0;
+        for (int w = 0; w < kTotalThreads / 64; ++w) { s1 += red1[w]; s2 += red2[w]; }
+        gg_fit_t f;
+        solve_fit_wave(s1, s2, n_elems, f);
+        if (tid == 0) out[0] = f;
+    }
+}
+
 // parameters for calls that do not fit first (one thread per unit)
 __global__ void k_seg_prepare(SegView sv, PrepArgs prep) {
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -818,6 +838,9 @@ struct RowsArgs {
     int32_t *symbols; float *grad; int accumulate;
     int do_fit;
     int batch;                // rows per wave and solve, 1..kRowBatch (set by the launcher)
+    double2 *wave_sums;       // per wave of the grid: sum |x|, sum x^2 over its rows (for the whole-matrix fit), or nullptr
+    int64_t wave_sums_cap;    // host: entries wave_sums has room for
+    gg_fit_t *total_out;      // host: where the whole-matrix fit goes (launched behind the row kernel), or nullptr
 };
 
 template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA>
@@ -826,6 +849,7 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
     const int64_t n_waves = (int64_t)gridDim.x * kWaves;
     const int len = (int)a.cols;
     const int batch = a.batch;       // rows a wave takes at a time, 1..kRowBatch: one lane-parallel solve per batch
+    double tot1 = 0.0, tot2 = 0.0;   // lane r: sums over the r-th rows of this wave's batches
     for (int64_t row0 = ((int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * batch; row0 < a.rows; row0 += n_waves * batch) {
         const int nr = a.rows - row0 < batch ? (int)(a.rows - row0) : batch;
         // lane r < nr works for row row0 + r from here to the second sweep
@@ -847,6 +871,7 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
             gg_fit_t f;
             solve_fit_batch(my_s1, my_s2, (uint64_t)len, nr, f);
             if (lane < nr) { a.fit[row0 + lane] = f; alpha = f.alpha; beta = f.beta; }
+            tot1 += my_s1; tot2 += my_s2;
         }
         if constexpr (RATE || PEN) {
             // the per-row constants of the second sweep, again one lane per row
@@ -899,6 +924,11 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
                 }
             }
         }
+    }
+    if (a.wave_sums) {               // every wave of the grid, also one without rows: the reader adds them all
+        tot1 = wave_reduce(tot1, OpAdd());
+        tot2 = wave_reduce(tot2, OpAdd());
+        if (lane == 0) a.wave_sums[(int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6)] = make_double2(tot1, tot2);
     }
 }
 
@@ -1327,8 +1357,20 @@ static int launch_rows_inst(const void *x, RowsArgs a, hipStream_t st) {
     const int64_t per_block = (int64_t)kWaves * batch;
     int64_t blocks = (a.rows + per_block - 1) / per_block;
     if (blocks > cap) blocks = cap;
+    // the whole-matrix fit: from the sums the waves leave when the workspace has room for them (fewer and
+    // smaller than the row records), else from the row records
+    const bool want_total = a.total_out != nullptr && a.do_fit;
+    const bool by_waves = want_total && a.wave_sums != nullptr && a.wave_sums_cap >= blocks * kWaves;
+    if (!by_waves) a.wave_sums = nullptr;
     hipLaunchKernelGGL((k_rows<T, MODE, RATE, PEN, EXTRA>), dim3((unsigned)blocks), dim3(kBlock), 0, st,
                        static_cast<const T *>(x), a);
+    if (want_total) {
+        if (by_waves)
+            hipLaunchKernelGGL(k_fit_total_waves, dim3(1), dim3(kTotalThreads), 0, st, (const double2 *)a.wave_sums, blocks * kWaves,
+                               (uint64_t)(a.rows * a.cols), a.total_out);
+        else
+            hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, (const gg_fit_t *)a.fit, a.rows, a.total_out);
+    }
     return check_launch();
 }
 
@@ -1498,11 +1540,10 @@ int gg_fit_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, gg_fit
     if (rows_take_wave_path(rows, cols)) {
         RowsArgs a{};
         a.rows = rows; a.cols = cols; a.fit = out_dev; a.do_fit = 1;
-        rc = launch_rows(g, x_dev, dtype, a, 0, GG_FLOOR, false, false, st);
-    } else {
-        rc = launch_fit(g, x_dev, dtype, out_dev, nullptr, st);
+        a.total_out = total_out_dev; a.wave_sums = g.partials(); a.wave_sums_cap = (int64_t)(g.wl.partials_bytes / sizeof(double2));
+        return launch_rows(g, x_dev, dtype, a, 0, GG_FLOOR, false, false, st);
     }
-    if (rc != GG_OK) return rc;
+    if ((rc = launch_fit(g, x_dev, dtype, out_dev, nullptr, st)) != GG_OK) return rc;
     if (total_out_dev) {
         hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, out_dev, rows, total_out_dev);
         return check_launch();
@@ -1712,12 +1753,8 @@ int gg_fused_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, floa
         a.rows = rows; a.cols = cols; a.fit = fit_dev; a.rate = rate_dev; a.delta_dev = delta_dev; a.delta_div = delta_div;
         a.lambda = lambda; a.symbols = rate_dev ? symbols_dev : nullptr; a.grad = grad_dev; a.accumulate = accumulate ? 1 : 0;
         a.do_fit = 1;
-        if ((rc = launch_rows(g, x_dev, dtype, a, eg_k, round_mode, rate_dev != nullptr, grad_dev != nullptr, st)) != GG_OK) return rc;
-        if (total_fit_dev) {
-            hipLaunchKernelGGL(k_fit_total, dim3(1), dim3(kTotalThreads), 0, st, fit_dev, rows, total_fit_dev);
-            return check_launch();
-        }
-        return GG_OK;
+        a.total_out = total_fit_dev; a.wave_sums = g.partials(); a.wave_sums_cap = (int64_t)(g.wl.partials_bytes / sizeof(double2));
+        return launch_rows(g, x_dev, dtype, a, eg_k, round_mode, rate_dev != nullptr, grad_dev != nullptr, st);
     }
     return fused_common(g, x_dev, dtype, delta_div, delta_dev, eg_k, round_mode, 0, nullptr, symbols_dev, lambda, grad_dev,
                         accumulate ? 1 : 0, fit_dev, total_fit_dev, rate_dev, (hipStream_t)stream);
