@@ -1022,17 +1022,25 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, 
             red_bits[tid >> 6] = t.bits; red_u[0][tid >> 6] = t.u_max; red_u[1][tid >> 6] = t.n_clamped; red_u[2][tid >> 6] = t.flags;
         }
     }
+    // bins above the unit's largest symbol are empty (a clamped symbol makes the largest >= nbins - 1): skip them
+    uint32_t um = r->u_max;                        // final for a unit inside one run
+    if (shared) {                                  // uniform over the block
+        __syncthreads();
+        um = 0;
+        for (int w = 0; w < kFinalizeThreads / 64; ++w) um = red_u[0][w] > um ? red_u[0][w] : um;
+    }
+    const int used = um < (uint32_t)(nbins - 1) ? (int)um + 1 : nbins;
     double h = 0.0;
     if (live) {
         const uint64_t *g = hist + (int64_t)seg * nbins;
         const double inv_n = 1.0 / (double)n;
         // ascending bins per lane, fixed tree above; eight loads in flight, the terms still added in bin order
-        for (int b0 = tid; b0 < nbins; b0 += 8 * kFinalizeThreads) {
+        for (int b0 = tid; b0 < used; b0 += 8 * kFinalizeThreads) {
             uint64_t c[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int b = b0 + k * kFinalizeThreads;
-                c[k] = b < nbins ? g[b] : 0;
+                c[k] = b < used ? g[b] : 0;
             }
 #pragma unroll
             for (int k = 0; k < 8; ++k)
