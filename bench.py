@@ -233,7 +233,9 @@ def main():
 
         step_sample()
         _, ms_s = time_steps(step_sample, 5, torch)
-        extra["gg_sample_bf16"] = {"elements": ns, "ms": round(ms_s, 4), "Gsamples/s": round(ns / ms_s / 1e6, 2)}
+        extra["gg_sample_bf16"] = {"elements": ns, "ms": round(ms_s, 4), "Gsamples/s": round(ns / ms_s / 1e6, 2),
+                                   "written_GB/s": round(2.0 * ns / ms_s / 1e6, 1),      # ALU-bound: a few % of the HBM peak
+                                   "frac_of_hbm_peak": round(2.0 * ns / ms_s / 1e6 / HBM_PEAK_GBS, 4)}
         del xs
         # companions: GCT update over the same bucket (reads g, ghat_prev, w; writes ghat, w = 20 B/elem),
         # rate gradient (4 B read + 4 B written), Exp-Golomb bit-stream encoder on a 64M-symbol slice
