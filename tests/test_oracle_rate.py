@@ -221,6 +221,9 @@ def test_laplace_closed_form_entropy_and_eg_rate():
     # small-step law: H ~ h(X)/ln2 - log2(Delta), h = 1 + ln(2 alpha) for Laplace
     assert H == pytest.approx((1.0 + math.log(2.0)) / math.log(2.0) - math.log2(r), abs=5e-4)
     assert H == pytest.approx(6.44293, abs=2e-5)
+    # the same mean with the order-0 length written out as 2 * bit_length(u + 1) - 1
+    by_hand = float(np.sum(p * [2 * int(v + 1).bit_length() - 1 for v in u_pos]) + np.sum(p * [2 * int(v + 1).bit_length() - 1 for v in u_neg]))
+    assert mean_len == pytest.approx(by_hand, abs=1e-12) and mean_len == pytest.approx(8.69872, abs=2e-5)
     # sampled source (scipy's Laplace, independent of the oracle's sampler)
     alpha, n = 0.02, 4_000_000
     x = stats.laplace.rvs(scale=alpha, size=n, random_state=np.random.default_rng(3)).astype(np.float32)
