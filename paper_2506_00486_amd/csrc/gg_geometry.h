@@ -219,10 +219,18 @@ static int geometry_uniform(int64_t rows, int64_t cols, void *ws, size_t ws_byte
     return GG_OK;
 }
 
-static int geometry_segmented(const int64_t *offsets, int32_t S, void *ws, size_t ws_bytes, Geometry &g) {
+// `single_as_uniform`: a bucket of one unit that starts at element 0 is a plain tensor; described as one (no
+// unit table to upload, no search in the kernels) when the caller's kernels need no table on the device.
+static int geometry_segmented(const int64_t *offsets, int32_t S, void *ws, size_t ws_bytes, Geometry &g,
+                              bool single_as_uniform = false) {
     // the unit table travels through kernel arguments (448 words per launch): keep it to a few thousand launches
     if (!offsets || S < 0 || S > kMaxSegments) return S < 0 || !offsets ? GG_ERR_INVALID_ARG : GG_ERR_BAD_SEGMENTS;
     if (offsets[0] < 0) return GG_ERR_BAD_SEGMENTS;
+    if (single_as_uniform && S == 1 && offsets[0] == 0) {
+        if (offsets[1] < 0) return GG_ERR_BAD_SEGMENTS;
+        const int rc = geometry_uniform(1, offsets[1], ws, ws_bytes, true, g);
+        return rc == GG_ERR_INVALID_ARG ? GG_ERR_BAD_SEGMENTS : rc;
+    }
     g.S = S;
     const size_t n_off = (size_t)S + 1;
     g.table.assign(n_off + (n_off + 1) / 2, 0);

@@ -1527,7 +1527,7 @@ int gg_fit_segmented(const void *x_dev, int dtype, const int64_t *offsets_host, 
                      void *ws_dev, size_t ws_bytes, void *stream) {
     if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
     Geometry g;
-    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g, true);
     if (rc != GG_OK) return rc;
     if ((rc = check_x(x_dev, dtype, g.n_total)) != GG_OK) return rc;
     if (S > 0 && (!out_dev || !aligned8(out_dev))) return GG_ERR_INVALID_ARG;
@@ -1585,7 +1585,7 @@ int gg_quantize_rate_segmented(const void *x_dev, int dtype, const int64_t *offs
                                int32_t *symbols_dev, gg_rate_t *out_dev, void *ws_dev, size_t ws_bytes, void *stream) {
     if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
     Geometry g;
-    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g, true);
     if (rc != GG_OK) return rc;
     if ((rc = check_x(x_dev, dtype, g.n_total)) != GG_OK) return rc;
     if ((rc = check_rate_args(eg_k, round_mode, nbins, hist_dev, symbols_dev)) != GG_OK) return rc;
@@ -1660,7 +1660,7 @@ int gg_penalty_grad_segmented(const void *w_dev, int dtype, const int64_t *offse
                               size_t ws_bytes, void *stream) {
     if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
     Geometry g;
-    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g, true);
     if (rc != GG_OK) return rc;
     if ((rc = check_x(w_dev, dtype, g.n_total)) != GG_OK) return rc;
     if (!std::isfinite(lambda)) return GG_ERR_INVALID_ARG;
@@ -1732,7 +1732,7 @@ int gg_fused_segmented(const void *x_dev, int dtype, const int64_t *offsets_host
                        gg_rate_t *rate_dev, void *ws_dev, size_t ws_bytes, void *stream) {
     if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
     Geometry g;
-    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g, true);
     if (rc != GG_OK) return rc;
     if ((rc = check_x(x_dev, dtype, g.n_total)) != GG_OK) return rc;
     if ((rc = check_fused(eg_k, round_mode, nbins, hist_dev, symbols_dev, delta_div, delta_dev, lambda, grad_dev, fit_dev,

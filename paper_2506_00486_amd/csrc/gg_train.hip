@@ -863,7 +863,7 @@ int gg_gct_update_segmented(float *w_dev, const float *g_dev, float *ghat_prev_d
                             const float *delta_dev, float eta, float lambda, float eps, int eg_k, int first_step,
                             void *ws_dev, size_t ws_bytes, void *stream) {
     Geometry g;
-    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
+    int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g, true);
     if (rc != GG_OK) return rc;
     if ((rc = check_gct(w_dev, g_dev, ghat_prev_dev, g.n_total, eta, lambda, eps, eg_k)) != GG_OK) return rc;
     if (S > 0 && !delta_dev) return GG_ERR_INVALID_ARG;
