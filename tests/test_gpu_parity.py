@@ -685,6 +685,29 @@ def test_random_matrices_by_rows_against_the_oracle(gg, seed):
             check_penalty(g[r_ * cols:(r_ + 1) * cols], oracle.penalty_grad(xs, frec[r_]["alpha"], frec[r_]["beta"], lam), where)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_one_unit_bucket_with_and_without_a_unit_table(gg, dtype):
+    """A bucket of one unit starting at element 0 is handled as a plain tensor (no unit table); the same
+    unit behind 16 other elements goes through the table.  Same data, same chunks: the same records."""
+    n, pad = 250_007, 16
+    x = make(n, 0.01, 0.7, seed=88, dtype=dtype)
+    padded = torch.cat([torch.ones(pad, device=DEV, dtype=dtype), x])
+    ws, wsp = gg.Workspace(n, 1), gg.Workspace(n + pad, 1)
+    grad, gradp = torch.zeros(n, device=DEV), torch.zeros(n + pad, device=DEV)
+    a = gg.gg_fused_segmented(x, [0, n], ws, delta_div=16.0, nbins=1024, want_symbols=True, lam=1e-4, grad=grad)
+    b = gg.gg_fused_segmented(padded, [pad, pad + n], wsp, delta_div=16.0, nbins=1024, want_symbols=True, lam=1e-4, grad=gradp)
+    torch.cuda.synchronize()
+    for key in ("fit", "rate", "hist"):
+        assert a[key].cpu().numpy().tobytes() == b[key].cpu().numpy().tobytes(), key
+    assert torch.equal(a["symbols"], b["symbols"][pad:]) and torch.equal(grad, gradp[pad:])
+    frec, rrec = gg.fit_records(a["fit"]), gg.rate_records(a["rate"])
+    hb = host_bits(x)
+    check_fit(frec[0], oracle.fit(hb), "one unit")
+    r, ohist, osym = oracle.quantize_rate(hb, float(rrec[0]["delta"]), nbins=1024, want_symbols=True)
+    check_rate(rrec[0], r, "one unit")
+    assert np.array_equal(a["hist"].cpu().numpy().view(np.uint64), ohist) and np.array_equal(a["symbols"].cpu().numpy(), osym)
+
+
 def test_two_streams_with_their_own_workspaces_do_not_interfere(gg):
     """The library keeps no state between calls: passes over different buffers, enqueued on two streams
     (default priority) so that they overlap, give what each gives alone."""
