@@ -332,7 +332,7 @@ def test_philox_words_bit_exact(gg):
 
 
 @pytest.mark.parametrize("alpha,beta", [(0.02, 1.0), (0.015, 1.5), (0.5, 0.8), (1e-4, 0.5), (0.01, 2.0), (1.0, 0.1),
-                                        (2.0, 6.0)])
+                                        (2.0, 6.0), (0.3, 0.05), (0.3, 20.0)])      # the last two: the ends of the shape range
 def test_sample_tracks_oracle_and_distribution(gg, alpha, beta):
     from scipy import stats
     n = 200_000
