@@ -19,7 +19,8 @@
  *
  * Conventions
  *   - Every pointer named *_dev is DEVICE memory; *_host is HOST memory.  The caller owns all
- *     buffers, including the workspace and the result structs.  The library allocates nothing,
+ *     buffers, including the workspace and the result structs.  The library allocates no device
+ *     memory (and no host memory outside the host helper gg_huffman_mean_bits),
  *     keeps no state between calls and never synchronises: all work is enqueued on `stream`
  *     (a hipStream_t passed as void*; NULL = the default stream); outputs are valid once the
  *     stream reaches that point.  Calls sharing a workspace must be ordered on one stream.
@@ -101,7 +102,8 @@ int gg_workspace_bytes(int64_t n_total, int32_t n_units, int32_t nbins, size_t *
 int gg_fit(const void *x_dev, int dtype, int64_t n, gg_fit_t *out_dev,
            void *ws_dev, size_t ws_bytes, void *stream);
 /* Flat bucket: unit s is x[offsets_host[s] .. offsets_host[s+1]) (element offsets, S+1 entries,
- * non-decreasing, offsets_host[0] >= 0; zero-length units are legal; S <= 2^20).  -> out_dev[S]. */
+ * non-decreasing, offsets_host[0] >= 0; zero-length units are legal; S <= 2^17: the table travels to the
+ * device as kernel arguments, 448 offsets per launch, read from offsets_host before the call returns).  -> out_dev[S]. */
 int gg_fit_segmented(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S,
                      gg_fit_t *out_dev, void *ws_dev, size_t ws_bytes, void *stream);
 /* Row-major rows x cols matrix: one fit per row -> out_dev[rows]; if total_out_dev is not NULL it
@@ -228,7 +230,8 @@ int gg_eg_decode_dequant(const uint8_t *stream_dev, const uint64_t *block_offset
                          float *out_dev, int accumulate, void *stream);
 /* The same for the stream of a flat bucket (gg_eg_encode_segmented): element i of unit s becomes q_i * delta_dev[s];
  * a unit without a positive finite step was coded as zeros and decodes to zeros.  n is offsets_host[S]; offsets
- * and ws_dev as in gg_fit_segmented (the workspace receives the unit table). */
+ * and ws_dev as in gg_fit_segmented (the workspace receives the unit table), except that offsets_host[0] must be 0
+ * (GG_ERR_BAD_SEGMENTS otherwise): the stream holds every element of the buffer, so the units must cover it. */
 int gg_eg_decode_dequant_segmented(const uint8_t *stream_dev, const uint64_t *block_offsets_dev, const int64_t *offsets_host,
                                    int32_t S, int eg_k, const float *delta_dev, float *out_dev, int accumulate, void *ws_dev,
                                    size_t ws_bytes, void *stream);
@@ -242,7 +245,8 @@ int gg_eg_encode_tensor(const void *x_dev, int dtype, int64_t n, float delta, in
 /* The same for a flat bucket with one step per unit (delta_dev[S], e.g. from gg_delta_from_fit; offsets as in
  * gg_fit_segmented): one stream for the whole bucket, equal to the stream of gg_quantize_rate_segmented's
  * symbols; a unit without a positive finite step contributes symbol 0 for every element.  ws_dev as for the
- * segmented calls (it receives the unit table). */
+ * segmented calls (it receives the unit table).  offsets_host[0] must be 0 (GG_ERR_BAD_SEGMENTS otherwise): the
+ * stream codes the elements 0 .. offsets_host[S) of x_dev, each with the step of the unit that holds it. */
 int gg_eg_encode_segmented(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S,
                            const float *delta_dev, int round_mode, int eg_k, uint8_t *stream_dev,
                            uint64_t stream_bytes, uint64_t *block_offsets_dev, uint64_t *total_bits_dev,

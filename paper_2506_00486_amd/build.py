@@ -18,9 +18,6 @@ FLAGS = [
 ]
 
 
-PROBE = os.path.join(HERE, "probe_bandwidth")   # stand-alone measurement tool, see csrc/probe_bandwidth.hip
-
-
 def build(verbose: bool = False) -> str:
     sys.path.insert(0, CSRC)
     try:
@@ -33,11 +30,6 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
-    probe = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-             "-packed-fp32-ops", "-o", PROBE, os.path.join(CSRC, "probe_bandwidth.hip")]
-    if verbose:
-        print(" ".join(probe))
-    subprocess.run(probe, check=True)
     return LIB
 
 

@@ -8,7 +8,6 @@
 #include <string.h>
 
 #include <type_traits>
-#include <vector>
 
 #include "../../include/gg.h"
 #include "gg_device.h"
@@ -131,9 +130,45 @@ struct SegParam {
 // ---------------------------------------------------------------------------------------------
 constexpr int kPackI64 = 448;  // 3584 bytes of kernel arguments per launch
 struct PackI64 { int64_t v[kPackI64]; };
+constexpr int kTableThreads = 1024;
 
-static __global__ void k_upload_i64(PackI64 pack, int count, int64_t *dst) {
-    for (int i = threadIdx.x; i < count; i += blockDim.x) dst[i] = pack.v[i];
+// Chunk prefix of a unit table, by one workgroup of kTableThreads: cpre[s] = chunks of the units before s,
+// cpre[S] = all of them.  A thread takes a contiguous range of units; the range totals are scanned across
+// the block (wave scan, wave totals through LDS) and every thread then writes its own range.
+__device__ __forceinline__ int32_t unit_chunks(const int64_t *off, int s) {
+    return (int32_t)((off[s + 1] - off[s] + kChunk - 1) / kChunk);
+}
+__device__ __forceinline__ void chunk_prefix_block(const int64_t *off, int32_t S, int32_t *cpre) {
+    __shared__ int32_t wave_tot[kTableThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (S + kTableThreads - 1) / kTableThreads;
+    const int s0 = tid * per < S ? tid * per : S, s1 = s0 + per < S ? s0 + per : S;
+    int32_t mine = 0;
+    for (int s = s0; s < s1; ++s) mine += unit_chunks(off, s);
+    int32_t incl = mine;                       // inclusive scan over the wave
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int32_t up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int32_t before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    int32_t run = before + incl - mine;
+    for (int s = s0; s < s1; ++s) { cpre[s] = run; run += unit_chunks(off, s); }
+    if (tid == kTableThreads - 1) cpre[S] = run;   // the last thread's range ends the table (possibly empty)
+}
+
+// `count` table words out of the kernel arguments to dst; the launch that carries the last words of a unit
+// table (cpre != nullptr) also derives the chunk prefix from the complete table `off`.
+static __global__ __launch_bounds__(kTableThreads) void k_upload_i64(PackI64 pack, int count, int64_t *dst,
+                                                                     const int64_t *off, int32_t S, int32_t *cpre) {
+    for (int i = threadIdx.x; i < count; i += kTableThreads) dst[i] = pack.v[i];
+    if (cpre) {
+        __syncthreads();                       // this block's own stores; earlier words came from earlier launches
+        chunk_prefix_block(off, S, cpre);
+    }
 }
 
 static __global__ void k_fill_u64(uint64_t *p, int64_t n) {
@@ -155,7 +190,8 @@ constexpr int kSolveTable = 4096;   // intervals of the tabulated moment-ratio c
 // it ends in (slot 2 run + 1); a piece that starts with the run takes the first.
 struct RatePiece {
     uint64_t bits;           // sum of code lengths
-    uint32_t u_max, n_clamped, flags, _pad[3];
+    uint64_t n_clamped;      // a run of a very large unit can hold more than 2^32 clamped elements
+    uint32_t u_max, flags, _pad[2];
 };
 static_assert(sizeof(RatePiece) == 32, "two 16-byte stores");
 constexpr int64_t kMaxRuns = 256 * 512;  // most blocks a reducing sweep is split into
@@ -185,7 +221,7 @@ static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t
 static inline bool aligned8(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; }
 
 constexpr int64_t kMaxUnits = 1 << 24;      // rows of a matrix
-constexpr int64_t kMaxSegments = 1 << 20;   // units of a flat bucket
+constexpr int64_t kMaxSegments = 1 << 17;   // units of a flat bucket (293 table launches)
 constexpr int64_t kMaxChunks = 2147483647LL;
 
 // A validated description of how a buffer is cut into units, plus where its tables live.
@@ -195,8 +231,8 @@ struct Geometry {
     int32_t S = 0;
     WsLayout wl{};
     char *ws = nullptr;
-    std::vector<int64_t> table;       // host copy of the unit table (segmented only): S+1 int64 element offsets
-                                      // followed by S+1 int32 chunk prefix sums, as it lies in the workspace
+    const int64_t *host_off = nullptr;   // the caller's S+1 element offsets (segmented only); the chunk prefix sums
+                                         // that follow them in the workspace are derived on the device
     SegParam *params() const { return reinterpret_cast<SegParam *>(ws + wl.params_at); }
     double2 *partials() const { return reinterpret_cast<double2 *>(ws + wl.partials_at); }
     RatePiece *rate_pieces() const { return reinterpret_cast<RatePiece *>(ws + wl.pieces_at); }
@@ -223,7 +259,7 @@ static int geometry_uniform(int64_t rows, int64_t cols, void *ws, size_t ws_byte
 // unit table to upload, no search in the kernels) when the caller's kernels need no table on the device.
 static int geometry_segmented(const int64_t *offsets, int32_t S, void *ws, size_t ws_bytes, Geometry &g,
                               bool single_as_uniform = false) {
-    // the unit table travels through kernel arguments (448 words per launch): keep it to a few thousand launches
+    // the unit table travels through kernel arguments (448 offsets per launch): keep it to a few hundred launches
     if (!offsets || S < 0 || S > kMaxSegments) return S < 0 || !offsets ? GG_ERR_INVALID_ARG : GG_ERR_BAD_SEGMENTS;
     if (offsets[0] < 0) return GG_ERR_BAD_SEGMENTS;
     if (single_as_uniform && S == 1 && offsets[0] == 0) {
@@ -232,18 +268,14 @@ static int geometry_segmented(const int64_t *offsets, int32_t S, void *ws, size_
         return rc == GG_ERR_INVALID_ARG ? GG_ERR_BAD_SEGMENTS : rc;
     }
     g.S = S;
+    g.host_off = offsets;
     const size_t n_off = (size_t)S + 1;
-    g.table.assign(n_off + (n_off + 1) / 2, 0);
-    memcpy(g.table.data(), offsets, n_off * sizeof(int64_t));
-    int32_t *cpre = reinterpret_cast<int32_t *>(g.table.data() + n_off);
     int64_t chunks = 0;
     for (int32_t s = 0; s < S; ++s) {
         if (offsets[s + 1] < offsets[s]) return GG_ERR_BAD_SEGMENTS;
-        cpre[s] = (int32_t)chunks;
         chunks += (offsets[s + 1] - offsets[s] + kChunk - 1) / kChunk;
         if (chunks > kMaxChunks) return GG_ERR_BAD_SEGMENTS;
     }
-    cpre[S] = (int32_t)chunks;
     g.n_chunks = chunks;
     g.n_total = S > 0 ? offsets[S] : 0;   // elements of the buffer the units index into (none without units)
     g.wl = ws_layout(g.n_total, S > 0 ? S : 1);
@@ -257,20 +289,21 @@ static int geometry_segmented(const int64_t *offsets, int32_t S, void *ws, size_
 
 static int check_launch() { return hipGetLastError() == hipSuccess ? GG_OK : GG_ERR_HIP; }
 
-// tables travel as kernel arguments: asynchronous, no pinned staging, no allocation
-static int upload_i64(const std::vector<int64_t> &v, int64_t *dst, hipStream_t st) {
-    for (size_t base = 0; base < v.size(); base += kPackI64) {
-        PackI64 pack;
-        const int count = (int)((v.size() - base) < (size_t)kPackI64 ? v.size() - base : kPackI64);
-        memcpy(pack.v, v.data() + base, (size_t)count * sizeof(int64_t));
-        hipLaunchKernelGGL(k_upload_i64, dim3(1), dim3(256), 0, st, pack, count, dst + base);
-    }
-    return check_launch();
-}
-
+// The unit table travels as kernel arguments, straight from the caller's array: asynchronous, no staging
+// buffer, no allocation on either side.  The last launch also writes the chunk prefix sums behind the offsets.
 static int upload_geometry(const Geometry &g, hipStream_t st) {
     if (g.sv.off == nullptr) return GG_OK;
-    return upload_i64(g.table, const_cast<int64_t *>(g.sv.off), st);   // offsets and chunk prefix in one go
+    int64_t *dst = const_cast<int64_t *>(g.sv.off);
+    const size_t words = (size_t)g.S + 1;
+    for (size_t base = 0; base < words; base += kPackI64) {
+        PackI64 pack;
+        const int count = (int)((words - base) < (size_t)kPackI64 ? words - base : kPackI64);
+        memcpy(pack.v, g.host_off + base, (size_t)count * sizeof(int64_t));
+        const bool last = base + kPackI64 >= words;
+        hipLaunchKernelGGL(k_upload_i64, dim3(1), dim3(kTableThreads), 0, st, pack, count, dst + base, g.sv.off, g.S,
+                           last ? const_cast<int32_t *>(g.sv.cpre) : (int32_t *)nullptr);
+    }
+    return check_launch();
 }
 
 template <typename F>

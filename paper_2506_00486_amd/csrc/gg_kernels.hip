@@ -743,7 +743,7 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
                         // other runs hold pieces of this unit: leave the sums in this run's slot
                         RatePiece *s = a.pieces + 2 * (int64_t)blockIdx.x + (piece_first == first ? 0 : 1);
                         RatePiece v;
-                        v.bits = bits; v.u_max = um; v.n_clamped = ncl; v.flags = fl; v._pad[0] = v._pad[1] = v._pad[2] = 0;
+                        v.bits = bits; v.u_max = um; v.n_clamped = ncl; v.flags = fl; v._pad[0] = v._pad[1] = 0;
                         if (piece_flushed) {
                             v.bits += s->bits; v.u_max = um > s->u_max ? um : s->u_max; v.n_clamped += s->n_clamped; v.flags |= s->flags;
                         }
@@ -937,8 +937,8 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
 // kernels fold them, in run order, into the record.  Units inside a single run are final already.
 // ---------------------------------------------------------------------------------------------
 struct PieceSum {
-    uint64_t bits = 0;
-    uint32_t u_max = 0, n_clamped = 0, flags = 0;
+    uint64_t bits = 0, n_clamped = 0;
+    uint32_t u_max = 0, flags = 0;
     __device__ __forceinline__ void add(const RatePiece &p) {
         bits += p.bits; u_max = p.u_max > u_max ? p.u_max : u_max; n_clamped += p.n_clamped; flags |= p.flags;
     }
@@ -960,8 +960,8 @@ __device__ __forceinline__ void store_piece_sum(gg_rate_t *r, const PieceSum &t)
 // one workgroup per unit
 __global__ __launch_bounds__(kBlock) void k_rate_reduce(SegView sv, const RatePiece *__restrict__ pieces, int32_t cpb,
                                                         gg_rate_t *__restrict__ rate) {
-    __shared__ uint64_t red_bits[kWaves];
-    __shared__ uint32_t red_u[3][kWaves];
+    __shared__ uint64_t red_bits[kWaves], red_ncl[kWaves];
+    __shared__ uint32_t red_u[2][kWaves];
     const int seg = blockIdx.x, tid = threadIdx.x;
     const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
     if (c1 <= c0) return;
@@ -974,8 +974,8 @@ __global__ __launch_bounds__(kBlock) void k_rate_reduce(SegView sv, const RatePi
     for (int64_t run = r0 + tid; run <= r1; run += kBlock) t.add(piece_slot(pieces, run, cpb, c0));
     t.bits = block_reduce(t.bits, OpAdd(), red_bits);
     t.u_max = block_reduce(t.u_max, OpMax(), red_u[0]);
-    t.n_clamped = block_reduce(t.n_clamped, OpAdd(), red_u[1]);
-    t.flags = block_reduce(t.flags, OpOr(), red_u[2]);
+    t.n_clamped = block_reduce(t.n_clamped, OpAdd(), red_ncl);
+    t.flags = block_reduce(t.flags, OpOr(), red_u[1]);
     if (tid == 0) store_piece_sum(r, t);
 }
 
@@ -1001,8 +1001,8 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, 
                                                                     gg_rate_t *__restrict__ rate,
                                                                     const uint64_t *__restrict__ hist, int32_t nbins) {
     __shared__ double red[kFinalizeThreads / 64];
-    __shared__ uint64_t red_bits[kFinalizeThreads / 64];
-    __shared__ uint32_t red_u[3][kFinalizeThreads / 64];
+    __shared__ uint64_t red_bits[kFinalizeThreads / 64], red_ncl[kFinalizeThreads / 64];
+    __shared__ uint32_t red_u[2][kFinalizeThreads / 64];
     const int seg = blockIdx.x, tid = threadIdx.x;
     gg_rate_t *r = rate + seg;
     const uint32_t flags = r->flags;
@@ -1019,7 +1019,7 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, 
         t.n_clamped = wave_reduce(t.n_clamped, OpAdd());
         t.flags = wave_reduce(t.flags, OpOr());
         if ((tid & 63) == 0) {
-            red_bits[tid >> 6] = t.bits; red_u[0][tid >> 6] = t.u_max; red_u[1][tid >> 6] = t.n_clamped; red_u[2][tid >> 6] = t.flags;
+            red_bits[tid >> 6] = t.bits; red_u[0][tid >> 6] = t.u_max; red_ncl[tid >> 6] = t.n_clamped; red_u[1][tid >> 6] = t.flags;
         }
     }
     // bins above the unit's largest symbol are empty (a clamped symbol makes the largest >= nbins - 1): skip them
@@ -1055,7 +1055,7 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, 
             PieceSum t;
             for (int w = 0; w < kFinalizeThreads / 64; ++w) {
                 t.bits += red_bits[w]; t.u_max = red_u[0][w] > t.u_max ? red_u[0][w] : t.u_max;
-                t.n_clamped += red_u[1][w]; t.flags |= red_u[2][w];
+                t.n_clamped += red_ncl[w]; t.flags |= red_u[1][w];
             }
             store_piece_sum(r, t);
         }
@@ -1714,6 +1714,9 @@ static int check_fused(int eg_k, int round_mode, int32_t nbins, uint64_t *hist, 
                        const float *delta_dev, float lambda, float *grad, gg_fit_t *fit, gg_rate_t *rate, int32_t S,
                        int64_t n_total) {
     if (S > 0 && (!fit || !aligned8(fit))) return GG_ERR_INVALID_ARG;
+    // the order and the rounding mode are checked whether or not a rate is asked for: the launchers shift by eg_k
+    if (eg_k < 0 || eg_k > GG_MAX_EG_K) return GG_ERR_INVALID_ARG;
+    if (round_mode != GG_FLOOR && round_mode != GG_NEAREST_EVEN) return GG_ERR_INVALID_ARG;
     if (rate) {
         int rc = check_rate_args(eg_k, round_mode, nbins, hist, symbols);
         if (rc != GG_OK) return rc;

@@ -930,6 +930,7 @@ int gg_eg_encode_segmented(const void *x_dev, int dtype, const int64_t *offsets_
     Geometry g;
     int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
     if (rc != GG_OK) return rc;
+    if (S > 0 && offsets_host[0] != 0) return GG_ERR_BAD_SEGMENTS;   // the stream codes elements 0 .. offsets[S): no gap in front
     const int64_t n = g.n_total;
     if ((rc = check_eg_buffers(n, eg_k, stream_dev, stream_bytes, block_offsets_dev, total_bits_dev)) != GG_OK) return rc;
     if (round_mode != GG_FLOOR && round_mode != GG_NEAREST_EVEN) return GG_ERR_INVALID_ARG;
@@ -996,6 +997,7 @@ int gg_eg_decode_dequant_segmented(const uint8_t *stream_dev, const uint64_t *bl
     Geometry g;
     int rc = geometry_segmented(offsets_host, S, ws_dev, ws_bytes, g);
     if (rc != GG_OK) return rc;
+    if (S > 0 && offsets_host[0] != 0) return GG_ERR_BAD_SEGMENTS;   // as in gg_eg_encode_segmented
     const int64_t n = g.n_total;
     if (n == 0) return GG_OK;
     if (!stream_dev || (reinterpret_cast<uintptr_t>(stream_dev) & 3u) || !block_offsets_dev || !aligned8(block_offsets_dev) ||

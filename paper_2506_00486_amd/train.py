@@ -41,9 +41,10 @@ class EGRate(torch.autograd.Function):
     @staticmethod
     def backward(ctx, grad_out):
         (flat,) = ctx.saved_tensors
-        g = B.gg_rate_grad(flat, ctx.delta, eg_k=ctx.eg_k)
-        g = (g * grad_out).to(ctx.dtype).reshape(ctx.shape)
-        return g, None, None
+        # the incoming scalar (lambda_act of J = D + lambda_act R) goes into the kernel as its `scale`
+        # argument: reading it costs one device-to-host copy of four bytes, no torch arithmetic
+        g = B.gg_rate_grad(flat, ctx.delta, eg_k=ctx.eg_k, scale=float(grad_out))
+        return g.to(ctx.dtype).reshape(ctx.shape), None, None
 
 
 def eg_rate(a: torch.Tensor, delta: float, eg_k: int = 0) -> torch.Tensor:

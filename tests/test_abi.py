@@ -79,7 +79,7 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.gg_fit_segmented(P, 0, None, 3, P, P, ws_bytes, None) == -1
     neg = np.array([-1, 10], dtype=np.int64)
     assert L.gg_fit_segmented(P, 0, neg.ctypes.data, 1, P, P, ws_bytes, None) == -3
-    assert L.gg_fit_segmented(P, 0, ok_off.ctypes.data, (1 << 20) + 1, P, P, ws_bytes, None) == -3   # too many units
+    assert L.gg_fit_segmented(P, 0, ok_off.ctypes.data, (1 << 17) + 1, P, P, ws_bytes, None) == -3   # too many units
     assert L.gg_fit_rows(P, 0, -1, 10, P, None, P, ws_bytes, None) == -1
     for delta in (0.0, -1.0, float("inf"), float("nan")):
         assert L.gg_quantize_rate(P, 0, 100, delta, 0, 0, 0, None, None, P, P, ws_bytes, None) == -1
@@ -105,6 +105,16 @@ def test_invalid_arguments_are_rejected_on_the_host():
                                 ws_bytes, None) == -1                                              # no step source
     assert L.gg_fused_segmented(P, 0, ok_off.ctypes.data, 3, 16.0, None, 0, 0, 0, None, None, 0.0, None, 0, None, P, P,
                                 ws_bytes, None) == -1                                              # no fit output
+    # the order and the rounding mode are checked even when no rate is asked for (penalty-only / fit-only calls)
+    for bad_k, bad_mode in ((-1, 0), (16, 0), (40, 0), (0, 2), (0, -1)):
+        assert L.gg_fused_segmented(P, 0, ok_off.ctypes.data, 3, 16.0, None, bad_k, bad_mode, 0, None, None, 1e-4, P, 0, P,
+                                    None, P, ws_bytes, None) == -1
+        assert L.gg_fused_rows(P, 0, 4, 5, 16.0, None, bad_k, bad_mode, None, 1e-4, P, 0, P, None, None, P, ws_bytes,
+                               None) == -1
+    # the bucket coder covers elements 0 .. offsets[S): a gap in front of the first unit is refused
+    gap_off = np.array([4, 10, 15, 20], dtype=np.int64)
+    assert L.gg_eg_encode_segmented(P, 0, gap_off.ctypes.data, 3, P, 0, 0, P, 1024, P, None, P, ws_bytes, None) == -3
+    assert L.gg_eg_decode_dequant_segmented(P, P, gap_off.ctypes.data, 3, 0, P, P, 0, P, ws_bytes, None) == -3
     assert L.gg_delta_from_fit(P, 3, 0.0, P, None) == -1
     # companions
     assert L.gg_rate_grad(P, 0, 100, 0.0, 0, 100, 1.0, P, 0, None) == -1                           # step 0
