@@ -182,6 +182,23 @@ int gg_fused_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols,
                   gg_fit_t *fit_dev, gg_fit_t *total_fit_dev, gg_rate_t *rate_dev,
                   void *ws_dev, size_t ws_bytes, void *stream);
 
+/* gg_fused_segmented for callers that cannot allocate and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error codes, minus
+ * the workspace: the scratch memory (fit partials, per-run rate slots, the unit table) is a device array of
+ * GG_NOALLOC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends.  The call makes no
+ * hipMalloc / hipFree and no host allocation.  A bucket whose gg_workspace_bytes(offsets_host[S], S, 0) exceeds
+ * GG_NOALLOC_SCRATCH_BYTES is refused with GG_ERR_WORKSPACE before anything is launched (16 MiB serve any bucket
+ * of up to 2^32 elements in up to 4096 units; the 1.5 G-element, 253-unit gradient bucket needs 7.6 MiB).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams, or
+ * different host threads) race on it and give wrong results; order them on one stream.  Nothing in the array
+ * has to be cleared between calls: every slot a kernel reads has been written earlier in the same call. */
+#define GG_NOALLOC_SCRATCH_BYTES (16u << 20)
+int gg_fused_segmented_noalloc(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S,
+                               float delta_div, const float *delta_dev, int eg_k, int round_mode,
+                               int32_t nbins, uint64_t *hist_dev, int32_t *symbols_dev,
+                               float lambda, float *grad_dev, int accumulate,
+                               gg_fit_t *fit_dev, gg_rate_t *rate_dev, void *stream);
+
 /* ---- companions of the pass inside the training algorithms ----------------------------------- */
 /* ACT backward (Sec. 4.2) / dR/dG of Sec. 4.3: gradient of the mean order-k Exp-Golomb length
  * R = (1/n_rate) sum_i [2 log2(u_i + 2^k) - k + 1] through the straight-through quantiser,

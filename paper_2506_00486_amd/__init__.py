@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     FIT_DTYPE, RATE_DTYPE, GGError, lib, lib_path, workspace_bytes, Workspace,
     gg_fit, gg_fit_segmented, gg_fit_rows, gg_quantize_rate, gg_quantize_rate_segmented, gg_quantize_rate_rows,
     gg_delta_from_fit, gg_penalty_grad, gg_penalty_grad_segmented, gg_sample, gg_philox_words, gg_init_alpha,
-    gg_compression_ratio, gg_fused_segmented, gg_fused_rows, fit_records, rate_records,
+    gg_compression_ratio, gg_fused_segmented, gg_fused_segmented_noalloc, gg_fused_rows, fit_records, rate_records,
     gg_rate_grad, gg_gct_update, gg_gct_update_segmented, gg_eg_encode, gg_eg_encode_tensor, gg_eg_encode_segmented, gg_eg_decode, gg_eg_decode_dequant, gg_eg_decode_dequant_segmented, eg_buffers, gg_huffman_mean_bits,
 )
 from .train import gg_init_, eg_rate, EGRate, GCTState  # noqa: F401,E402

@@ -69,6 +69,7 @@ def lib():
             "gg_init_alpha": (f64, [i64, f64, f64]),
             "gg_compression_ratio": (f64, [f64, f64]),
             "gg_fused_segmented": (ci, [vp, ci, vp, i32, f32, vp, ci, ci, i32, vp, vp, f32, vp, ci, vp, vp, vp, sz, vp]),
+            "gg_fused_segmented_noalloc": (ci, [vp, ci, vp, i32, f32, vp, ci, ci, i32, vp, vp, f32, vp, ci, vp, vp, vp]),
             "gg_fused_rows": (ci, [vp, ci, i64, i64, f32, vp, ci, ci, vp, f32, vp, ci, vp, vp, vp, vp, sz, vp]),
             "gg_rate_grad": (ci, [vp, ci, i64, f32, ci, i64, f32, vp, ci, vp]),
             "gg_gct_update": (ci, [vp, vp, vp, i64, f32, f32, f32, f32, ci, i64, ci, vp]),
@@ -281,6 +282,20 @@ def gg_fused_segmented(x: torch.Tensor, offsets, ws: Workspace, delta_div: float
                                     _dev(grad), int(bool(accumulate)), _dev(fit), _dev(rate) if want_rate else None,
                                     ws.ptr, ws.bytes, _stream()), "gg_fused_segmented")
     return dict(fit=fit, rate=rate if want_rate else None, hist=hist, symbols=sym, grad=grad)
+
+
+def gg_fused_segmented_noalloc(x: torch.Tensor, offsets, fit: torch.Tensor, rate: Optional[torch.Tensor] = None,
+                               delta_div: float = 16.0, delta: Optional[torch.Tensor] = None, eg_k: int = 0,
+                               round_mode: int = GG_FLOOR, nbins: int = 0, hist: Optional[torch.Tensor] = None,
+                               symbols: Optional[torch.Tensor] = None, lam: float = 0.0,
+                               grad: Optional[torch.Tensor] = None, accumulate: bool = False) -> None:
+    """The whole pass with the library's own scratch memory.  Every buffer, outputs included, is the caller's:
+    this wrapper creates no tensor, so the call allocates nothing on either side."""
+    off = _offsets(offsets)
+    _check(lib().gg_fused_segmented_noalloc(_dev(x), _dtype_code(x), off.ctypes.data, off.size - 1, _f32(delta_div),
+                                            _dev(delta), eg_k, round_mode, nbins, _dev(hist), _dev(symbols), _f32(lam),
+                                            _dev(grad), int(bool(accumulate)), _dev(fit), _dev(rate), _stream()),
+           "gg_fused_segmented_noalloc")
 
 
 def gg_fused_rows(x: torch.Tensor, rows: int, cols: int, ws: Workspace, delta_div: float = 16.0,

@@ -20,9 +20,9 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
 #include <cmath>
 #include <type_traits>
-#include <vector>
 
 #include "../../include/gg.h"
 #include "gg_device.h"
@@ -1769,6 +1769,50 @@ int gg_fused_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, floa
     }
     return fused_common(g, x_dev, dtype, delta_div, delta_dev, eg_k, round_mode, 0, nullptr, symbols_dev, lambda, grad_dev,
                         accumulate ? 1 : 0, fit_dev, total_fit_dev, rate_dev, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The pass for callers that cannot allocate and have no workspace to hand over (code under graph
+// capture, serving loops, harnesses that forbid hipMalloc): the workspace of gg_fused_segmented lives in a
+// file-scope device array.  Every GPU holds its own copy of the array at its own address; host code never
+// uses the array's name as an address, only what hipGetSymbolAddress returned for the current device.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[GG_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];   // per device, set on the first call made with that device current
+
+// device address of `scratch` on the current device, or nullptr when it cannot be had
+static void *scratch_for_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void *q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) { (void)hipGetLastError(); return nullptr; }
+    g_scratch_ptr[dev].store(q, std::memory_order_release);   // two threads racing here store the same address
+    return q;
+}
+
+int gg_fused_segmented_noalloc(const void *x_dev, int dtype, const int64_t *offsets_host, int32_t S, float delta_div,
+                               const float *delta_dev, int eg_k, int round_mode, int32_t nbins, uint64_t *hist_dev,
+                               int32_t *symbols_dev, float lambda, float *grad_dev, int accumulate, gg_fit_t *fit_dev,
+                               gg_rate_t *rate_dev, void *stream) {
+    if (dtype != GG_F32 && dtype != GG_BF16) return GG_ERR_BAD_DTYPE;
+    // sizes first, against the fixed capacity, before anything touches the device
+    Geometry g;
+    int rc = geometry_segmented(offsets_host, S, reinterpret_cast<void *>(uintptr_t(256)), GG_NOALLOC_SCRATCH_BYTES, g, true);
+    if (rc != GG_OK) return rc;    // GG_ERR_WORKSPACE: the bucket needs more scratch than the library holds
+    if ((rc = check_x(x_dev, dtype, g.n_total)) != GG_OK) return rc;
+    if ((rc = check_fused(eg_k, round_mode, nbins, hist_dev, symbols_dev, delta_div, delta_dev, lambda, grad_dev, fit_dev,
+                          rate_dev, S, g.n_total)) != GG_OK)
+        return rc;
+    void *ws = scratch_for_current_device();
+    if (!ws) return GG_ERR_HIP;
+    if ((rc = geometry_segmented(offsets_host, S, ws, GG_NOALLOC_SCRATCH_BYTES, g, true)) != GG_OK) return rc;
+    // nothing in the workspace has to start at zero: every slot a kernel reads was written earlier in this call
+    return fused_common(g, x_dev, dtype, delta_div, delta_dev, eg_k, round_mode, nbins, hist_dev, symbols_dev, lambda,
+                        grad_dev, accumulate ? 1 : 0, fit_dev, nullptr, rate_dev, (hipStream_t)stream);
 }
 
 }  // extern "C"
