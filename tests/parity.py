@@ -4,6 +4,9 @@ Bars (from the benchmark spec): symbols, histogram counts, bit counts, u_max, fl
 bit-exact.  Moments 1e-5 relative; beta, alpha 1e-4 relative; penalty 1e-5 relative + 1e-7
 absolute; entropy 1e-9 relative (both sides evaluate it in fp64 from identical integer counts).
 """
+import concurrent.futures
+import os
+
 import numpy as np
 
 import gg_inputs
@@ -58,3 +61,13 @@ def check_penalty(gpu_grad: np.ndarray, orc_grad: np.ndarray, where="", penalty:
         scale = np.maximum(scale, np.abs(penalty.astype(np.float64)))
     bad = ~both_inf & ~(np.abs(g - o) <= PEN_ATOL + PEN_RTOL * scale)
     assert not bad.any(), (where, int(bad.sum()), g[bad][:5], o[bad][:5])
+
+
+def oracle_threads(fn, items, workers=None):
+    """fn(item) for every item on a pool of host threads, results in order.  The oracle's routines are plain C
+    without global state, called through ctypes (which releases the interpreter lock for the duration of the
+    call), so whole segments of a large bucket are swept side by side on the host's cores -- none of the
+    threads touches the GPU."""
+    workers = workers or min(16, os.cpu_count() or 1)
+    with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as pool:
+        return list(pool.map(fn, items))

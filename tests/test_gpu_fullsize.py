@@ -1,15 +1,16 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 
-The 1.5-billion-element bucket is too large for the oracle to sweep whole within a test, so the
-oracle recomputes a sample of whole segments (every size class, first/last, the ones next to run
-boundaries) one by one, and properties that hold at any size cover the rest."""
+The oracle sweeps the whole 1.5-billion-element bucket: every segment's fit and rate record is recomputed on the
+host (segments side by side on the host's cores) and compared to the bars of parity.py.  The 7B weight set is
+checked on every element of one full layer and both vocabulary matrices (penalty gradient) and on a sample of
+segments elsewhere; properties that hold at any size cover the rest."""
 import numpy as np
 import pytest
 import torch
 
 import gg_inputs
 import oracle
-from parity import check_fit, check_penalty, check_rate, host_bits
+from parity import check_fit, check_penalty, check_rate, host_bits, oracle_threads
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -51,18 +52,24 @@ def test_gradient_bucket_1p5b_fused_pass(gg):
         assert float(seg.abs().sum()) == pytest.approx(float(frec["sum_abs"][s]), rel=1e-6)
         assert float((seg * seg).sum()) == pytest.approx(float(frec["sum_sq"][s]), rel=1e-6)
 
-    # oracle on sampled whole segments: every tensor kind of layers 0, 13, 27 (which straddle run boundaries
-    # differently), all 56 norm vectors, and the 233M-element embedding
-    sample = [s for s, seg in enumerate(layout) if seg.name.split(".")[0] in ("l0", "l13", "l27")]
-    sample += [s for s, seg in enumerate(layout) if "norm" in seg.name]
-    sample = sorted(set(sample)) + [S - 1]
-    for s in sample:
+    # the oracle on EVERY segment: moments, shape, scale, bit count, u_max, fl_bits, flags of the timed configuration
+    print("host copy of the bucket", flush=True)
+    host = host_bits(flat)
+
+    def one(s):
         lo, hi = int(off[s]), int(off[s + 1])
-        print(f"oracle on {layout[s].name} ({hi - lo} elements)", flush=True)
-        hb = host_bits(flat[lo:hi])
-        check_fit(frec[s], oracle.fit(hb), layout[s].name)
-        r, _, _ = oracle.quantize_rate(hb, float(rrec[s]["delta"]))
+        f = oracle.fit(host[lo:hi])
+        r, _, _ = oracle.quantize_rate(host[lo:hi], float(rrec[s]["delta"]))
+        return f, r
+
+    order = sorted(range(S), key=lambda s: -int(sizes[s]))         # largest first: the embedding bounds the wall time
+    print(f"oracle on all {S} segments ({n} elements)", flush=True)
+    results = dict(zip(order, oracle_threads(one, order)))
+    for s in range(S):
+        f, r = results[s]
+        check_fit(frec[s], f, layout[s].name)
         check_rate(rrec[s], r, layout[s].name, entropy=False)
+    del host
 
     # same call again: bit-identical records (fixed reduction order, integer atomics)
     res2 = gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, eg_k=0)
@@ -135,16 +142,28 @@ def test_weights_7b_fit_penalty_accumulate_and_resample(gg):
     assert np.array_equal(frec["n"], np.diff(off).astype(np.uint64)) and not frec["flags"].any()
     big = np.diff(off) >= 100_000
     assert np.all(np.abs(frec["beta"][big] - beta[big]) < 0.03)
+    # fits of a sample of segments across the set, by the oracle
     for s in (0, 1, 7, 8, 145, 288, 289):
+        check_fit(frec[s], oracle.fit(host_bits(flat[int(off[s]):int(off[s + 1])])), layout[s].name)
+    # the penalty update on EVERY element of one full layer (9 tensors) and of both vocabulary matrices
+    # (about 464 M elements): slices of 4 M elements side by side on the host's cores
+    for s in list(range(9)) + [S - 2, S - 1]:
         lo, hi = int(off[s]), int(off[s + 1])
-        m = min(hi - lo, 3_000_000)
-        print(f"oracle on {layout[s].name} (first {m} of {hi - lo})", flush=True)
-        hb_full = host_bits(flat[lo:hi])
-        check_fit(frec[s], oracle.fit(hb_full), layout[s].name)
-        base = np.full(m, 0.25, dtype=np.float32)
-        pen = oracle.penalty_grad(hb_full[:m], frec[s]["alpha"], frec[s]["beta"], 1e-4)
-        og = oracle.penalty_grad(hb_full[:m], frec[s]["alpha"], frec[s]["beta"], 1e-4, grad=base, accumulate=True)
-        check_penalty(res["grad"][lo:lo + m].cpu().numpy(), og, layout[s].name, penalty=pen)
+        print(f"oracle penalty on {layout[s].name} ({hi - lo} elements)", flush=True)
+        hb = host_bits(flat[lo:hi])
+        got = res["grad"][lo:hi].cpu().numpy()
+        check_fit(frec[s], oracle.fit(hb), layout[s].name)
+        a_s, b_s = frec[s]["alpha"], frec[s]["beta"]
+
+        def piece(p0, hb=hb, got=got, a_s=a_s, b_s=b_s, name=layout[s].name):
+            p1 = min(p0 + (1 << 22), hb.size)
+            base = np.full(p1 - p0, 0.25, dtype=np.float32)
+            pen = oracle.penalty_grad(hb[p0:p1], a_s, b_s, 1e-4)
+            og = oracle.penalty_grad(hb[p0:p1], a_s, b_s, 1e-4, grad=base, accumulate=True)
+            check_penalty(got[p0:p1], og, f"{name}[{p0}:{p1}]", penalty=pen)
+            return p1 - p0
+
+        assert sum(oracle_threads(piece, range(0, hb.size, 1 << 22))) == hi - lo
     del grad, res
     # re-sample layer 0 (9 tensors) at the GG-init scale of its fan-in, shape = the fitted one
     fan_in = {"q": 4096, "k": 4096, "v": 4096, "o": 4096, "gate": 4096, "up": 4096, "down": 11008}
