@@ -188,7 +188,7 @@ int gg_fused_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols,
  * GG_NOALLOC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends.  The call makes no
  * hipMalloc / hipFree and no host allocation.  A bucket whose gg_workspace_bytes(offsets_host[S], S, 0) exceeds
  * GG_NOALLOC_SCRATCH_BYTES is refused with GG_ERR_WORKSPACE before anything is launched (16 MiB serve any bucket
- * of up to 2^32 elements in up to 4096 units; the 1.5 G-element, 253-unit gradient bucket needs 7.6 MiB).
+ * of up to 2^31 elements in up to 4096 units; the 1.5 G-element, 253-unit gradient bucket needs 7.2 MiB).
  * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams, or
  * different host threads) race on it and give wrong results; order them on one stream.  Nothing in the array
  * has to be cleared between calls: every slot a kernel reads has been written earlier in the same call. */

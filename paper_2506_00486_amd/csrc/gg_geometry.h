@@ -196,6 +196,17 @@ struct RatePiece {
 static_assert(sizeof(RatePiece) == 32, "two 16-byte stores");
 constexpr int64_t kMaxRuns = 256 * 512;  // most blocks a reducing sweep is split into
 
+// A rate sweep that also writes a stream (penalty gradient, symbols) runs as short blocks, kStreamParts per
+// chunk, like the element-wise sweeps; every such block leaves its sums in a slot of its own (block index =
+// chunk * kStreamParts + part), and one workgroup per unit folds the unit's slots, which are consecutive.
+struct PartSlot { uint32_t bits, u_max, flags, _pad; };
+static_assert(sizeof(PartSlot) == 16, "one 16-byte store");
+#ifndef GG_STREAM_PARTS
+#define GG_STREAM_PARTS 4                // 4096 elements per block = 256 lanes x 4 loads x 4 elements
+#endif
+constexpr int kStreamParts = GG_STREAM_PARTS;
+static_assert(kStreamParts * sizeof(PartSlot) <= 2 * sizeof(RatePiece), "the slot area is sized as two run slots per chunk");
+
 struct WsLayout {
     size_t off_bytes, params_bytes, partials_bytes, pieces_bytes, total;   // off_bytes: offsets + chunk prefix
     size_t off_at, params_at, partials_at, pieces_at;
@@ -211,7 +222,7 @@ static WsLayout ws_layout(int64_t n_total, int64_t n_units) {
     w.off_at = 256;
     w.params_at = w.off_at + w.off_bytes;
     w.partials_at = w.params_at + w.params_bytes;
-    w.pieces_bytes = align_up((size_t)(max_chunks < (size_t)kMaxRuns ? max_chunks : (size_t)kMaxRuns) * 2 * sizeof(RatePiece), 256);   // runs <= chunks
+    w.pieces_bytes = align_up(max_chunks * 2 * sizeof(RatePiece), 256);   // runs <= chunks; or kStreamParts part slots per chunk
     w.pieces_at = w.partials_at + w.partials_bytes;
     w.total = w.pieces_at + w.pieces_bytes;
     return w;
@@ -236,6 +247,7 @@ struct Geometry {
     SegParam *params() const { return reinterpret_cast<SegParam *>(ws + wl.params_at); }
     double2 *partials() const { return reinterpret_cast<double2 *>(ws + wl.partials_at); }
     RatePiece *rate_pieces() const { return reinterpret_cast<RatePiece *>(ws + wl.pieces_at); }
+    PartSlot *part_slots() const { return reinterpret_cast<PartSlot *>(ws + wl.pieces_at); }
 };
 
 static int geometry_uniform(int64_t rows, int64_t cols, void *ws, size_t ws_bytes, bool need_ws, Geometry &g) {

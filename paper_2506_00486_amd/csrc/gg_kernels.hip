@@ -449,6 +449,7 @@ struct QuantArgs {
     // FIT
     double2 *partials;
     RatePiece *pieces;        // RATE: per-run slots for units that several runs share
+    PartSlot *part_slots;     // RATE with a written stream: one slot per block (k_quant_parts)
     // work split
     int64_t n_chunks;
     int32_t chunks_per_block;
@@ -818,6 +819,51 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
     flush(true);
 }
 
+// The rate sweep that also writes a stream (penalty gradient and / or symbols; no histogram) as short blocks:
+// a stream that writes as much as it reads moves fastest in blocks of 16 KiB, all loads of a block issued at
+// once (a plain copy: 5.8 TB/s against 5.1-5.4 TB/s for 64 KiB per block or resident runs on MI355X).  Block
+// chunk * parts + part takes part `part` of chunk `chunk` and leaves its sums in slot [blockIdx.x].
+template <typename T, int MODE, bool PEN, bool SYM>
+__global__ __launch_bounds__(kBlock) void k_quant_parts(SegView sv, const T *__restrict__ x, QuantArgs a) {
+    __shared__ uint32_t red[3][kWaves];
+    const int tid = threadIdx.x;
+    const int64_t chunk = blockIdx.x / a.parts;
+    if (chunk >= a.n_chunks) return;
+    const ChunkLoc L = locate(sv, chunk);
+    const SegParam P = a.params ? a.params[L.seg] : a.single;
+    const bool rate_live = !(P.flags & kSkipRate);
+    int64_t start; int len;
+    const bool any = chunk_part(L.start, L.len, (int)(blockIdx.x - chunk * a.parts), a.parts, start, len);
+    uint32_t lsum = 0, um = 0, nan = 0;
+    if (any) {                                 // uniform over the block
+        QuantBody<MODE, true, PEN, SYM> body;
+        body.eg_add = a.eg_add;
+        body.symbols = a.symbols; body.grad = a.grad; body.accumulate = a.accumulate;
+        body.lds_hist = nullptr; body.ghist = nullptr; body.last_bin = 0; body.lbins = 0; body.hist_live = false;
+        body.inv_delta = P.inv_delta; body.inv_alpha = P.inv_alpha; body.beta_m1 = P.beta_m1;
+        body.pen_coef = P.pen_coef; body.pen_live = !(P.flags & kPenZero);
+        if constexpr (sizeof(T) == 2) process_chunk<ElemBf16x4, 4>(x, start, len, body);
+        else process_chunk<Elem<T>, 4>(x, start, len, body);
+        lsum = wave_reduce(body.clz_sum, OpAdd());       // at most 4096 x 32: fits 32 bits
+        um = wave_reduce(body.u_max, OpMax());
+        nan = wave_reduce((uint32_t)body.nan_seen, OpOr());
+    }
+    if ((tid & 63) == 0) { red[0][tid >> 6] = lsum; red[1][tid >> 6] = um; red[2][tid >> 6] = nan; }
+    __syncthreads();
+    if (tid == 0) {
+        PartSlot v{0u, 0u, 0u, 0u};
+        if (any && rate_live) {
+            uint32_t l = 0, m = 0, f = 0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) { l += red[0][w]; m = red[1][w] > m ? red[1][w] : m; f |= red[2][w]; }
+            v.bits = (uint32_t)len * a.eg_const - 2u * l;
+            v.u_max = m;
+            v.flags = (f ? GG_F_NONFINITE : 0u) | (m >= 2147483647u ? GG_F_SATURATED : 0u);
+        }
+        a.part_slots[blockIdx.x] = v;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // wave-per-row pass.  For matrices whose rows fit a few cache lines per lane (activations: one row
 // per token) a wave owns a row outright: it sums the moments, solves the fit, derives the row's
@@ -993,6 +1039,65 @@ __global__ __launch_bounds__(64) void k_rate_reduce_lanes(SegView sv, const Rate
     PieceSum t;
     for (int64_t run = r0; run <= r1; ++run) t.add(piece_slot(pieces, run, cpb, c0));
     store_piece_sum(r, t);
+}
+
+// the same for the slots of k_quant_parts: the blocks of a unit are consecutive, parts per chunk
+template <int THREADS>
+__device__ __forceinline__ void fold_part_slots(const PartSlot *__restrict__ slots, int64_t i0, int64_t i1, int t, PieceSum &acc) {
+    const gg_u4 *__restrict__ p = reinterpret_cast<const gg_u4 *>(slots);
+    for (int64_t i = i0 + t; i < i1; i += 8 * THREADS) {          // eight 16-byte loads in flight per thread
+        gg_u4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int64_t j = i + (int64_t)k * THREADS;
+            v[k] = j < i1 ? p[j] : gg_u4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { acc.bits += v[k].x; acc.u_max = v[k].y > acc.u_max ? v[k].y : acc.u_max; acc.flags |= v[k].z; }
+    }
+}
+
+constexpr int kPartReduceThreads = 1024;
+__global__ __launch_bounds__(kPartReduceThreads) void k_rate_reduce_parts(SegView sv, const PartSlot *__restrict__ slots, int32_t parts,
+                                                                          gg_rate_t *__restrict__ rate) {
+    __shared__ uint64_t red_bits[kPartReduceThreads / 64];
+    __shared__ uint32_t red_u[2][kPartReduceThreads / 64];
+    const int seg = blockIdx.x, tid = threadIdx.x;
+    const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
+    if (c1 <= c0) return;
+    gg_rate_t *r = rate + seg;
+    if (r->flags & (GG_F_DEGENERATE | GG_F_EMPTY)) return;       // no rate was evaluated
+    PieceSum t;
+    fold_part_slots<kPartReduceThreads>(slots, c0 * parts, c1 * parts, tid, t);
+    t.bits = wave_reduce(t.bits, OpAdd());
+    t.u_max = wave_reduce(t.u_max, OpMax());
+    t.flags = wave_reduce(t.flags, OpOr());
+    if ((tid & 63) == 0) { red_bits[tid >> 6] = t.bits; red_u[0][tid >> 6] = t.u_max; red_u[1][tid >> 6] = t.flags; }
+    __syncthreads();
+    if (tid == 0) {
+        PieceSum all;
+        for (int w = 0; w < kPartReduceThreads / 64; ++w) {
+            all.bits += red_bits[w]; all.u_max = red_u[0][w] > all.u_max ? red_u[0][w] : all.u_max; all.flags |= red_u[1][w];
+        }
+        store_piece_sum(r, all);
+    }
+}
+
+// one wave per unit (many small units)
+__global__ __launch_bounds__(kBlock) void k_rate_reduce_parts_waves(SegView sv, const PartSlot *__restrict__ slots, int32_t parts,
+                                                                    gg_rate_t *__restrict__ rate) {
+    const int seg = blockIdx.x * kWaves + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (seg >= sv.S) return;
+    const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
+    if (c1 <= c0) return;
+    gg_rate_t *r = rate + seg;
+    if (r->flags & (GG_F_DEGENERATE | GG_F_EMPTY)) return;
+    PieceSum t;
+    fold_part_slots<64>(slots, c0 * parts, c1 * parts, lane, t);
+    t.bits = wave_reduce(t.bits, OpAdd());
+    t.u_max = wave_reduce(t.u_max, OpMax());
+    t.flags = wave_reduce(t.flags, OpOr());
+    if (lane == 0) store_piece_sum(r, t);
 }
 
 // With a histogram: the same folding, then the entropy of the unit's bins, one workgroup per unit.
@@ -1243,6 +1348,7 @@ struct QuantOpts {
     bool fit_too = false;              // one-sweep mode: the rate sweep also writes moment partials
     bool hist_cleared = false;         // the kernel that prepared the units has cleared the histograms already
     int32_t chunks_per_block_out = 1;  // the run length the sweep used (the fit finalisation needs it)
+    int32_t parts_out = 0;             // > 0: the sweep ran as short blocks and left one slot per block (k_quant_parts)
 };
 
 #ifndef GG_PEN_PARTS
@@ -1270,6 +1376,18 @@ static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hip
     // that reduce keep one run per resident block (their per-block epilogue costs more than the balance gains).
     RunSplit rs;
     a.parts = 1;
+    if constexpr (RATE && !FIT && (PEN || EXTRA)) {
+        if (lds == 0) {              // rate sums and a written stream, no histogram: short blocks, one slot each
+            a.parts = kStreamParts;
+            a.part_slots = g.ws ? g.part_slots() : nullptr;
+            if (!a.part_slots) return GG_ERR_WORKSPACE;
+            if (g.n_chunks > 2147483647LL / a.parts) return GG_ERR_INVALID_ARG;
+            o.parts_out = a.parts;
+            hipLaunchKernelGGL((k_quant_parts<T, MODE, PEN, EXTRA>), dim3((unsigned)(g.n_chunks * a.parts)), dim3(kBlock), 0, st,
+                               g.sv, static_cast<const T *>(x), a);
+            return check_launch();
+        }
+    }
     if (!RATE && !FIT) {
         a.parts = GG_PEN_PARTS;      // 4096 elements per block = 256 lanes x 4 loads x 4 elements
         if (g.n_chunks > 2147483647LL / a.parts) return GG_ERR_INVALID_ARG;
@@ -1323,11 +1441,20 @@ static int launch_quant(const Geometry &g, const void *x, int dtype, QuantOpts &
 
 // after a rate sweep: fold the run slots of shared units into their records; with a histogram also the entropy
 static int launch_rate_finalize(const Geometry &g, gg_rate_t *rate, const uint64_t *hist, int32_t nbins, int32_t cpb,
-                                hipStream_t st) {
+                                int32_t parts, hipStream_t st) {
     if (g.S == 0 || g.n_chunks == 0) return GG_OK;
     if (hist) {
         hipLaunchKernelGGL(k_rate_finalize, dim3((unsigned)g.S), dim3(kFinalizeThreads), 0, st, g.sv, g.rate_pieces(), cpb, rate,
                            hist, nbins);
+        return check_launch();
+    }
+    if (parts > 0) {                                     // short blocks: every unit's record comes from its slots
+        if (g.S >= kManyUnits)
+            hipLaunchKernelGGL(k_rate_reduce_parts_waves, dim3((unsigned)((g.S + kWaves - 1) / kWaves)), dim3(kBlock), 0, st, g.sv,
+                               g.part_slots(), parts, rate);
+        else
+            hipLaunchKernelGGL(k_rate_reduce_parts, dim3((unsigned)g.S), dim3(kPartReduceThreads), 0, st, g.sv, g.part_slots(),
+                               parts, rate);
         return check_launch();
     }
     if (g.n_chunks <= cpb) return GG_OK;                 // a single run: nothing is shared
@@ -1430,7 +1557,7 @@ static int run_second_sweep(const Geometry &g, const void *x, int dtype, QuantOp
     if (o.rate || o.pen) {
         if ((rc = launch_quant(g, x, dtype, o, st)) != GG_OK) return rc;
     }
-    if (o.rate) return launch_rate_finalize(g, o.rate_out, o.hist, o.nbins, o.chunks_per_block_out, st);
+    if (o.rate) return launch_rate_finalize(g, o.rate_out, o.hist, o.nbins, o.chunks_per_block_out, o.parts_out, st);
     return GG_OK;
 }
 

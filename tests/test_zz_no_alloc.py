@@ -74,7 +74,7 @@ def test_noalloc_rejects_what_does_not_fit_and_bad_arguments():
     assert gg.workspace_bytes(1 << 36, 1) > cap
     assert L.gg_fused_segmented_noalloc(P, 0, big.ctypes.data, 1, 16.0, None, 0, 0, 0, None, None, 0.0, None, 0, P, P, None) == -4
     # the documented capacity holds
-    assert gg.workspace_bytes(1 << 32, 4096) <= cap
+    assert gg.workspace_bytes(1 << 31, 4096) <= cap
     ok = np.array([0, 10, 20], dtype=np.int64)
     assert L.gg_fused_segmented_noalloc(P, 7, ok.ctypes.data, 2, 16.0, None, 0, 0, 0, None, None, 0.0, None, 0, P, P, None) == -2
     assert L.gg_fused_segmented_noalloc(None, 0, ok.ctypes.data, 2, 16.0, None, 0, 0, 0, None, None, 0.0, None, 0, P, P, None) == -1
