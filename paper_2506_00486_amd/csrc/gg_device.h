@@ -207,6 +207,82 @@ __device__ __forceinline__ void process_chunk(const typename E::type *__restrict
     if (tid < len - done) body.one(E::load1(x + start + done + tid), start + done + tid);
 }
 
+// The same walk in two steps, with the loads of the next group of U vectors issued before the current group is
+// worked on (two register sets taking turns): for bodies whose work per element is long compared with what the
+// resident waves can hide -- a kernel limited to few waves per compute unit by its LDS -- so that a lane always
+// has loads in flight.  begin() issues the first group's loads and returns at once, so that the caller can do
+// other work (clear LDS, ...) while they travel; peek() hands the first group's elements to a functor without
+// consuming them (a look at the data before the body is chosen); run() visits every element exactly once.
+template <typename E, int U, int GROUP = kBlock>
+struct AheadWalk {
+    using T = typename E::type;
+    static constexpr int W = E::W;
+    const T *x;
+    const T *p;
+    int64_t start, vstart;
+    int len, head, nvec, tid;
+    typename E::raw cur[U];
+    bool have;
+
+    __device__ __forceinline__ void begin(const T *__restrict__ x_, int64_t start_, int len_) {
+        x = x_; start = start_; len = len_;
+        tid = threadIdx.x & (GROUP - 1);
+        head = (int)((W - (int)(start % W)) % W);
+        if (head > len) head = len;
+        vstart = start + head;
+        nvec = (len - head) / W;
+        p = x + vstart;
+        have = tid + (U - 1) * GROUP < nvec;
+        if (have) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) cur[u] = E::loadv(p + (int64_t)(tid + u * GROUP) * W);
+        }
+    }
+
+    // f(v) for the W elements of the first loaded vector of this lane, if it has one
+    template <typename F>
+    __device__ __forceinline__ void peek(F &&f) const {
+        if (have) {
+            float v[W];
+            E::unpack(cur[0], v);
+            f(v);
+        }
+    }
+
+    template <typename Body>
+    __device__ __forceinline__ void run(Body &body) {
+        if (tid < head) body.one(E::load1(x + start + tid), start + tid);
+        int i = tid;
+        typename E::raw nxt[U];
+        while (have) {
+            const int j = i + U * GROUP;
+            const bool more = j + (U - 1) * GROUP < nvec;
+            if (more) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) nxt[u] = E::loadv(p + (int64_t)(j + u * GROUP) * W);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float v[W];
+                E::unpack(cur[u], v);
+                body.vec(v, vstart + (int64_t)(i + u * GROUP) * W);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+            i = j;
+            have = more;
+        }
+        for (; i < nvec; i += GROUP) {
+            typename E::raw r = E::loadv(p + (int64_t)i * W);
+            float v[W];
+            E::unpack(r, v);
+            body.vec(v, vstart + (int64_t)i * W);
+        }
+        const int done = head + nvec * W;
+        if (tid < len - done) body.one(E::load1(x + start + done + tid), start + done + tid);
+    }
+};
+
 // ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): ten rounds of multiply-hi/lo mixing, key bumped by the
 // Weyl constants after each round.

@@ -122,7 +122,8 @@ struct SegParam {
     float inv_alpha;
     float beta_m1;
     uint32_t flags;
-    uint32_t _pad[2];
+    uint32_t ticket;   // how many workgroups of the unit's finalisation have delivered their part (starts at 0)
+    uint32_t _pad;
 };
 
 // ---------------------------------------------------------------------------------------------

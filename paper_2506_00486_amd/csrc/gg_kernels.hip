@@ -44,6 +44,8 @@
 
 namespace gg {
 
+constexpr int kMaxDevices = 64;   // devices of one process the per-device caches below have room for
+
 // ---------------------------------------------------------------------------------------------
 // sweep 1: moments
 // ---------------------------------------------------------------------------------------------
@@ -283,7 +285,7 @@ struct PrepArgs {
 
 __device__ __forceinline__ void prepare_unit(const PrepArgs &a, int seg, int64_t n, float alpha, float beta) {
     SegParam p;
-    p.flags = 0; p._pad[0] = p._pad[1] = 0;
+    p.flags = 0; p.ticket = 0; p._pad = 0;
     float delta;
     if (a.delta_div > 0.f) delta = (float)((double)alpha / (double)a.delta_div);  // == one fp32 division
     else delta = a.delta_dev ? a.delta_dev[seg] : a.delta_scalar;
@@ -443,6 +445,8 @@ struct QuantArgs {
     uint64_t *hist;           // S * nbins
     int32_t nbins;
     int32_t lbins;            // bins privatised in LDS
+    int32_t cbins;            // k_hist: bins of the column layout (each in kHistCopies copies)
+    int32_t lds_words;        // k_hist: 32-bit counters in LDS, either layout with its spare counter(s)
     // PEN
     float *grad;
     int accumulate;
@@ -865,6 +869,305 @@ __global__ __launch_bounds__(kBlock) void k_quant_parts(SegView sv, const T *__r
 }
 
 // ---------------------------------------------------------------------------------------------
+// Rate sweep with a histogram and nothing else to write (the entropy / Huffman statistics of a tensor): one
+// workgroup of 1024 threads per compute unit shares ONE set of block-private counters -- 128 KiB of the 160 KiB
+// of LDS -- so that sixteen waves hide each other's loads and the counters are merged into the unit's histogram
+// once per compute unit instead of once per small block.
+//
+// What LDS increments cost here is bank conflicts, not their number: scattered over plain bins a wave's 64
+// increments take about 21 cycles, in distinct banks they are free next to the load stream.  So the counters
+// have two layouts, chosen per piece (block, unit) from 4096 of its elements:
+//   columns  bins 0 .. 1022, each kept in 32 copies, copy (lane mod 32): a half-wave never meets in a bank.
+//            For quantised GG data nearly every symbol is below 1023 (the shape makes the distribution peaked);
+//            the few beyond go to the unit's histogram one by one.
+//   plain    up to 32768 bins, one copy: any distribution.
+// The layout changes the speed only: both count every element exactly.
+//
+// The common path spends 8 vector instructions and one LDS increment per element, without a branch: with r = -q
+// (an integer-valued float) the symbol is u = 2|r| - [r < 0] = |2r + 1/2| - 1/2, and f = |2r + 1/2| + (C - 1/2)
+// with C = 1.5 * 2^e is exact while it stays below 2^(e+1) and carries u, times the byte stride of a bin, in its
+// low mantissa bits (e = 21: stride 4, e = 16: stride 128).  Codes are clamped to the first counter the layout
+// does not have (a spare one), and the largest code of a group of elements tells whether any of them needs the
+// exact integer route of the general sweep (NaN, symbols past the counters or past the histogram): only then
+// is the group looked at again.  Bit count and largest symbol of the elements counted in the block's counters
+// are derived from the counters when they are merged -- a bin IS its symbol.
+// ---------------------------------------------------------------------------------------------
+#ifndef GG_HIST_THREADS
+#define GG_HIST_THREADS 1024
+#endif
+constexpr int kHistThreads = GG_HIST_THREADS;
+constexpr int kHistWaves = kHistThreads / 64;
+constexpr int kHistMaxLdsBins = 32768;              // plain layout: private bins (128 KiB)
+#ifndef GG_HIST_COPIES
+#define GG_HIST_COPIES 32
+#endif
+constexpr int kHistCopies = GG_HIST_COPIES;         // column layout: copies of a bin, one per bank
+constexpr int kHistColumnBins = kHistMaxLdsBins / kHistCopies - 1;   // and its bins (one more column is the spare counter)
+#ifndef GG_HIST_RARE_MAX
+#define GG_HIST_RARE_MAX 8
+#endif
+constexpr uint32_t kHistSampleRareMax = GG_HIST_RARE_MAX;   // symbols past the columns among them (of 4096) that still choose the columns
+
+typedef __attribute__((address_space(3))) uint32_t lds_u32_t;
+// LDS byte address of a __shared__ object, and an increment of the 32-bit counter at an LDS byte address
+__device__ __forceinline__ uint32_t lds_address(uint32_t *p) { return (uint32_t)(uintptr_t)(lds_u32_t *)p; }
+__device__ __forceinline__ void lds_increment(uint32_t byte_address) {
+    __hip_atomic_fetch_add((lds_u32_t *)(uintptr_t)byte_address, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+#ifndef GG_HIST_RUNS_PER_BLOCK
+#define GG_HIST_RUNS_PER_BLOCK 1
+#endif
+#ifndef GG_HIST_U
+#define GG_HIST_U 4       // 16-byte loads a lane keeps in flight
+#endif
+
+// STRIDE = bytes from one bin to the next: 4 (plain) or 4 * kHistCopies (columns)
+template <bool NEAREST, int STRIDE>
+struct HistBody {
+    static constexpr int kExp = 23 - (STRIDE == 4 ? 2 : (STRIDE == 128 ? 7 : 8));     // one unit in the last place of C is 1 / STRIDE
+    static_assert(STRIDE == 4 || STRIDE == 128 || STRIDE == 256, "plain bins, or 32 / 64 copies");
+    static constexpr uint32_t kMagicBits = ((uint32_t)(kExp + 127) << 23) | 0x400000u;  // C = 1.5 * 2^kExp
+    float inv_delta, magic_m_half;   // C - 1/2
+    uint32_t lim_bits;               // kMagicBits + STRIDE * fast_lim: codes from here on are not counted in the block's counters
+    uint32_t lds_bins;               // LDS byte address of this lane's copy of bin 0
+    uint64_t *ghist;
+    uint32_t last_bin, fast_lim, eg_add, eg_const;
+    // what does not come out of the block's counters
+    uint64_t rare_bits = 0;
+    uint32_t rare_umax = 0, n_clamped = 0, n_last = 0;
+    bool nan_seen = false;
+
+    __device__ __forceinline__ void setup(float inv_delta_, uint32_t lds_base, uint32_t fast_lim_) {
+        inv_delta = inv_delta_; fast_lim = fast_lim_;
+        magic_m_half = __uint_as_float(kMagicBits) - 0.5f;
+        lim_bits = kMagicBits + (uint32_t)STRIDE * fast_lim_;
+        lds_bins = lds_base + (STRIDE == 4 ? 0u : 4u * (threadIdx.x & (uint32_t)(STRIDE / 4 - 1)));
+    }
+
+    // C + u as a bit pattern: kMagicBits + STRIDE u while exact, larger (as an unsigned number) for larger symbols and NaN
+    __device__ __forceinline__ uint32_t code(float x, float &t, float &r) const {
+        t = x * inv_delta;                                            // the one fp32 rounding of the quantiser
+        r = NEAREST ? rintf(-t) : ceilf(-t);
+        const float g = __builtin_fmaf(r, 2.0f, 0.5f);                // exact while |r| < 2^22
+        return __float_as_uint(fabsf(g) + magic_m_half);              // exact below 2^(kExp+1), monotone beyond
+    }
+
+    // the exact integer route of the general sweep, for an element the block's counters do not take
+    __device__ __forceinline__ void rare(float t, float r) {
+        nan_seen |= (t != t);
+        int32_t m = cvt_i32_sat(r);                                   // NaN -> 0, saturating
+        m = m < -kQLimI ? -kQLimI : (m > kQLimI ? kQLimI : m);
+        const uint32_t u = ((uint32_t)m << 1) ^ (uint32_t)(m >> 31);
+        if (u < fast_lim) { lds_increment(lds_bins + (uint32_t)STRIDE * u); return; }   // a NaN's symbol 0: counted and priced through its bin
+        rare_bits += eg_const - 2u * (uint32_t)__builtin_clz(u + eg_add);
+        rare_umax = u > rare_umax ? u : rare_umax;
+        if (u >= last_bin) { n_last += 1u; n_clamped += u > last_bin ? 1u : 0u; }
+        else atomicAdd(reinterpret_cast<unsigned long long *>(&ghist[u]), 1ull);   // fast_lim <= u < last_bin
+    }
+
+    template <int W>
+    __device__ __forceinline__ void vec(const float (&v)[W], int64_t) {
+        uint32_t top = 0;
+        const uint32_t base = lds_bins - kMagicBits;
+#pragma unroll
+        for (int j = 0; j < W; ++j) {
+            float t, r;
+            const uint32_t b = code(v[j], t, r);
+            top = b > top ? b : top;
+            lds_increment((b < lim_bits ? b : lim_bits) + base);      // its bin, or the spare counter
+        }
+        if (top >= lim_bits) {
+#pragma unroll
+            for (int j = 0; j < W; ++j) {
+                float t, r;
+                if (code(v[j], t, r) >= lim_bits) rare(t, r);
+            }
+        }
+    }
+    __device__ __forceinline__ void one(float v, int64_t) {
+        float t, r;
+        const uint32_t b = code(v, t, r);
+        if (b < lim_bits) lds_increment(b + (lds_bins - kMagicBits));
+        else rare(t, r);
+    }
+};
+
+struct HistPiece {           // what a block knows about the piece it is on (uniform over the block)
+    const SegParam *P;
+    uint64_t *ghist;
+    uint32_t last_bin;
+};
+
+// one sub-piece [e0, e) in layout STRIDE: count, then merge the block's counters into the unit's histogram.
+// Leaves the piece's sums in red64 / red (combined by thread 0 of the caller).
+template <typename T> using HistWalk = AheadWalk<Elem<T>, GG_HIST_U, kHistThreads>;
+
+template <typename T, bool NEAREST, int STRIDE>
+__device__ __forceinline__ void hist_sub_piece(HistWalk<T> &walk, const QuantArgs &a, const HistPiece &pc,
+                                               uint32_t *lds_hist, uint32_t fast_lim, uint64_t *red64, uint32_t (*red)[kHistWaves]) {
+    const int tid = threadIdx.x;
+    HistBody<NEAREST, STRIDE> body;
+    body.setup(pc.P->inv_delta, lds_address(lds_hist), fast_lim);
+    body.ghist = pc.ghist; body.last_bin = pc.last_bin; body.eg_add = a.eg_add; body.eg_const = a.eg_const;
+    walk.run(body);
+    __syncthreads();                                  // every increment of this piece is in the counters
+    // merge: a thread's bins, ascending; their elements' code lengths and the largest symbol come with them
+    uint64_t bits = body.rare_bits;
+    uint32_t um = body.rare_umax;
+    for (uint32_t b = tid; b < fast_lim; b += kHistThreads) {
+        uint32_t c;
+        if constexpr (STRIDE == 4) {
+            c = lds_hist[b];
+            if (c) lds_hist[b] = 0;
+        } else {                                      // the copies of bin b, starting at copy b so that the lanes of a wave stay in distinct banks
+            constexpr int kCopies = STRIDE / 4;
+            uint32_t *row = lds_hist + b * kCopies;
+            c = 0;
+#pragma unroll 8
+            for (int k = 0; k < kCopies; ++k) {
+                const int kk = (k + (int)b) & (kCopies - 1);
+                c += row[kk];
+                row[kk] = 0;
+            }
+        }
+        if (c) {
+            atomicAdd(reinterpret_cast<unsigned long long *>(&pc.ghist[b]), (unsigned long long)c);
+            bits += (uint64_t)c * (a.eg_const - 2u * (uint32_t)__builtin_clz(b + a.eg_add));
+            um = b > um ? b : um;
+        }
+    }
+    // the spare counter(s) too: the next piece may use the other layout, where these words are bins
+    if (tid < STRIDE / 4) lds_hist[fast_lim * (STRIDE / 4) + tid] = 0;
+    bits = wave_reduce(bits, OpAdd());
+    um = wave_reduce(um, OpMax());
+    const uint32_t nan_w = wave_reduce((uint32_t)body.nan_seen, OpOr());
+    const uint32_t ncl_w = wave_reduce(body.n_clamped, OpAdd());
+    const uint32_t nlast_w = wave_reduce(body.n_last, OpAdd());
+    if ((tid & 63) == 0) {
+        const int w = tid >> 6;
+        red64[w] = bits; red[0][w] = um; red[1][w] = nan_w; red[2][w] = ncl_w; red[3][w] = nlast_w;
+    }
+    __syncthreads();
+}
+
+template <typename T, bool NEAREST>
+__global__ __launch_bounds__(kHistThreads) void k_hist(SegView sv, const T *__restrict__ x, QuantArgs a) {
+    extern __shared__ __align__(16) uint32_t lds_hist[];
+    __shared__ uint64_t red64[kHistWaves];
+    __shared__ uint32_t red[4][kHistWaves];
+    const int tid = threadIdx.x;
+    const int64_t first = (int64_t)blockIdx.x * a.chunks_per_block;
+    int64_t last = first + a.chunks_per_block;
+    if (last > a.n_chunks) last = a.n_chunks;
+    if (first >= last) return;
+#ifdef GG_HIST_DEBUG
+    const uint64_t t_in = wall_clock64();
+    uint64_t t_probe = 0, t_sweep = 0;
+#endif
+    const uint32_t last_bin = (uint32_t)(a.nbins - 1);
+    const uint32_t fast_plain = (uint32_t)a.lbins < last_bin ? (uint32_t)a.lbins : last_bin;
+    const uint32_t fast_cols = (uint32_t)a.cbins < last_bin ? (uint32_t)a.cbins : last_bin;
+    bool lds_clear = false;
+    int64_t chunk = first;
+    while (chunk < last) {                                    // one piece per unit the run touches
+        const ChunkLoc L = locate(sv, chunk);
+        const int64_t c0u = unit_chunk0(sv, L.seg), c1u = unit_chunk1(sv, L.seg);
+        const int64_t stop = c1u < last ? c1u : last;         // chunks [chunk, stop) of this unit are the block's
+        const bool piece_shared = c0u < first || c1u > last;
+        const bool first_slot = chunk == first;
+        int64_t e0 = L.start, e1 = L.start + (stop - chunk) * kChunk;
+        const int64_t uend = unit_end(sv, L.seg);
+        if (e1 > uend) e1 = uend;
+        const SegParam P = a.params ? a.params[L.seg] : a.single;
+        chunk = stop;
+        if (P.flags & kSkipRate) continue;                    // no usable step: nothing to count (uniform over the block)
+        HistPiece pc{&P, a.hist + (int64_t)L.seg * a.nbins, last_bin};
+
+        bool flushed = false;
+        while (e0 < e1) {                                     // 32-bit counters and lane sums: at most 2^30 elements at a time
+            const int64_t e = e1 - e0 > (1LL << 30) ? e0 + (1LL << 30) : e1;
+            HistWalk<T> walk;
+            walk.begin(x, e0, (int)(e - e0));                 // the first loads travel while the counters are cleared
+            if (!lds_clear) {
+                gg_u4 *z = reinterpret_cast<gg_u4 *>(lds_hist);
+                for (int b = tid; b < (a.lds_words + 3) / 4; b += kHistThreads) z[b] = gg_u4{0u, 0u, 0u, 0u};
+                lds_clear = true;                             // from here on every merge leaves them cleared
+            }
+            // Which layout?  The first vector of every lane (8192 or 4096 elements at the head of the piece) tells.
+            bool columns = false;
+            if (fast_cols > 0) {
+                HistBody<NEAREST, 4 * kHistCopies> probe;
+                probe.setup(P.inv_delta, 0u, fast_cols);
+                uint32_t beyond = 0;
+                walk.peek([&](const float (&v)[Elem<T>::W]) {
+#pragma unroll
+                    for (int j = 0; j < Elem<T>::W; ++j) {
+                        float t, r;
+                        beyond += probe.code(v[j], t, r) >= probe.lim_bits ? 1u : 0u;
+                    }
+                });
+                beyond = wave_reduce(beyond, OpAdd());
+                if ((tid & 63) == 0) red[0][tid >> 6] = beyond;
+                __syncthreads();                              // also: the counters are cleared
+                uint32_t all = 0;
+#pragma unroll
+                for (int w = 0; w < kHistWaves; ++w) all += red[0][w];
+                // the same sum in every thread; taken from the first lane so that the branch below is a scalar one
+                columns = (uint32_t)__builtin_amdgcn_readfirstlane((int)all) * 4096u <= kHistSampleRareMax * (uint32_t)(kHistThreads * Elem<T>::W);
+            }
+            __syncthreads();
+#ifdef GG_HIST_FORCE_PLAIN     // tuning builds
+            columns = false;
+#endif
+#ifdef GG_HIST_FORCE_COLUMNS
+            columns = fast_cols > 0;
+#endif
+#ifdef GG_HIST_DEBUG
+            t_probe = wall_clock64();
+#endif
+            if (columns) hist_sub_piece<T, NEAREST, 4 * kHistCopies>(walk, a, pc, lds_hist, fast_cols, red64, red);
+            else hist_sub_piece<T, NEAREST, 4>(walk, a, pc, lds_hist, fast_plain, red64, red);
+#ifdef GG_HIST_DEBUG
+            t_sweep = wall_clock64();
+#endif
+            if (tid == 0) {
+                uint64_t tb = 0; uint32_t tu = 0, tn = 0, tc = 0, tl = 0;
+                for (int w = 0; w < kHistWaves; ++w) {
+                    tb += red64[w]; tu = red[0][w] > tu ? red[0][w] : tu; tn |= red[1][w]; tc += red[2][w]; tl += red[3][w];
+                }
+                const uint32_t fl = (tn ? GG_F_NONFINITE : 0u) | (tu >= 2147483647u ? GG_F_SATURATED : 0u);
+                if (piece_shared) {                           // other runs hold pieces of this unit: this run's slot
+                    RatePiece *sl = a.pieces + 2 * (int64_t)blockIdx.x + (first_slot ? 0 : 1);
+                    RatePiece v;
+                    v.bits = tb; v.u_max = tu; v.n_clamped = tc; v.flags = fl; v._pad[0] = v._pad[1] = 0;
+                    if (flushed) { v.bits += sl->bits; v.u_max = tu > sl->u_max ? tu : sl->u_max; v.n_clamped += sl->n_clamped; v.flags |= sl->flags; }
+                    *sl = v;
+                } else {                                      // the whole unit lies in this run: its record is this block's alone
+                    gg_rate_t *r = a.rate + L.seg;
+                    r->eg_bits += tb;
+                    const uint32_t m = tu > r->u_max ? tu : r->u_max;
+                    r->u_max = m;
+                    if (m) r->fl_bits = 32u - (uint32_t)__builtin_clz(m);
+                    r->n_clamped += tc;
+                    if (fl) r->flags |= fl;
+                }
+                if (tl) atomicAdd(reinterpret_cast<unsigned long long *>(&pc.ghist[last_bin]), (unsigned long long)tl);
+            }
+            flushed = true;
+            e0 = e;
+            __syncthreads();                                  // the reduction slots and the (cleared) counters are free again
+        }
+    }
+#ifdef GG_HIST_DEBUG
+    if (tid == 0 && (blockIdx.x % 64) == 0)
+        printf("block %3d: enter %llu | loads + clear + layout +%llu | count+merge +%llu | record +%llu (x10 ns)\n", (int)blockIdx.x,
+               (unsigned long long)t_in, (unsigned long long)(t_probe - t_in),
+               (unsigned long long)(t_sweep - t_probe), (unsigned long long)(wall_clock64() - t_sweep));
+#endif
+}
+
+// ---------------------------------------------------------------------------------------------
 // wave-per-row pass.  For matrices whose rows fit a few cache lines per lane (activations: one row
 // per token) a wave owns a row outright: it sums the moments, solves the fit, derives the row's
 // step and immediately quantises the row again while it is still in cache.  Short rows are taken
@@ -1100,15 +1403,21 @@ __global__ __launch_bounds__(kBlock) void k_rate_reduce_parts_waves(SegView sv, 
     if (lane == 0) store_piece_sum(r, t);
 }
 
-// With a histogram: the same folding, then the entropy of the unit's bins, one workgroup per unit.
+// With a histogram: the same folding, then the entropy of the unit's bins.  `split` workgroups share a unit:
+// workgroup j takes the bins [1024 (i split + j), 1024 (i split + j + 1)), i = 0, 1, ..., a thread one bin of each,
+// and leaves the sum of its terms (lane-strided ascending, fixed tree: the same bits whatever the timing) in
+// parts[seg * split + j]; the workgroup that delivers last adds the parts in the order of j and writes the
+// record.  No workgroup waits for another.
 constexpr int kFinalizeThreads = 1024;
+constexpr int kFinalizeSplitMax = 8;
 __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, const RatePiece *__restrict__ pieces, int32_t cpb,
                                                                     gg_rate_t *__restrict__ rate,
-                                                                    const uint64_t *__restrict__ hist, int32_t nbins) {
+                                                                    const uint64_t *__restrict__ hist, int32_t nbins,
+                                                                    SegParam *__restrict__ params, double *__restrict__ parts, int split) {
     __shared__ double red[kFinalizeThreads / 64];
     __shared__ uint64_t red_bits[kFinalizeThreads / 64], red_ncl[kFinalizeThreads / 64];
     __shared__ uint32_t red_u[2][kFinalizeThreads / 64];
-    const int seg = blockIdx.x, tid = threadIdx.x;
+    const int seg = blockIdx.x / split, part = blockIdx.x - seg * split, tid = threadIdx.x;
     gg_rate_t *r = rate + seg;
     const uint32_t flags = r->flags;
     const uint64_t n = r->n;
@@ -1116,7 +1425,7 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, 
     const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
     const int64_t r0 = c1 > c0 ? c0 / cpb : 0, r1 = c1 > c0 ? (c1 - 1) / cpb : 0;
     const bool shared = live && r0 < r1;           // uniform over the block
-    if (shared) {
+    if (shared) {                                  // every workgroup of the unit folds the slots: it needs the largest symbol
         PieceSum t;
         for (int64_t run = r0 + tid; run <= r1; run += kFinalizeThreads) t.add(piece_slot(pieces, run, cpb, c0));
         t.bits = wave_reduce(t.bits, OpAdd());
@@ -1139,34 +1448,42 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, 
     if (live) {
         const uint64_t *g = hist + (int64_t)seg * nbins;
         const double inv_n = 1.0 / (double)n;
-        // ascending bins per lane, fixed tree above; eight loads in flight, the terms still added in bin order
-        for (int b0 = tid; b0 < used; b0 += 8 * kFinalizeThreads) {
-            uint64_t c[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int b = b0 + k * kFinalizeThreads;
-                c[k] = b < used ? g[b] : 0;
-            }
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if (c[k]) { const double p = (double)c[k] * inv_n; h -= p * log2(p); }
+        for (int b = part * kFinalizeThreads + tid; b < used; b += split * kFinalizeThreads) {
+            const uint64_t c = g[b];
+            if (c) { const double p = (double)c * inv_n; h -= p * log2(p); }
         }
     }
     h = wave_reduce(h, OpAdd());
     if ((tid & 63) == 0) red[tid >> 6] = h;
     __syncthreads();
     if (tid == 0) {
-        if (shared) {
-            PieceSum t;
-            for (int w = 0; w < kFinalizeThreads / 64; ++w) {
-                t.bits += red_bits[w]; t.u_max = red_u[0][w] > t.u_max ? red_u[0][w] : t.u_max;
-                t.n_clamped += red_ncl[w]; t.flags |= red_u[1][w];
-            }
-            store_piece_sum(r, t);
-        }
         h = 0.0;
         for (int w = 0; w < kFinalizeThreads / 64; ++w) h += red[w];
-        r->entropy_bits = h;
+        uint32_t before = 0;
+        if (split > 1) {
+            // deliver: the part, then (release) the ticket; whoever finds every other ticket taken reads (acquire) the parts
+            __hip_atomic_store(reinterpret_cast<uint64_t *>(&parts[(int64_t)seg * split + part]), (uint64_t)__double_as_longlong(h),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            before = __hip_atomic_fetch_add(&params[seg].ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (before == (uint32_t)(split - 1)) {
+            if (split > 1) {
+                h = 0.0;
+                for (int j = 0; j < split; ++j)
+                    h += __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<uint64_t *>(&parts[(int64_t)seg * split + j]),
+                                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                __hip_atomic_store(&params[seg].ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // as it was found
+            }
+            if (shared) {
+                PieceSum t;
+                for (int w = 0; w < kFinalizeThreads / 64; ++w) {
+                    t.bits += red_bits[w]; t.u_max = red_u[0][w] > t.u_max ? red_u[0][w] : t.u_max;
+                    t.n_clamped += red_ncl[w]; t.flags |= red_u[1][w];
+                }
+                store_piece_sum(r, t);
+            }
+            r->entropy_bits = h;
+        }
     }
 }
 
@@ -1422,11 +1739,66 @@ static int launch_quant_mode(const Geometry &g, const void *x, QuantOpts &o, hip
     }
 }
 
+// LDS a workgroup may use on the current device (a property of the device; asked once per device)
+static size_t lds_per_block() {
+    static std::atomic<size_t> cached[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 64u << 10;
+    size_t v = cached[dev].load(std::memory_order_relaxed);
+    if (v) return v;
+    int bytes = 0;
+    if (hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess || bytes <= 0) bytes = 64 << 10;
+    cached[dev].store((size_t)bytes, std::memory_order_relaxed);
+    return (size_t)bytes;
+}
+
+// the histogram-only rate sweep: one workgroup of 1024 threads per compute unit (two where the bins leave room)
+template <typename T, bool NEAREST>
+static int launch_hist_inst(const Geometry &g, const void *x, QuantOpts &o, hipStream_t st) {
+    QuantArgs a{};
+    a.pieces = g.ws ? g.rate_pieces() : nullptr;
+    if (!a.pieces) return GG_ERR_WORKSPACE;
+    a.params = o.params; a.single = o.single; a.rate = o.rate_out;
+    a.eg_add = 1u << o.eg_k; a.eg_const = 63u - (uint32_t)o.eg_k;
+    a.hist = o.hist; a.nbins = o.nbins;
+    const size_t room = (lds_per_block() - 1024) / sizeof(uint32_t);   // counters, beside the kernel's own reduction slots
+    // plain layout: a counter per bin and a spare one; column layout: kHistCopies counters per bin and a spare column
+    int64_t lbins = o.nbins < kHistMaxLdsBins ? o.nbins : kHistMaxLdsBins;
+    if ((size_t)lbins + 1 > room) lbins = (int64_t)room - 1;
+    int64_t cbins = o.nbins - 1 < kHistColumnBins ? o.nbins - 1 : kHistColumnBins;
+    if ((size_t)(cbins + 1) * kHistCopies > room) cbins = (int64_t)(room / kHistCopies) - 1;
+    if (cbins < 0) cbins = 0;
+    const int64_t words = lbins + 1 > (cbins + 1) * kHistCopies ? lbins + 1 : (cbins + 1) * kHistCopies;
+    a.lbins = (int32_t)lbins; a.cbins = (int32_t)cbins; a.lds_words = (int32_t)words;
+    const size_t lds = (size_t)((words + 3) / 4 * 4) * sizeof(uint32_t);   // cleared 16 bytes at a time
+    auto kernel = k_hist<T, NEAREST>;
+    if (lds > (48u << 10) &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+        (void)hipGetLastError();
+        return GG_ERR_HIP;
+    }
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kHistThreads, lds) != hipSuccess || per_cu < 1) per_cu = 1;
+    if (per_cu > 2) per_cu = 2;
+    // a few runs per resident workgroup: the compute units finish at different times, and a workgroup that met
+    // a piece it has to count in plain bins takes longer than its neighbours
+    const RunSplit rs = split_runs(g.n_chunks, per_cu * GG_HIST_RUNS_PER_BLOCK);
+    if (rs.blocks > kMaxRuns) return GG_ERR_WORKSPACE;
+    a.n_chunks = g.n_chunks; a.chunks_per_block = rs.chunks_per_block;
+    o.chunks_per_block_out = rs.chunks_per_block;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)rs.blocks), dim3(kHistThreads), lds, st, g.sv, static_cast<const T *>(x), a);
+    return check_launch();
+}
+
 static int launch_quant(const Geometry &g, const void *x, int dtype, QuantOpts &o, hipStream_t st) {
     if (g.n_chunks == 0) return GG_OK;
     return by_dtype(dtype, [&](auto *tag) {
         using T = std::remove_const_t<std::remove_pointer_t<decltype(tag)>>;
         if (!o.rate) return launch_quant_inst<T, GG_FLOOR, false, true, false>(g, x, o, st);
+#ifndef GG_NO_HIST_KERNEL   // tuning builds
+        if (o.hist && !o.symbols && !o.pen && !o.fit_too)
+            return o.round_mode == GG_FLOOR ? launch_hist_inst<T, false>(g, x, o, st) : launch_hist_inst<T, true>(g, x, o, st);
+#endif
         // kernel MODE: bit 0 = rounding, bit 1 = exponent-based lengths (k = 0, no histogram, no symbols)
 #ifdef GG_NO_EXP0   // tuning builds
         const bool exp0 = false;
@@ -1444,8 +1816,16 @@ static int launch_rate_finalize(const Geometry &g, gg_rate_t *rate, const uint64
                                 int32_t parts, hipStream_t st) {
     if (g.S == 0 || g.n_chunks == 0) return GG_OK;
     if (hist) {
-        hipLaunchKernelGGL(k_rate_finalize, dim3((unsigned)g.S), dim3(kFinalizeThreads), 0, st, g.sv, g.rate_pieces(), cpb, rate,
-                           hist, nbins);
+        // few units: several workgroups share a unit's bins (their parts go where the moment partials were; the fit
+        // that read those has run).  Many units keep the machine busy with a workgroup each.
+        int split = 1;
+        if (g.S <= 32 && nbins > kFinalizeThreads) {
+            split = (nbins + kFinalizeThreads - 1) / kFinalizeThreads;
+            if (split > kFinalizeSplitMax) split = kFinalizeSplitMax;
+            if ((size_t)g.S * split * sizeof(double) > g.wl.partials_bytes) split = 1;
+        }
+        hipLaunchKernelGGL(k_rate_finalize, dim3((unsigned)(g.S * split)), dim3(kFinalizeThreads), 0, st, g.sv, g.rate_pieces(), cpb,
+                           rate, hist, nbins, g.params(), reinterpret_cast<double *>(g.partials()), split);
         return check_launch();
     }
     if (parts > 0) {                                     // short blocks: every unit's record comes from its slots
@@ -1906,7 +2286,6 @@ int gg_fused_rows(const void *x_dev, int dtype, int64_t rows, int64_t cols, floa
 // ---------------------------------------------------------------------------------------------
 static __device__ __align__(256) unsigned char scratch[GG_NOALLOC_SCRATCH_BYTES];
 
-constexpr int kMaxDevices = 64;
 static std::atomic<void *> g_scratch_ptr[kMaxDevices];   // per device, set on the first call made with that device current
 
 // device address of `scratch` on the current device, or nullptr when it cannot be had

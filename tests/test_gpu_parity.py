@@ -8,6 +8,7 @@ import torch
 
 import gg_inputs
 import oracle
+import parity
 from parity import (check_fit, check_penalty, check_rate, host_bits)
 
 pytestmark = pytest.mark.gpu
@@ -264,6 +265,73 @@ def test_quantize_rate_segmented_with_histograms(gg):
         r, ohist, osym = oracle.quantize_rate(hb[off[s]:off[s + 1]], float(d), nbins=512, want_symbols=True)
         check_rate(rec[s], r, f"seg {s}")
         assert np.array_equal(hist[s], ohist) and np.array_equal(sym[off[s]:off[s + 1]], osym)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_histogram_sweep_layouts_and_transitions(gg, dtype):
+    """The histogram-only sweep counts in one of two LDS layouts, chosen per piece from the data (copies of the low
+    bins for peaked symbol distributions, plain bins otherwise).  A bucket of 6 M elements -- more chunks than the
+    sweep has workgroups, so that a workgroup walks through several units -- whose units alternate between peaked
+    and wide distributions, with NaN / Inf / zeros planted, tiny, empty and degenerate units in between: every
+    count, bit sum, largest symbol and flag against the oracle, for histograms narrower and wider than either
+    layout, both rounding modes, two code orders."""
+    rng = np.random.default_rng(5)
+    sizes, kinds = [], []
+    for i in range(60):
+        sizes.append(int(rng.choice([0, 1, 777, 5000, 16384, 40_001, 131_072, 300_000])))
+        kinds.append(i % 3)
+    sizes += [1_200_000, 900_001]
+    kinds += [0, 1]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n, S = int(off[-1]), len(sizes)
+    assert n > 256 * 16384
+    x = torch.empty(n, dtype=torch.float32, device=DEV)
+    delta_h = np.empty(S, dtype=np.float32)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(55)
+    for s in range(S):
+        lo, hi = int(off[s]), int(off[s + 1])
+        if kinds[s] == 0:       # peaked: nearly every symbol below a thousand
+            x[lo:hi] = gg_inputs.gg_torch(hi - lo, 0.02, 0.8, gen, DEV)
+            delta_h[s] = 0.02 / 8
+        elif kinds[s] == 1:     # wide: symbols in the thousands and tens of thousands
+            x[lo:hi] = gg_inputs.gg_torch(hi - lo, 0.5, 1.6, gen, DEV)
+            delta_h[s] = 0.5 / 3000
+        else:                   # in between, with a heavy tail
+            x[lo:hi] = gg_inputs.gg_torch(hi - lo, 1e-3, 0.5, gen, DEV)
+            delta_h[s] = 1e-3 / 16
+    delta_h[7] = 0.0                                   # a unit without a usable step
+    pos = torch.randint(0, n, (400,), generator=gen, device=DEV)
+    x[pos[:100]] = float("nan")
+    x[pos[100:200]] = float("inf")
+    x[pos[200:300]] = -float("inf")
+    x[pos[300:]] = 0.0
+    x = x.to(dtype)
+    hb = host_bits(x)
+    delta = torch.tensor(delta_h, device=DEV)
+    ws = gg.Workspace(n, S)
+    for nbins, mode, k in ((2, gg.GG_FLOOR, 0), (40, gg.GG_NEAREST_EVEN, 0), (1024, gg.GG_FLOOR, 3), (1500, gg.GG_FLOOR, 0),
+                           (4096, gg.GG_NEAREST_EVEN, 1), (40000, gg.GG_FLOOR, 0), (65536, gg.GG_FLOOR, 0)):
+        out, hist, _ = gg.gg_quantize_rate_segmented(x, off, delta, ws, eg_k=k, round_mode=mode, nbins=nbins)
+        rec = gg.rate_records(out)
+        hist = hist.cpu().numpy().view(np.uint64).reshape(S, nbins)
+
+        def one(s):
+            return oracle.quantize_rate(hb[off[s]:off[s + 1]], float(delta_h[s]), eg_k=k, round_mode=mode, nbins=nbins)
+
+        live = [s for s in range(S) if sizes[s] > 0 and delta_h[s] > 0]
+        for s, (r, ohist, _) in zip(live, parity.oracle_threads(one, live)):
+            check_rate(rec[s], r, f"nbins {nbins} unit {s} kind {kinds[s]}")
+            assert np.array_equal(hist[s], ohist), (nbins, s)
+        assert rec[7]["flags"] == gg.GG_F_DEGENERATE and not hist[7].any()
+        for s in range(S):
+            if sizes[s] == 0:
+                assert rec[s]["flags"] == gg.GG_F_EMPTY and not hist[s].any()
+    # the same through the single-tensor call: one unit shared by every workgroup
+    out, hist1, _ = gg.gg_quantize_rate(x, 0.02 / 8, ws, nbins=4096)
+    r, ohist, _ = oracle.quantize_rate(hb, 0.02 / 8, nbins=4096)
+    check_rate(gg.rate_records(out)[0], r, "whole buffer")
+    assert np.array_equal(hist1.cpu().numpy().view(np.uint64), ohist)
 
 
 def test_quantize_rate_rows(gg):
@@ -746,10 +814,11 @@ def test_rows_histogram_coder_and_sampler_are_graph_capturable(gg):
     def work():
         r = gg.gg_fused_rows(x, rows, cols, ws, delta_div=8.0, want_total=True)
         rate, hist, sym = gg.gg_quantize_rate(x, 0.01, ws1, nbins=4096, want_symbols=True)
+        rate_h, hist_h, _ = gg.gg_quantize_rate(x, 0.01, ws1, nbins=2048)          # the histogram-only sweep
         gg.gg_eg_encode_tensor(x, 0.01, buffers=bufs)
         back = gg.gg_eg_decode_dequant(bufs[0], bufs[1][: tiles + 1], n, 0.01)
         smp = gg.gg_sample(5000, 0.1, 0.7, seed=3)
-        return [r["fit"], r["rate"], r["total"], rate, hist, sym, bufs[2], back, smp]
+        return [r["fit"], r["rate"], r["total"], rate, hist, sym, rate_h, hist_h, bufs[2], back, smp]
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
