@@ -28,8 +28,8 @@
  *   - Every function returns GG_OK or a negative error code.  Invalid arguments are detected on
  *     the host before anything is launched.  Data-dependent conditions (empty, degenerate,
  *     clamped, non-finite input) are reported per unit in the `flags` fields, never as errors.
- *   - dtype: GG_F32 (IEEE binary32) or GG_BF16 (bfloat16, widened exactly to fp32).
- *   - Supported magnitude range of inputs: |x| < 1e18 (squares are accumulated in fp32 partials).
+ *   - dtype: GG_F32 (IEEE binary32) or GG_BF16 (bfloat16, widened exactly to fp32).  Any finite values, denormals
+ *     included: where the fp32 square of a value would leave the fp32 range, the moment sums form it in fp64.
  */
 #ifndef GG_H
 #define GG_H

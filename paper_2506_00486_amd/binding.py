@@ -181,11 +181,14 @@ def gg_fit_rows(x: torch.Tensor, rows: int, cols: int, ws: Workspace, want_total
 
 
 def gg_quantize_rate(x: torch.Tensor, delta: float, ws: Workspace, eg_k: int = 0, round_mode: int = GG_FLOOR,
-                     nbins: int = 0, want_symbols: bool = False):
-    """Returns (rate record tensor, hist uint64-as-int64 tensor or None, symbols int32 tensor or None)."""
-    hist = torch.empty(nbins, dtype=torch.int64, device=x.device) if nbins > 0 else None
-    sym = torch.empty(x.numel(), dtype=torch.int32, device=x.device) if want_symbols else None
-    out = _records(1, 48, x.device)
+                     nbins: int = 0, want_symbols: bool = False, out: Optional[torch.Tensor] = None,
+                     hist: Optional[torch.Tensor] = None, symbols: Optional[torch.Tensor] = None):
+    """Returns (rate record tensor, hist uint64-as-int64 tensor or None, symbols int32 tensor or None).
+    `out`, `hist`, `symbols`: buffers of the caller to write into instead of new ones."""
+    if nbins > 0 and hist is None:
+        hist = torch.empty(nbins, dtype=torch.int64, device=x.device)
+    sym = symbols if symbols is not None else (torch.empty(x.numel(), dtype=torch.int32, device=x.device) if want_symbols else None)
+    out = out if out is not None else _records(1, 48, x.device)
     _check(lib().gg_quantize_rate(_dev(x), _dtype_code(x), x.numel(), _f32(delta), eg_k, round_mode, nbins, _dev(hist),
                                   _dev(sym), _dev(out), ws.ptr, ws.bytes, _stream()), "gg_quantize_rate")
     return out, hist, sym
@@ -268,14 +271,19 @@ def gg_fused_segmented(x: torch.Tensor, offsets, ws: Workspace, delta_div: float
                        delta: Optional[torch.Tensor] = None, eg_k: int = 0, round_mode: int = GG_FLOOR,
                        nbins: int = 0, want_symbols: bool = False, lam: float = 0.0,
                        grad: Optional[torch.Tensor] = None, accumulate: bool = False, want_rate: bool = True,
-                       fit: Optional[torch.Tensor] = None, rate: Optional[torch.Tensor] = None):
-    """Returns dict(fit=, rate=, hist=, symbols=, grad=) of device tensors (None where not requested)."""
+                       fit: Optional[torch.Tensor] = None, rate: Optional[torch.Tensor] = None,
+                       hist: Optional[torch.Tensor] = None):
+    """Returns dict(fit=, rate=, hist=, symbols=, grad=) of device tensors (None where not requested).
+    `fit`, `rate`, `hist`: buffers of the caller to write into instead of new ones."""
     off = _offsets(offsets)
     S = off.size - 1
     fit = fit if fit is not None else _records(S, 40, x.device)
     if want_rate and rate is None:
         rate = _records(S, 48, x.device)
-    hist = torch.empty(max(S, 1) * nbins, dtype=torch.int64, device=x.device) if (nbins > 0 and want_rate) else None
+    if not (nbins > 0 and want_rate):
+        hist = None
+    elif hist is None:
+        hist = torch.empty(max(S, 1) * nbins, dtype=torch.int64, device=x.device)
     sym = torch.empty(x.numel(), dtype=torch.int32, device=x.device) if (want_symbols and want_rate) else None
     _check(lib().gg_fused_segmented(_dev(x), _dtype_code(x), off.ctypes.data, S, _f32(delta_div), _dev(delta), eg_k,
                                     round_mode, nbins if hist is not None else 0, _dev(hist), _dev(sym), _f32(lam),
@@ -301,10 +309,13 @@ def gg_fused_segmented_noalloc(x: torch.Tensor, offsets, fit: torch.Tensor, rate
 def gg_fused_rows(x: torch.Tensor, rows: int, cols: int, ws: Workspace, delta_div: float = 16.0,
                   delta: Optional[torch.Tensor] = None, eg_k: int = 0, round_mode: int = GG_FLOOR,
                   want_symbols: bool = False, lam: float = 0.0, grad: Optional[torch.Tensor] = None,
-                  accumulate: bool = False, want_rate: bool = True, want_total: bool = False):
-    fit = _records(rows, 40, x.device)
-    total = _records(1, 40, x.device) if want_total else None
-    rate = _records(rows, 48, x.device) if want_rate else None
+                  accumulate: bool = False, want_rate: bool = True, want_total: bool = False,
+                  fit: Optional[torch.Tensor] = None, total: Optional[torch.Tensor] = None,
+                  rate: Optional[torch.Tensor] = None):
+    """`fit`, `total`, `rate`: buffers of the caller to write into instead of new ones."""
+    fit = fit if fit is not None else _records(rows, 40, x.device)
+    total = (total if total is not None else _records(1, 40, x.device)) if want_total else None
+    rate = (rate if rate is not None else _records(rows, 48, x.device)) if want_rate else None
     sym = torch.empty(x.numel(), dtype=torch.int32, device=x.device) if (want_symbols and want_rate) else None
     _check(lib().gg_fused_rows(_dev(x), _dtype_code(x), rows, cols, _f32(delta_div), _dev(delta), eg_k, round_mode,
                                _dev(sym), _f32(lam), _dev(grad), int(bool(accumulate)), _dev(fit), _dev(total),

@@ -66,6 +66,40 @@ struct FitBody {
     }
 };
 
+// The fp32 squares of a lane's share leave the representable range when all of its values lie below about 1e-19
+// (the squares vanish) or one above about 1e19 (its square is infinite).  The sums tell: a sum of squares below
+// 2^-90 next to a positive sum of magnitudes (had even one square been in range, the sum would be there too, and
+// the at most 64 vanished ones beside it would be 2^-54 of it), or an infinite sum.  Such a share -- in practice
+// a whole tensor that lives at such a scale, or none -- is summed again with the squares formed in fp64.
+struct FitBody64 {
+    double s1 = 0.0, s2 = 0.0;
+    template <int W>
+    __device__ __forceinline__ void vec(const float (&v)[W], int64_t) {
+#pragma unroll
+        for (int j = 0; j < W; ++j) { const double d = (double)v[j]; s1 += fabs(d); s2 = fma(d, d, s2); }
+    }
+    __device__ __forceinline__ void one(float v, int64_t) { const double d = (double)v; s1 += fabs(d); s2 = fma(d, d, s2); }
+};
+
+__device__ __forceinline__ bool fit_sums_left_range(const float (&s1)[4], const float (&s2)[4]) {
+    const float a = (s1[0] + s1[1]) + (s1[2] + s1[3]), b = (s2[0] + s2[1]) + (s2[2] + s2[3]);
+    return (a > 0.f && b < 0x1p-90f) || a == __builtin_inff() || b == __builtin_inff();
+}
+
+// the lane's sums of one walk as doubles (d1, d2 are added to); E, GROUP and the range as in the walk that filled `fb`
+template <typename E, int GROUP>
+__device__ __forceinline__ void add_lane_moments(const float (&s1)[4], const float (&s2)[4], const typename E::type *__restrict__ x,
+                                                 int64_t start, int len, double &d1, double &d2) {
+    if (fit_sums_left_range(s1, s2)) {             // per lane: the walk has no barrier in it
+        FitBody64 wide;
+        process_chunk<E, 1, FitBody64, GROUP>(x, start, len, wide);
+        d1 += wide.s1; d2 += wide.s2;
+    } else {
+        d1 += ((double)s1[0] + (double)s1[1]) + ((double)s1[2] + (double)s1[3]);
+        d2 += ((double)s2[0] + (double)s2[1]) + ((double)s2[2] + (double)s2[3]);
+    }
+}
+
 // A block owns a run of consecutive chunks.  Lanes keep fp32 sums per chunk (<= 16 terms each) and
 // fold them into fp64 lane totals; lanes are combined only when the run leaves a unit or ends.
 // The combined value of a (run, unit) piece goes to the slot of the piece's first chunk, which is
@@ -108,8 +142,7 @@ __global__ __launch_bounds__(kBlock) void k_fit_partials(SegView sv, const T *__
         }
         FitBody body;
         process_chunk<Elem<T>, GG_U_FIT>(x, cur.L.start, cur.L.len, body);
-        d1 += ((double)body.s1[0] + (double)body.s1[1]) + ((double)body.s1[2] + (double)body.s1[3]);
-        d2 += ((double)body.s2[0] + (double)body.s2[1]) + ((double)body.s2[2] + (double)body.s2[3]);
+        add_lane_moments<Elem<T>, kBlock>(body.s1, body.s2, x, cur.L.start, cur.L.len, d1, d2);
     }
     flush(piece_first);
 }
@@ -267,6 +300,81 @@ __device__ __forceinline__ void solve_fit_batch(double s1, double s2, uint64_t n
         if (lane == r) j = coarse[r] + c2 - 1;
     }
     if (search) finish_from_table(j, target, m2, f);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same root with the transcendental functions in fp32, for the wave-per-row kernel, where a fit costs as much
+// as reading the row: about 150 instructions instead of about 300 double-precision ones (half rate).  Every lane
+// of the wave takes the same arguments.  What keeps the result at 3e-7 relative (the fp64 solvers: 2e-7 after
+// rounding to fp32; the bar is 1e-4):
+//   * ln v of a double v = m 2^e as e ln 2 + ln m, the first term and the sum in fp64, ln m by v_log_f32 with
+//     |ln m| < 0.7: 6e-8 absolute;
+//   * the interpolation on differences to the table (x_k - target, a_k - a_1 formed in fp64, then fp32): the
+//     quantities interpolated are a grid step wide, so fp32 rounding is 1e-7 of 1.5e-3;
+//   * alpha = 2^k 2^r with k + r = log2(e) * (ln m2 + a) / 2 split in fp64, 2^r by v_exp_f32 with |r| <= 1/2.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ double ln_by_parts(double v) {      // v > 0, finite
+    const int e = __builtin_amdgcn_frexp_exp(v);
+    const float m = (float)__builtin_amdgcn_frexp_mant(v);       // [0.5, 1)
+    return (double)e * 0.69314718055994530942 + (double)(0.69314718056f * __builtin_amdgcn_logf(m));
+}
+
+__device__ __forceinline__ float exp_by_parts(double ln_v) {    // e^ln_v as a float
+    const double y = ln_v * 1.44269504088896340736;
+    const double k = __builtin_rint(y);
+    const float r = (float)(y - k);                              // |r| <= 1/2, exact difference
+    return ldexpf(__builtin_amdgcn_exp2f(r), (int)k);
+}
+
+__device__ __forceinline__ void solve_fit_wave_f32(double s1, double s2, uint64_t n, gg_fit_t &f) {
+    static_assert(kSolveTable == 64 * 64, "two 64-way rounds cover the table");
+    const CurvePoint *__restrict__ table = kSolveCurve;
+    const int lane = threadIdx.x & 63;
+    f.sum_abs = s1; f.sum_sq = s2; f.n = n; f.beta = 0.f; f.alpha = 0.f; f.flags = 0; f._pad = 0;
+    if (n == 0) { f.flags = GG_F_EMPTY; return; }
+    if (!isfinite(s1) || !isfinite(s2)) { f.flags = GG_F_NONFINITE; f.beta = 2.f; return; }
+    if (s2 == 0.0) { f.flags = GG_F_DEGENERATE; f.beta = 2.f; return; }
+    const double ln_n = ln_by_parts((double)n);
+    const double ln_m2 = ln_by_parts(s2) - ln_n;
+    const double target = 2.0 * (ln_by_parts(s1) - ln_n) - ln_m2;                  // ln of the moment ratio (s1 > 0 since s2 > 0)
+    if (!(target > table[0].x)) { f.beta = (float)GG_BETA_MIN; f.flags = GG_F_BETA_CLAMPED_LO; f.alpha = exp_by_parts(0.5 * (ln_m2 + table[0].y)); return; }
+    if (!(target < table[kSolveTable].x)) { f.beta = (float)GG_BETA_MAX; f.flags = GG_F_BETA_CLAMPED_HI; f.alpha = exp_by_parts(0.5 * (ln_m2 + table[kSolveTable].y)); return; }
+    int c1 = __popcll(__ballot(table[64 * lane].x <= target));
+    c1 = c1 < 1 ? 1 : c1;
+    const int coarse = 64 * (c1 - 1);
+    const CurvePoint t2 = table[coarse + lane];
+    int c2 = __popcll(__ballot(t2.x <= target));
+    c2 = c2 < 1 ? 1 : c2;
+    const int j0 = first_point(coarse + c2 - 1);
+    double fs[4], as[4];
+    if (j0 >= coarse && j0 + 3 <= coarse + 63) {          // the four points are in this round's lanes
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { fs[k] = __shfl(t2.x, j0 - coarse + k, 64); as[k] = __shfl(t2.y, j0 - coarse + k, 64); }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { const CurvePoint t = table[j0 + k]; fs[k] = t.x; as[k] = t.y; }
+    }
+    // inverse interpolation in node units: tau = sum_k k w_k, w_k = prod_{m != k} d_m / (d_m - d_k), d_k = x_k - target
+    float d[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) d[k] = (float)(fs[k] - target);
+    float tau = 0.f;
+#pragma unroll
+    for (int k = 1; k < 4; ++k) {
+        float num = (float)k, den = 1.f;
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+            if (m != k) { num *= d[m]; den *= d[m] - d[k]; }
+        tau += num / den;
+    }
+    const double l_min = log(GG_BETA_MIN), h = (log(GG_BETA_MAX) - l_min) / (double)kSolveTable;   // constants
+    const float l = (float)(l_min + h * (double)j0) + (float)h * tau;
+    f.beta = __builtin_amdgcn_exp2f(l * 1.44269504089f);
+    // the scale factor of Eq. 2 at tau: cubic through a_k - a_1 on the nodes 0, 1, 2, 3
+    const float e0 = (float)(as[0] - as[1]), e2 = (float)(as[2] - as[1]), e3 = (float)(as[3] - as[1]);
+    const float t0 = tau, t1 = tau - 1.f, t2f = tau - 2.f, t3 = tau - 3.f;
+    const float da = e0 * (t1 * t2f * t3) * (-1.f / 6.f) + e2 * (t0 * t1 * t3) * (-0.5f) + e3 * (t0 * t1 * t2f) * (1.f / 6.f);
+    f.alpha = exp_by_parts(0.5 * (ln_m2 + as[1] + (double)da));                     // Eq. 2 with sigma^2 = m2
 }
 
 // where the step and the penalty parameters of a unit come from
@@ -812,8 +920,7 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
         else
             process_chunk<Elem<T>, GG_U_QUANT>(x, cur.L.start, cur.L.len, body);
         if constexpr (FIT) {   // per chunk: <= 16-term fp32 lane sums into the fp64 lane totals
-            d1 += ((double)body.s1[0] + (double)body.s1[1]) + ((double)body.s1[2] + (double)body.s1[3]);
-            d2 += ((double)body.s2[0] + (double)body.s2[1]) + ((double)body.s2[2] + (double)body.s2[3]);
+            add_lane_moments<Elem<T>, kBlock>(body.s1, body.s2, x, cur.L.start, cur.L.len, d1, d2);
 #pragma unroll
             for (int j = 0; j < 4; ++j) { body.s1[j] = 0.f; body.s2[j] = 0.f; }
         }
@@ -1211,8 +1318,8 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
                 FitBody fb;
                 // cached loads: the row is read again a few microseconds later by this same wave
                 process_chunk<Elem<T, !(RATE || PEN)>, 4, FitBody, 64>(x, (row0 + r) * a.cols, len, fb);
-                double s1 = ((double)fb.s1[0] + (double)fb.s1[1]) + ((double)fb.s1[2] + (double)fb.s1[3]);
-                double s2 = ((double)fb.s2[0] + (double)fb.s2[1]) + ((double)fb.s2[2] + (double)fb.s2[3]);
+                double s1 = 0.0, s2 = 0.0;
+                add_lane_moments<Elem<T, !(RATE || PEN)>, 64>(fb.s1, fb.s2, x, (row0 + r) * a.cols, len, s1, s2);
                 s1 = wave_reduce(s1, OpAdd());
                 s2 = wave_reduce(s2, OpAdd());
                 if (lane == r) { my_s1 = s1; my_s2 = s2; }
@@ -1279,6 +1386,124 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
         tot2 = wave_reduce(tot2, OpAdd());
         if (lane == 0) a.wave_sums[(int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6)] = make_double2(tot1, tot2);
     }
+}
+
+// Rows of at most 8 KiB whose byte length is a multiple of 16 (activations: a few thousand bf16 per token), fit +
+// rate and nothing to write per element: the wave keeps its row in registers -- NV 16-byte vectors per lane --
+// between the two sweeps, so memory sees every element exactly once whatever the caches hold, and the fit between
+// the sweeps is the fp32-based one (no batching of rows: a fit costs less than a tenth of the row's sweeps).
+template <typename T, int NV, bool NEAREST>
+__global__ __launch_bounds__(kBlock) void k_rows_reg(const T *__restrict__ x, RowsArgs a) {
+    using E = Elem<T, true>;                       // streaming loads: nothing is read twice
+    using Raw = typename E::raw;
+    constexpr int W = E::W;
+    const int lane = threadIdx.x & 63;
+    const int64_t n_waves = (int64_t)gridDim.x * kWaves;
+    const int len = (int)a.cols;
+    const int nvec = len / W;                      // the launcher takes only rows of whole vectors, NV = ceil(nvec / 64)
+    const int padded = NV * 64 * W - len;          // elements a short last group is filled up with (zeros)
+    // Loads are never predicated per lane (a predicated load makes the compiler wait for each one by itself):
+    // lanes past the end of a short last group read the row's last vector again and zero it afterwards.
+    auto load_row = [&](int64_t row, Raw (&dst)[NV]) {
+        const T *__restrict__ p = x + row * a.cols;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int i = lane + 64 * v;
+            dst[v] = E::loadv(p + (int64_t)((v < NV - 1 || i < nvec) ? i : nvec - 1) * W);
+        }
+    };
+    double tot1 = 0.0, tot2 = 0.0;
+
+    // one row from the registers `cur`; the wave's next row, if there is one, starts travelling into `nxt` on the way
+    auto do_row = [&](int64_t row, Raw (&cur)[NV], Raw (&nxt)[NV]) {
+        if (padded && lane + 64 * (NV - 1) >= nvec) cur[NV - 1] = Raw{};
+        // sweep 1: moments, at most 16 terms per fp32 partial sum
+        FitBody fb;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) { float e[W]; E::unpack(cur[v], e); fb.vec(e, 0); }
+        double s1, s2;
+        if (fit_sums_left_range(fb.s1, fb.s2)) {   // squares out of the fp32 range: again, in fp64, from the registers
+            FitBody64 wide;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) { float e[W]; E::unpack(cur[v], e); wide.vec(e, 0); }
+            s1 = wide.s1; s2 = wide.s2;
+        } else {
+            s1 = ((double)fb.s1[0] + (double)fb.s1[1]) + ((double)fb.s1[2] + (double)fb.s1[3]);
+            s2 = ((double)fb.s2[0] + (double)fb.s2[1]) + ((double)fb.s2[2] + (double)fb.s2[3]);
+        }
+        s1 = wave_reduce(s1, OpAdd());
+        s2 = wave_reduce(s2, OpAdd());
+        gg_fit_t f;
+        solve_fit_wave_f32(s1, s2, (uint64_t)len, f);
+        if (lane == 0) a.fit[row] = f;
+        tot1 += s1; tot2 += s2;
+        // the row's step: one correctly rounded fp32 division each, as on the host
+        const float delta = a.delta_div > 0.f ? f.alpha / a.delta_div : a.delta_dev[row];
+        const bool ok = delta > 0.f && isfinite(delta);
+        float inv_delta = ok ? 1.0f / delta : 0.f;
+        asm volatile("" : "+v"(inv_delta));        // formed here, not where it is first used
+        // The next row starts travelling now, after everything above that waits for memory (a wait behind a conditional
+        // load waits for all loads): the registers the fit needed are free, and the second sweep and the reductions
+        // behind it take about as long as the loads.
+        __builtin_amdgcn_sched_barrier(0);         // (keeps the instruction scheduler from moving the division below the loads)
+        if (row + n_waves < a.rows) load_row(row + n_waves, nxt);
+        // sweep 2 from the registers.  The empty statements keep the compiler from carrying the widened fp32 values of
+        // sweep 1 over the fit (twice or four times the registers of the packed row); they are formed again here.
+#pragma unroll
+        for (int v = 0; v < NV; ++v) asm volatile("" : "+v"(cur[v].x), "+v"(cur[v].y), "+v"(cur[v].z), "+v"(cur[v].w));
+        // The exponent path (see QuantBody) two elements at a time: three-operand add, max and min.  Whether the row holds
+        // a NaN is known from its sum of magnitudes, so no element is tested for it.
+        uint32_t exp_sum = 0;
+        float r_max = 0.f, r_min = 0.f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            float e[W];
+            E::unpack(cur[v], e);
+#pragma unroll
+            for (int j = 0; j < W; j += 2) {
+                const float r0 = NEAREST ? rintf(-(e[j] * inv_delta)) : ceilf(-(e[j] * inv_delta));
+                const float r1 = NEAREST ? rintf(-(e[j + 1] * inv_delta)) : ceilf(-(e[j + 1] * inv_delta));
+                const float a0 = __builtin_amdgcn_fmed3f(fabsf(r0), 0.5f, 1073741824.0f);
+                const float a1 = __builtin_amdgcn_fmed3f(fabsf(r1), 0.5f, 1073741824.0f);
+                exp_sum += (__float_as_uint(a0) >> 23) + (__float_as_uint(a1) >> 23);
+                r_max = fmaxf(fmaxf(r_max, r0), r1);       // NaN operands are ignored by v_max / v_min
+                r_min = fminf(fminf(r_min, r0), r1);
+            }
+        }
+        QuantBody<2, true, false, false> ends;     // (for the largest symbol from the two extremes of -q)
+        ends.r_max = r_max; ends.r_min = r_min;
+        // the zeros a short last group was filled up with were counted as symbol 0: exponent 126
+        const uint64_t lsum = wave_reduce((uint64_t)exp_sum, OpAdd()) - 126ull * (uint64_t)padded;
+        const uint32_t um = wave_reduce(ends.exp0_u_max(), OpMax());
+        if (lane == 0) {
+            gg_rate_t rr;
+            rr.n = (uint64_t)len; rr.n_clamped = 0; rr.entropy_bits = 0.0; rr.delta = delta;
+            if (ok) {
+                rr.eg_bits = 2ull * lsum - 251ull * (uint64_t)len;
+                rr.u_max = um;
+                rr.fl_bits = um ? 32u - (uint32_t)__builtin_clz(um) : 1u;
+                // an element is NaN exactly when the row's sum of magnitudes is (an infinite element makes it infinite, not NaN)
+                rr.flags = (s1 != s1 ? GG_F_NONFINITE : 0u) | (um >= 2147483647u ? GG_F_SATURATED : 0u);
+            } else {
+                rr.eg_bits = 0; rr.u_max = 0; rr.fl_bits = 0; rr.flags = GG_F_DEGENERATE;
+            }
+            a.rate[row] = rr;
+        }
+    };
+
+    // the wave index as a scalar, so that the branches on the row number are scalar branches
+    int64_t row = (int64_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    Raw ra[NV], rb[NV];                            // two register sets taking turns
+    if (row < a.rows) load_row(row, ra);
+    while (row < a.rows) {
+        do_row(row, ra, rb);
+        row += n_waves;
+        if (row >= a.rows) break;
+        do_row(row, rb, ra);
+        row += n_waves;
+    }
+    if (a.wave_sums && lane == 0)     // every wave of the grid, also one without rows: the reader adds them all
+        a.wave_sums[(int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6)] = make_double2(tot1, tot2);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1904,6 +2129,38 @@ static int launch_rows_mode(const void *x, const RowsArgs &a, bool rate, bool pe
 
 static bool rows_take_wave_path(int64_t rows, int64_t cols) { return rows > 0 && cols > 0 && cols <= kRowWaveMax; }
 
+// rows that fit a wave's registers (k_rows_reg): whole 16-byte vectors, at most 8 per lane; order-0 code lengths
+constexpr int64_t kRowRegBytes = 8192;
+template <typename T, bool NEAREST>
+static int launch_rows_reg(const void *x, RowsArgs a, hipStream_t st) {
+    const int64_t vecs = a.cols * (int64_t)sizeof(T) / 16;
+    const int nv = (int)((vecs + 63) / 64);
+    auto go = [&](auto kernel) {
+        const int bpc = resident_blocks(kernel, 0, 8);
+        const int64_t cap_waves = (int64_t)kComputeUnits * bpc * kWaves;
+        const int64_t waves = a.rows < cap_waves ? a.rows : cap_waves;
+        const int64_t blocks = (waves + kWaves - 1) / kWaves;
+        const bool want_total = a.total_out != nullptr;
+        if (want_total && !(a.wave_sums != nullptr && a.wave_sums_cap >= blocks * kWaves)) return -1;   // the caller takes the general kernel
+        if (!want_total) a.wave_sums = nullptr;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kBlock), 0, st, static_cast<const T *>(x), a);
+        if (want_total)
+            hipLaunchKernelGGL(k_fit_total_waves, dim3(1), dim3(kTotalThreads), 0, st, (const double2 *)a.wave_sums, blocks * kWaves,
+                               (uint64_t)(a.rows * a.cols), a.total_out);
+        return check_launch();
+    };
+    switch (nv) {
+        case 1: return go(k_rows_reg<T, 1, NEAREST>);
+        case 2: return go(k_rows_reg<T, 2, NEAREST>);
+        case 3: return go(k_rows_reg<T, 3, NEAREST>);
+        case 4: return go(k_rows_reg<T, 4, NEAREST>);
+        case 5: return go(k_rows_reg<T, 5, NEAREST>);
+        case 6: return go(k_rows_reg<T, 6, NEAREST>);
+        case 7: return go(k_rows_reg<T, 7, NEAREST>);
+        default: return go(k_rows_reg<T, 8, NEAREST>);
+    }
+}
+
 static int launch_rows(const Geometry &g, const void *x, int dtype, RowsArgs a, int eg_k, int round_mode, bool rate, bool pen,
                        hipStream_t st) {
     a.eg_add = 1u << eg_k; a.eg_const = 63u - (uint32_t)eg_k;
@@ -1913,6 +2170,12 @@ static int launch_rows(const Geometry &g, const void *x, int dtype, RowsArgs a, 
         if (!rate && !pen) return launch_rows_inst<T, GG_FLOOR, false, false, false>(x, a, st);
         if (!rate) return launch_rows_inst<T, GG_FLOOR, false, true, false>(x, a, st);
         const bool exp0 = eg_k == 0 && !extra && !pen;
+#ifndef GG_NO_ROWS_REG   // tuning builds
+        if (exp0 && a.do_fit && a.cols * (int64_t)sizeof(T) <= kRowRegBytes && (a.cols * (int64_t)sizeof(T)) % 16 == 0) {
+            const int rc = round_mode == GG_FLOOR ? launch_rows_reg<T, false>(x, a, st) : launch_rows_reg<T, true>(x, a, st);
+            if (rc != -1) return rc;
+        }
+#endif
         if (round_mode == GG_FLOOR)
             return exp0 ? launch_rows_mode<T, 2>(x, a, rate, pen, extra, st) : launch_rows_mode<T, 0>(x, a, rate, pen, extra, st);
         return exp0 ? launch_rows_mode<T, 3>(x, a, rate, pen, extra, st) : launch_rows_mode<T, 1>(x, a, rate, pen, extra, st);

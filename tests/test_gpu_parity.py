@@ -547,6 +547,110 @@ def test_fused_rows_taken_two_at_a_time(gg, dtype, cols):
     assert int(rrec["n"].astype(np.int64).sum()) == rows * cols
 
 
+@pytest.mark.parametrize("dtype,cols", [(torch.bfloat16, 4096), (torch.bfloat16, 8), (torch.bfloat16, 520), (torch.bfloat16, 1544),
+                                        (torch.bfloat16, 3592), (torch.float32, 2048), (torch.float32, 4), (torch.float32, 772),
+                                        (torch.float32, 1284)])
+@pytest.mark.parametrize("mode", ["floor", "nearest"])
+def test_fused_rows_kept_in_registers(gg, dtype, cols, mode):
+    """Rows of at most 8 KiB made of whole 16-byte vectors, fit + order-0 rate: the wave keeps the row in registers
+    between its two sweeps, 1 to 8 vectors per lane, the last group of 64 vectors full or short, and fits the row
+    with the fp32-based solver.  Shapes from 0.06 to 19 along the rows; rows holding NaN, Inf, zeros, one value."""
+    rows = 1100
+    rng = np.random.default_rng(cols)
+    betas = np.exp(rng.uniform(np.log(0.06), np.log(19.0), size=rows))
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(cols)
+    x = torch.empty(rows, cols, device=DEV)
+    for lo in range(0, rows, 50):          # a shape per group of 50 rows
+        x[lo:lo + 50] = gg_inputs.gg_torch(min(50, rows - lo) * cols, 0.3, float(betas[lo]), gen, DEV).reshape(-1, cols)
+    x[3] = 0.0
+    x[4] = -0.75
+    x[5, cols // 2] = float("nan")
+    x[6, 0] = float("inf")
+    x[7, cols - 1] = -float("inf")
+    x[8] *= 1e-30
+    x = x.to(dtype).reshape(-1)
+    rmode = gg.GG_FLOOR if mode == "floor" else gg.GG_NEAREST_EVEN
+    ws = gg.Workspace(rows * cols, rows)
+    res = gg.gg_fused_rows(x, rows, cols, ws, delta_div=8.0, round_mode=rmode, want_total=True)
+    frec, rrec, tot = gg.fit_records(res["fit"]), gg.rate_records(res["rate"]), gg.fit_records(res["total"])[0]
+    hb = host_bits(x)
+
+    def one(r_):
+        xs = hb[r_ * cols:(r_ + 1) * cols]
+        d = float(rrec[r_]["delta"])
+        return oracle.fit(xs), (oracle.quantize_rate(xs, d, round_mode=rmode)[0] if d > 0 and np.isfinite(d) else None)
+
+    for r_, (f, r) in enumerate(parity.oracle_threads(one, range(rows))):
+        check_fit(frec[r_], f, f"row {r_} beta {betas[r_ - r_ % 50]:.3f}")
+        if r is None:
+            assert int(rrec[r_]["flags"]) & gg.GG_F_DEGENERATE, r_
+        else:
+            check_rate(rrec[r_], r, f"row {r_}", entropy=False)
+            assert rrec[r_]["delta"] == np.float32(frec[r_]["alpha"]) / np.float32(8.0)
+    assert int(rrec[5]["flags"]) & gg.GG_F_NONFINITE or int(rrec[5]["flags"]) & gg.GG_F_DEGENERATE
+    if not (np.isnan(tot["sum_abs"]) or np.isinf(tot["sum_abs"])):
+        check_fit(tot, oracle.fit(hb), "whole matrix")
+    else:
+        assert int(tot["flags"]) & gg.GG_F_NONFINITE
+    # the same rows through the general wave-per-row kernel (symbols asked for): the records have to agree
+    res2 = gg.gg_fused_rows(x, rows, cols, ws, delta_div=8.0, round_mode=rmode, want_symbols=True)
+    f2, r2 = gg.fit_records(res2["fit"]), gg.rate_records(res2["rate"])
+    for r_ in range(0, rows, 37):
+        if rrec[r_]["delta"] == r2[r_]["delta"]:
+            for k in ("eg_bits", "u_max", "fl_bits", "flags"):
+                assert rrec[r_][k] == r2[r_][k], (r_, k)
+        assert abs(float(frec[r_]["beta"]) - float(f2[r_]["beta"])) <= 2e-5 * float(f2[r_]["beta"]), r_
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_fit_at_very_small_and_very_large_scales(gg, dtype):
+    """Eq. 3 has no range condition: tensors whose squares underflow or overflow fp32 (values around 1e-25 and 1e25,
+    down to fp32 denormals) are fitted like any other -- every entry point that sums moments, against the oracle."""
+    n = 150_001
+    base = make(n, 1.0, 0.9, seed=77).float()
+    hb_of = lambda t: host_bits(t)
+    ws = gg.Workspace(4 * n, 4)
+    for scale in (1e-25, 1e25, 3e-36, 2e37):
+        x = (base * scale).to(dtype)
+        o = oracle.fit(hb_of(x))
+        assert o.flags == 0 and abs(o.beta - 0.9) < 0.05
+        check_fit(gg.fit_records(gg.gg_fit(x, ws))[0], o, f"tensor x {scale}")
+    # a bucket that mixes the scales (each unit its own), with an ordinary unit between them; the fused one-sweep mode too
+    parts = [base * 1e-25, base[:40_000], base * 1e25, base[:7] * 1e-30]
+    flat = torch.cat(parts).to(dtype)
+    off = np.concatenate([[0], np.cumsum([p_.numel() for p_ in parts])]).astype(np.int64)
+    hb = hb_of(flat)
+    rec = gg.fit_records(gg.gg_fit_segmented(flat, off, ws))
+    for s_ in range(4):
+        check_fit(rec[s_], oracle.fit(hb[off[s_]:off[s_ + 1]]), f"unit {s_}")
+    res = gg.gg_fused_segmented(flat, off, ws, delta_div=16.0)
+    rec2, rrec = gg.fit_records(res["fit"]), gg.rate_records(res["rate"])
+    delta = res["rate"].new_empty(0)
+    for s_ in range(4):
+        check_fit(rec2[s_], oracle.fit(hb[off[s_]:off[s_ + 1]]), f"fused unit {s_}")
+        r, _, _ = oracle.quantize_rate(hb[off[s_]:off[s_ + 1]], float(rrec[s_]["delta"]))
+        check_rate(rrec[s_], r, f"fused unit {s_}", entropy=False)
+    steps = gg.gg_delta_from_fit(res["fit"], 4, 16.0)
+    res1 = gg.gg_fused_segmented(flat, off, ws, delta_div=0.0, delta=steps)          # moments and rate from one sweep
+    rec3 = gg.fit_records(res1["fit"])
+    for s_ in range(4):
+        check_fit(rec3[s_], oracle.fit(hb[off[s_]:off[s_ + 1]]), f"one-sweep unit {s_}")
+    # rows: the general wave-per-row kernel (symbols asked for) and the one that keeps rows in registers
+    rows, cols = 300, 512
+    m = (make(rows * cols, 1.0, 1.3, seed=78).float().reshape(rows, cols) *
+         torch.logspace(-30, 30, rows, device=DEV).reshape(rows, 1)).to(dtype).reshape(-1)
+    hm = hb_of(m)
+    wsr = gg.Workspace(rows * cols, rows)
+    for kw in (dict(want_symbols=True), dict()):
+        fr = gg.fit_records(gg.gg_fused_rows(m, rows, cols, wsr, delta_div=8.0, **kw)["fit"])
+        for r_ in range(rows):
+            check_fit(fr[r_], oracle.fit(hm[r_ * cols:(r_ + 1) * cols]), f"row {r_} {kw}")
+    fr = gg.fit_records(gg.gg_fit_rows(m, rows, cols, wsr))
+    for r_ in range(rows):
+        check_fit(fr[r_], oracle.fit(hm[r_ * cols:(r_ + 1) * cols]), f"fit_rows {r_}")
+
+
 def test_fit_only_and_penalty_only_fused_modes(gg):
     segs = gg_inputs.scaled_layout(gg_inputs.weights_7b()[:9], 2003)
     flat, off, _, _ = gg_inputs.make_bucket(segs, seed=4, device=DEV, dtype=torch.bfloat16, alpha_range=(0.005, 0.03),
