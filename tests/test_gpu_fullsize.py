@@ -76,6 +76,26 @@ def test_gradient_bucket_1p5b_fused_pass(gg):
     assert res2["fit"].cpu().numpy().tobytes() == res["fit"].cpu().numpy().tobytes()
     assert res2["rate"].cpu().numpy().tobytes() == res["rate"].cpu().numpy().tobytes()
 
+    # the same pass with the penalty gradient written in the rate sweep (the sweep runs as 16 KiB blocks then): the
+    # records must not change, and the gradient is checked on every element of layer 13 (9 tensors, 45 M elements)
+    # and of the first 8 M elements of the embedding
+    grad = torch.empty(n, dtype=torch.float32, device=DEV)
+    res3 = gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, eg_k=0, lam=1e-4, grad=grad)
+    assert res3["fit"].cpu().numpy().tobytes() == res["fit"].cpu().numpy().tobytes()
+    assert res3["rate"].cpu().numpy().tobytes() == res["rate"].cpu().numpy().tobytes()
+    for s in [i for i, seg in enumerate(layout) if seg.name.startswith("l13.")] + [S - 1]:
+        lo, hi = int(off[s]), min(int(off[s + 1]), int(off[s]) + (1 << 23))
+        hb = host_bits(flat[lo:hi])
+        got = grad[lo:hi].cpu().numpy()
+        a_s, b_s = frec[s]["alpha"], frec[s]["beta"]
+
+        def piece(p0, hb=hb, got=got, a_s=a_s, b_s=b_s, name=layout[s].name):
+            p1 = min(p0 + (1 << 21), hb.size)
+            check_penalty(got[p0:p1], oracle.penalty_grad(hb[p0:p1], a_s, b_s, 1e-4), f"{name}[{p0}:{p1}]")
+            return p1 - p0
+
+        assert sum(oracle_threads(piece, range(0, hb.size, 1 << 21))) == hi - lo
+
 
 def test_linear_weight_bf16_fit_rate_penalty(gg):
     """4096 x 11008 bf16 weight: fit + rate with Delta = alpha/32 + penalty gradient written as fp32."""
