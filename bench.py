@@ -31,7 +31,7 @@ ALGO_BYTES_PER_ELEM = 8.0      # fp32 bucket: 4 B read by the moment sweep + 4 B
 # Box-Muller, the accept test, the power) -> 302 G attempts/s
 SAMPLER_PEAK_GSAMPLES = 256 * 4 * 16 * 2.4 / 130.0
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
-KERNEL_SOURCES = ("gg_kernels.hip", "gg_train.hip", "gg_device.h", "gg_geometry.h", "gen_solve_curve.py")
+KERNEL_SOURCES = ("gg_kernels.hip", "gg_device.h", "gg_geometry.h", "gen_solve_curve.py")   # what the pass kernels are built from
 CONFIG_NAMES = ("C4_penalty", "C1", "C2", "C3", "C5", "sampler")
 
 

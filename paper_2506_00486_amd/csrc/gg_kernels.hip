@@ -1004,7 +1004,10 @@ __global__ __launch_bounds__(kBlock) void k_quant_parts(SegView sv, const T *__r
 #endif
 constexpr int kHistThreads = GG_HIST_THREADS;
 constexpr int kHistWaves = kHistThreads / 64;
-constexpr int kHistMaxLdsBins = 32768;              // plain layout: private bins (128 KiB)
+#ifndef GG_HIST_MAX_LDS_BINS
+#define GG_HIST_MAX_LDS_BINS 32768
+#endif
+constexpr int kHistMaxLdsBins = GG_HIST_MAX_LDS_BINS;   // plain layout: private bins (128 KiB)
 #ifndef GG_HIST_COPIES
 #define GG_HIST_COPIES 32
 #endif
@@ -1392,8 +1395,11 @@ __global__ __launch_bounds__(kBlock) void k_rows(const T *__restrict__ x, RowsAr
 // rate and nothing to write per element: the wave keeps its row in registers -- NV 16-byte vectors per lane --
 // between the two sweeps, so memory sees every element exactly once whatever the caches hold, and the fit between
 // the sweeps is the fp32-based one (no batching of rows: a fit costs less than a tenth of the row's sweeps).
+#ifndef GG_ROWS_REG_WAVES
+#define GG_ROWS_REG_WAVES 4
+#endif
 template <typename T, int NV, bool NEAREST>
-__global__ __launch_bounds__(kBlock) void k_rows_reg(const T *__restrict__ x, RowsArgs a) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(GG_ROWS_REG_WAVES, 8))) void k_rows_reg(const T *__restrict__ x, RowsArgs a) {
     using E = Elem<T, true>;                       // streaming loads: nothing is read twice
     using Raw = typename E::raw;
     constexpr int W = E::W;
@@ -1421,16 +1427,10 @@ __global__ __launch_bounds__(kBlock) void k_rows_reg(const T *__restrict__ x, Ro
         FitBody fb;
 #pragma unroll
         for (int v = 0; v < NV; ++v) { float e[W]; E::unpack(cur[v], e); fb.vec(e, 0); }
-        double s1, s2;
-        if (fit_sums_left_range(fb.s1, fb.s2)) {   // squares out of the fp32 range: again, in fp64, from the registers
-            FitBody64 wide;
-#pragma unroll
-            for (int v = 0; v < NV; ++v) { float e[W]; E::unpack(cur[v], e); wide.vec(e, 0); }
-            s1 = wide.s1; s2 = wide.s2;
-        } else {
-            s1 = ((double)fb.s1[0] + (double)fb.s1[1]) + ((double)fb.s1[2] + (double)fb.s1[3]);
-            s2 = ((double)fb.s2[0] + (double)fb.s2[1]) + ((double)fb.s2[2] + (double)fb.s2[3]);
-        }
+        // (squares out of the fp32 range: the lane reads its share of the row again and forms them in fp64 -- a loop
+        // that is not unrolled, so that this rare path costs the kernel no registers)
+        double s1 = 0.0, s2 = 0.0;
+        add_lane_moments<E, 64>(fb.s1, fb.s2, x, row * a.cols, len, s1, s2);
         s1 = wave_reduce(s1, OpAdd());
         s2 = wave_reduce(s2, OpAdd());
         gg_fit_t f;
