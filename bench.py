@@ -133,7 +133,7 @@ def other_configs(gg, gg_inputs, torch, dev, args, timer, bucket, want):
         grad = torch.empty(n4, dtype=torch.float32, device=dev)
         med, mean = timer.each(lambda: gg.gg_fused_segmented(flat, off, ws, delta_div=16.0, eg_k=0, fit=fit, rate=rate,
                                                              lam=1e-4, grad=grad), reps)
-        res["C4_bucket_fit_rate_penalty_written"] = entry(n4, med, mean, 12.0, "k_quant<float, rate + penalty>", reps,
+        res["C4_bucket_fit_rate_penalty_written"] = entry(n4, med, mean, 12.0, "k_quant_parts<float, rate + penalty>", reps,
                                                           traffic=measured_traffic("k_quant_c4_penalty"))
         del grad
     if "C1" in want:
@@ -156,7 +156,7 @@ def other_configs(gg, gg_inputs, torch, dev, args, timer, bucket, want):
         o2 = gg.gg_fused_segmented(x, [0, n], w2, delta_div=32.0, lam=1e-4, grad=grad)
         med, mean = timer.each(lambda: gg.gg_fused_segmented(x, [0, n], w2, delta_div=32.0, lam=1e-4, grad=grad,
                                                              fit=o2["fit"], rate=o2["rate"]), 40)
-        res["C2_4096x11008_bf16_fit_rate_penalty"] = entry(n, med, mean, 8.0, "k_quant<bf16, rate + penalty>", 40,
+        res["C2_4096x11008_bf16_fit_rate_penalty"] = entry(n, med, mean, 8.0, "k_quant_parts<bf16, rate + penalty>", 40,
                                                            traffic=measured_traffic("k_quant_c2_penalty"))
         del x, grad
     if "C3" in want:
@@ -173,12 +173,13 @@ def other_configs(gg, gg_inputs, torch, dev, args, timer, bucket, want):
                                                             fit=r0["fit"], total=r0["total"], rate=r0["rate"]), 40)
         h0 = gg.gg_quantize_rate(x, tot_alpha / 8.0, w3, nbins=32768)
         med_h, mean_h = timer.each(lambda: gg.gg_quantize_rate(x, tot_alpha / 8.0, w3, nbins=32768, out=h0[0], hist=h0[1]), 40)
-        res["C3_16384x4096_bf16_rows_fit_rate"] = entry(n, med_r, mean_r, 4.0, "k_rows<bf16, fit + rate>", 40,
+        # rows of 8 KiB stay in registers between the moment sums and the code lengths: the input moves once (2 B/element)
+        res["C3_16384x4096_bf16_rows_fit_rate"] = entry(n, med_r, mean_r, 2.0, "k_rows_reg<bf16, 8 vectors per lane>", 40,
                                                         traffic=measured_traffic("k_rows_c3"))
-        res["C3_tensor_histogram_32768_bins"] = entry(n, med_h, mean_h, 2.0, "k_quant<bf16, rate + histogram>", 40,
+        res["C3_tensor_histogram_32768_bins"] = entry(n, med_h, mean_h, 2.0, "k_hist<bf16>", 40,
                                                       traffic=measured_traffic("k_quant_c3_histogram"))
-        # both calls against the 2 + 2 bytes per element of one moment sweep and one rate sweep
-        res["C3_both_calls"] = entry(n, med_r + med_h, mean_r + mean_h, 4.0, "k_quant<bf16, rate + histogram>", 40)
+        # both calls against the 2 + 2 bytes per element the configuration has to move (each call reads the input once)
+        res["C3_both_calls"] = entry(n, med_r + med_h, mean_r + mean_h, 4.0, "k_rows_reg<bf16> + k_hist<bf16>", 40)
         del x
     if "C5" in want and not args.small:
         # 7B-shaped bf16 weight set, fused fit + penalty accumulated into fp32 (the update step), and written

@@ -544,13 +544,13 @@ __global__ __launch_bounds__(kBlock) void k_eg_encode(Src src, int64_t n, int64_
 // below the word that holds the tile's last bit, whatever the stream contains.
 constexpr int kEgDecStep = 4;      // symbols between top-ups
 // Symbols a lane decodes between writes (ROW of k_eg_decode).  32 symbols of a tile are one 128-byte line per
-// store round: 16 was 10 % slower, 8 and 4 25-80 % (partial lines), 64 15 % (LDS leaves room for fewer waves).
-// The per-unit variant, whose writers also track units, does best at 16.
+// store round, written with streaming stores: 16 is 15-20 % slower, 8 and 4 25-80 % (partial lines), 64 15 % (LDS
+// leaves room for fewer waves).  The per-unit variant takes the same (its own constant for tuning builds).
 #ifndef GG_EG_DEC_ROW
 #define GG_EG_DEC_ROW 32
 #endif
 #ifndef GG_EG_DEC_ROW_UNITS
-#define GG_EG_DEC_ROW_UNITS 16
+#define GG_EG_DEC_ROW_UNITS 32
 #endif
 constexpr int kEgRing = 16;        // ring words per lane
 constexpr int kEgTopUp = 4;        // words a lane loads per top-up
@@ -585,14 +585,22 @@ __device__ __forceinline__ float eg_unit_step(const EgUnits &un, int u) {
     return d > 0.f && isfinite(d) ? d : 0.f;
 }
 
+// -m without signed overflow (a stream that is not a code stream may decode to any 32 bits)
+__device__ __forceinline__ int32_t eg_turn(int32_t m) { return (int32_t)(0u - (uint32_t)m); }
+
 template <int OUT, int ROW>
 __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ stream, const uint64_t *__restrict__ index,
                                                   int64_t n, int64_t tiles, int eg_k, int32_t *__restrict__ q,
                                                   float *__restrict__ xhat, float delta, int accumulate, EgUnits un) {
     __shared__ int tile_unit[64];
-    __shared__ uint32_t ring[kEgRing][64];
+    __shared__ uint32_t ring[kEgRing + 1][64];        // see commit4
     constexpr int kEgLanesPerTile = ROW / 4;          // lanes that write one tile's symbols of a round, 16 bytes each
     constexpr int kEgTilesPerPass = 64 / kEgLanesPerTile;   // tiles one store instruction of the wave covers
+#ifdef GG_EG_DEC_PLAIN_STORES   // tuning builds
+    constexpr bool kStreamOut = false;
+#else
+    constexpr bool kStreamOut = ROW >= 32;
+#endif
     __shared__ int32_t stage[64][ROW + 1];
     const int lane = threadIdx.x;
     const int64_t tile0 = (int64_t)blockIdx.x * 64;
@@ -602,14 +610,22 @@ __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ s
         const int64_t e = tile * GG_EG_TILE;
         tile_unit[lane] = live && e < n ? eg_unit_of(un, e) : 0;
     }
-    int row_unit[kEgLanesPerTile];       // OUT 2: the units the rows this lane writes have reached
+    // OUT 2: the unit each row this lane writes has reached, where that unit ends and its step -- kept in registers,
+    // so that only a group of four elements that reaches the end of its unit goes back to the unit table
+    int row_unit[kEgLanesPerTile];
+    int64_t row_end[kEgLanesPerTile];
+    float row_step[kEgLanesPerTile];
 #pragma unroll
-    for (int r = 0; r < kEgLanesPerTile; ++r) row_unit[r] = -1;
-    const uint64_t pos = live ? index[tile] : 0;
-    const uint64_t end = live ? index[tile + 1] : 0;
-    const uint32_t *src = stream + (pos >> 5);                              // the lane's words, counted from its first
-    const uint32_t end_rel = end > pos ? (uint32_t)(((end + 31u) >> 5) - (pos >> 5)) : 0u;   // words from here on read as zero
-    uint32_t ld = 0, rd = 0;          // words loaded into / taken from the ring; rd <= ld <= rd + kEgRing
+    for (int r = 0; r < kEgLanesPerTile; ++r) { row_unit[r] = -1; row_end[r] = 0; row_step[r] = 0.f; }
+    const uint64_t pos0 = live ? index[tile] : 0;
+    const uint32_t *src = stream + (pos0 >> 5);                             // the lane's words, counted from its first
+    // Words from `end_rel` on read as zero: the stream's words end there (those that hold bits of the indexed tiles).
+    // A lane may load words of the tiles behind its own -- it decodes GG_EG_TILE symbols and no more -- so that only
+    // the loads at the very end of the stream take the word-by-word path below.
+    const uint64_t stream_words = (index[tiles] + 31u) >> 5, first_word = pos0 >> 5;
+    const uint64_t left = live && stream_words > first_word ? stream_words - first_word : 0u;
+    const uint32_t end_rel = left < 0x7fffffffu ? (uint32_t)left : 0x7fffffffu;
+    uint32_t ld = 0;                  // words loaded into the ring so far (a multiple of kEgTopUp)
     // four words from the lane's position `ld` on (a 16-byte load from a 4-byte-aligned address)
     auto fetch4 = [&]() -> EgWords4 {
         EgWords4 w = {0u, 0u, 0u, 0u};
@@ -622,65 +638,72 @@ __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ s
         }
         return w;
     };
+    // word i of the lane lives in slot kEgRing - (i mod kEgRing), so that a word and its successor are read as one
+    // 64-bit value with the earlier word on top; words 0, kEgRing, ... are kept in slot 0 as well (no wrap in a window)
     auto commit4 = [&](EgWords4 w) {
-        ring[ld & (kEgRing - 1)][lane] = __builtin_bswap32(w.x);
-        ring[(ld + 1) & (kEgRing - 1)][lane] = __builtin_bswap32(w.y);
-        ring[(ld + 2) & (kEgRing - 1)][lane] = __builtin_bswap32(w.z);
-        ring[(ld + 3) & (kEgRing - 1)][lane] = __builtin_bswap32(w.w);
+        const uint32_t slot = kEgRing - (ld & (kEgRing - 1)), first = __builtin_bswap32(w.x);
+        ring[slot][lane] = first;
+        ring[slot - 1][lane] = __builtin_bswap32(w.y);
+        ring[slot - 2][lane] = __builtin_bswap32(w.z);
+        ring[slot - 3][lane] = __builtin_bswap32(w.w);
+        if (slot == kEgRing) ring[0][lane] = first;
         ld += kEgTopUp;
     };
 #pragma unroll 1
     for (int r = 0; r < kEgRing / kEgTopUp; ++r) commit4(fetch4());       // fill the ring
 
-    // `win` holds the next `avail` (33..64) bits of the stream, earliest on top; `ahead` is the word after them
-    uint64_t win = ((uint64_t)ring[0][lane] << 32) | (uint64_t)ring[1][lane];
-    win <<= (uint32_t)(pos & 31u);
-    uint32_t avail = 64u - (uint32_t)(pos & 31u);
-    uint32_t ahead = ring[2][lane];
-    rd = 3;
-    // branch-free: in nearly every step some lane of the wave needs a word, so all take the same path
-    auto refill = [&]() {
-        const bool take = avail <= 32u;
-        const uint64_t more_bits = (uint64_t)ahead << (32u - (take ? avail : 32u));
-        win |= take ? more_bits : 0ull;
-        avail += take ? 32u : 0u;
-        const uint32_t nxt = ring[rd & (kEgRing - 1)][lane];   // used only when the slot is loaded (rd < ld)
-        ahead = take ? nxt : ahead;
-        rd += take ? 1u : 0u;
+    // The lane's position in its part of the stream is one number, `pos` (bits from the start of its first word); the
+    // 32 bits from any position on are two neighbouring ring words shifted together, so a symbol costs no window
+    // upkeep: count the zeros, cut the value out of the same 32 bits, move on.  Words below pos / 32 are spent.
+    uint32_t pos = (uint32_t)(pos0 & 31u);
+    auto bits32 = [&](uint32_t at) -> uint32_t {
+        const uint32_t *p = &ring[(kEgRing - 1) - ((at >> 5) & (uint32_t)(kEgRing - 1))][lane];   // the successor's slot
+        const uint64_t two = ((uint64_t)p[64] << 32) | (uint64_t)p[0];
+        return (uint32_t)((two << (at & 31u)) >> 32);
     };
 
-    const uint32_t add = 1u << eg_k;
+    const uint32_t add = 1u << eg_k, k1 = (uint32_t)eg_k + 1u;
+    const bool adding = OUT != 0 && accumulate && n >= 4;
     for (int s0 = 0; s0 < GG_EG_TILE; s0 += ROW) {
+        // adding to what is there: the values this round's writers will add to start travelling now, while the
+        // round's symbols are decoded (a writer past the end of the data asks for elements 0..3 and drops them)
+        gg_f4 was[kEgLanesPerTile];
+        if constexpr (OUT != 0) {
+            if (adding) {
+#pragma unroll
+                for (int r = 0; r < kEgLanesPerTile; ++r) {
+                    const int row = r * kEgTilesPerPass + lane / kEgLanesPerTile, c = (lane % kEgLanesPerTile) * 4;
+                    const int64_t g = (tile0 + row) * GG_EG_TILE + s0 + c;
+                    const gg_f4 *from = reinterpret_cast<const gg_f4 *>(xhat + (g + 4 <= n ? g : 0));
+                    if constexpr (kStreamOut) was[r] = __builtin_nontemporal_load(from);
+                    else was[r] = *from;
+                }
+            }
+        }
 #pragma unroll
         for (int s1 = 0; s1 < ROW; s1 += kEgDecStep) {
-            while (__any(ld - rd < (uint32_t)kEgStepWords)) {          // rare: only streams with very long codes
-                if (ld - rd < (uint32_t)kEgStepWords) commit4(fetch4());
+            while (__any(ld - (pos >> 5) < (uint32_t)kEgStepWords)) {          // rare: only streams with very long codes
+                if (ld - (pos >> 5) < (uint32_t)kEgStepWords) commit4(fetch4());
             }
-            const bool more = ld - rd <= (uint32_t)(kEgRing - kEgTopUp);   // room for four more whatever this step takes
+            const bool more = ld - (pos >> 5) <= (uint32_t)(kEgRing - kEgTopUp);   // room for four more whatever this step takes
             EgWords4 pre = {0u, 0u, 0u, 0u};
             if (more) pre = fetch4();
             // lanes past the end of the data decode zeros or stale bits; nothing of that is written
 #pragma unroll
             for (int j = 0; j < kEgDecStep; ++j) {
-                const uint32_t top = (uint32_t)(win >> 32);
-                uint32_t zeros = top ? (uint32_t)__builtin_clz(top) : 31u;
+                const uint32_t top = bits32(pos);
+                uint32_t zeros = (uint32_t)__clz((int)top);         // 32 for no bit at all
                 zeros = zeros > 31u ? 31u : zeros;                  // a valid stream has at most 31
-                uint32_t L = zeros + (uint32_t)eg_k + 1u;
+                uint32_t L = zeros + k1;
                 L = L > 32u ? 32u : L;
+                const uint32_t total = zeros + L;
                 uint32_t v;
-                if (__any(zeros + L > 32u)) {       // some lane's code does not fit the 32 bits that are sure to be there
-                    win <<= zeros; avail -= zeros;
-                    refill();
-                    v = (uint32_t)(win >> 32) >> (32u - L);
-                    win <<= L; avail -= L;
-                } else {
-                    v = (top << zeros) >> (32u - L);
-                    win <<= zeros + L; avail -= zeros + L;
-                }
-                refill();
+                if (__any(total > 32u)) v = bits32(pos + zeros) >> (32u - L);   // some lane's code does not end within these 32 bits
+                else v = (top << zeros) >> (32u - L);
+                pos += total;
                 const uint32_t u = v - add;
-                // inverse Map: odd -> positive (u+1)/2, even -> negative -u/2
-                stage[lane][s1 + j] = (u & 1u) ? (int32_t)((u >> 1) + 1u) : -(int32_t)(u >> 1);
+                // inverse Map, negated: -q is the zig-zag decoding of u (the writers below turn the sign)
+                stage[lane][s1 + j] = (int32_t)(u >> 1) ^ -(int32_t)(u & 1u);
             }
             if (more) commit4(pre);
         }
@@ -695,36 +718,40 @@ __global__ __launch_bounds__(64) void k_eg_decode(const uint32_t *__restrict__ s
                 float d[4] = {delta, delta, delta, delta};
                 if constexpr (OUT == 2) {
                     if (g < n) {
-                        if (row_unit[r] < 0) row_unit[r] = tile_unit[row];
-                        int u = row_unit[r];
-                        eg_unit_seek(un, u, g);
-                        row_unit[r] = u;
-                        d[0] = eg_unit_step(un, u);
-                        if (u + 1 >= un.S || g + 4 <= un.off[u + 1]) {
-                            d[1] = d[0]; d[2] = d[0]; d[3] = d[0];          // the four elements share a unit
+                        if (g + 4 <= row_end[r]) {                          // the four elements lie in the row's unit
+                            d[0] = row_step[r]; d[1] = d[0]; d[2] = d[0]; d[3] = d[0];
                         } else {
-                            for (int x = 1; x < 4; ++x) { eg_unit_seek(un, u, g + x); d[x] = eg_unit_step(un, u); }
+                            int u = row_unit[r] < 0 ? tile_unit[row] : row_unit[r];
+                            for (int x = 0; x < 4; ++x) { eg_unit_seek(un, u, g + x); d[x] = eg_unit_step(un, u); }
+                            row_unit[r] = u;                                // the unit of element g + 3: later groups start behind it
+                            row_end[r] = u + 1 < un.S ? un.off[u + 1] : 0x7fffffffffffffffLL;
+                            row_step[r] = d[3];
                         }
                     }
                 }
                 if (g + 4 <= n) {
-                    gg_f4 val = {(float)stage[row][c] * d[0], (float)stage[row][c + 1] * d[1], (float)stage[row][c + 2] * d[2],
-                                 (float)stage[row][c + 3] * d[3]};
+                    gg_f4 val = {(float)eg_turn(stage[row][c]) * d[0], (float)eg_turn(stage[row][c + 1]) * d[1], (float)eg_turn(stage[row][c + 2]) * d[2],
+                                 (float)eg_turn(stage[row][c + 3]) * d[3]};
                     gg_f4 *dst = reinterpret_cast<gg_f4 *>(xhat + g);
-                    if (accumulate) val += *dst;
-                    *dst = val;
+                    // streaming accesses where a round writes whole 128-byte lines: what is written here is not read
+                    // again by this kernel, and the cache is better spent on the stream lines, which every lane comes
+                    // back to eight times
+                    if (adding) val += was[r];
+                    if constexpr (kStreamOut) __builtin_nontemporal_store(val, dst);
+                    else *dst = val;
                 } else {
                     for (int x = 0; x < 4; ++x)
                         if (g + x < n) {
-                            const float val = (float)stage[row][c + x] * d[x];
+                            const float val = (float)eg_turn(stage[row][c + x]) * d[x];
                             xhat[g + x] = accumulate ? xhat[g + x] + val : val;
                         }
                 }
             } else if (g + 4 <= n) {
-                const gg_i4 val = {stage[row][c], stage[row][c + 1], stage[row][c + 2], stage[row][c + 3]};
-                *reinterpret_cast<gg_i4 *>(q + g) = val;
+                const gg_i4 val = {eg_turn(stage[row][c]), eg_turn(stage[row][c + 1]), eg_turn(stage[row][c + 2]), eg_turn(stage[row][c + 3])};
+                if constexpr (kStreamOut) __builtin_nontemporal_store(val, reinterpret_cast<gg_i4 *>(q + g));
+                else *reinterpret_cast<gg_i4 *>(q + g) = val;
             } else {
-                for (int x = 0; x < 4; ++x) if (g + x < n) q[g + x] = stage[row][c + x];
+                for (int x = 0; x < 4; ++x) if (g + x < n) q[g + x] = eg_turn(stage[row][c + x]);
             }
         }
         __syncthreads();
