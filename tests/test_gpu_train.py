@@ -177,6 +177,31 @@ def test_eg_stream_extreme_symbols_and_tight_capacity(gg):
     assert total > 64 * 8 and stream.numel() == 64
 
 
+def test_eg_decode_of_bytes_that_are_no_code_stream(gg):
+    # What the decoder reads and writes does not depend on what the stream holds: under the index of a real stream,
+    # bytes that are no code stream (random, all zero = endless prefixes, all one = shortest codes) decode to
+    # something, the call returns, and nothing but the n outputs is written.
+    n = 70 * gg.GG_EG_TILE + 19
+    rng = np.random.default_rng(11)
+    q = torch.tensor(rng.integers(-300, 301, size=n).astype(np.int32), device=DEV)
+    for k in (0, 3):
+        stream, index, total = gg.gg_eg_encode(q, eg_k=k)
+        fills = [torch.tensor(rng.integers(0, 256, size=stream.numel()).astype(np.uint8), device=DEV),
+                 torch.zeros_like(stream), torch.full_like(stream, 0xFF)]
+        for other in fills:
+            buf = torch.full((n + 256,), 12345, dtype=torch.int32, device=DEV)
+            gg.gg_eg_decode(other, index, n, eg_k=k, out=buf[:n])
+            fbuf = torch.full((n + 256,), 7.0, dtype=torch.float32, device=DEV)
+            gg.gg_eg_decode_dequant(other, index, n, 0.5, eg_k=k, out=fbuf[:n], accumulate=True)
+            torch.cuda.synchronize()
+            assert bool((buf[n:] == 12345).all()) and bool((fbuf[n:] == 7.0).all())
+        # with k = 0 a one bit is the whole code of u = 0, so all-one bytes decode to zeros from a tile's first bit on
+        if k == 0:
+            ones = gg.gg_eg_decode(fills[2], index, n, eg_k=0)
+            assert bool((ones[: gg.GG_EG_TILE] == 0).all())
+        assert torch.equal(gg.gg_eg_decode(stream, index, n, eg_k=k), q)     # and the real stream still decodes
+
+
 def test_eg_stream_truncated_by_capacity(gg):
     # the stream buffer ends inside the data: every packing tile (2048 symbols) that fits is written whole,
     # wherever the cut falls relative to the groups of four tiles a workgroup packs
