@@ -624,7 +624,7 @@ struct QuantBody {
     // u_max follows from the extremes of r = -q, since Map grows with |q| on either side of zero.
     static constexpr bool kNearest = (MODE & 1) != 0;
     static constexpr bool kExp0 = (MODE & 2) != 0;
-    static_assert(!kExp0 || (RATE && !EXTRA && !PEN), "the exponent path serves the lean rate-only kernels");
+    static_assert(!kExp0 || (RATE && !EXTRA), "the exponent path forms no integer symbol: nothing to count in bins or to store");
     uint32_t exp_sum = 0;
     float r_max = 0.f, r_min = 0.f;      // 0 is neutral: Map(0) = 0
 
@@ -955,8 +955,9 @@ __global__ __launch_bounds__(kBlock) void k_quant_parts(SegView sv, const T *__r
         body.pen_coef = P.pen_coef; body.pen_live = !(P.flags & kPenZero);
         if constexpr (sizeof(T) == 2) process_chunk<ElemBf16x4, 4>(x, start, len, body);
         else process_chunk<Elem<T>, 4>(x, start, len, body);
-        lsum = wave_reduce(body.clz_sum, OpAdd());       // at most 4096 x 32: fits 32 bits
-        um = wave_reduce(body.u_max, OpMax());
+        // at most 4096 x 32 (leading zeros) or 4096 x 157 (exponents): fits 32 bits
+        lsum = wave_reduce(decltype(body)::kExp0 ? body.exp_sum : body.clz_sum, OpAdd());
+        um = wave_reduce(decltype(body)::kExp0 ? body.exp0_u_max() : body.u_max, OpMax());
         nan = wave_reduce((uint32_t)body.nan_seen, OpOr());
     }
     if ((tid & 63) == 0) { red[0][tid >> 6] = lsum; red[1][tid >> 6] = um; red[2][tid >> 6] = nan; }
@@ -967,7 +968,8 @@ __global__ __launch_bounds__(kBlock) void k_quant_parts(SegView sv, const T *__r
             uint32_t l = 0, m = 0, f = 0;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) { l += red[0][w]; m = red[1][w] > m ? red[1][w] : m; f |= red[2][w]; }
-            v.bits = (uint32_t)len * a.eg_const - 2u * l;
+            // sum of 63 - k - 2 clz(u + 2^k), or with k = 0 on the exponent path of 2 e - 251
+            v.bits = (MODE & 2) ? 2u * l - 251u * (uint32_t)len : (uint32_t)len * a.eg_const - 2u * l;
             v.u_max = m;
             v.flags = (f ? GG_F_NONFINITE : 0u) | (m >= 2147483647u ? GG_F_SATURATED : 0u);
         }
@@ -1949,7 +1951,8 @@ static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hip
 template <typename T, int MODE>
 static int launch_quant_mode(const Geometry &g, const void *x, QuantOpts &o, hipStream_t st) {
     const bool extra = o.hist || o.symbols;
-    if constexpr ((MODE & 2) != 0) {   // exponent path: the lean rate-only kernels
+    if constexpr ((MODE & 2) != 0) {   // exponent path: rate sums without the integer symbol, with or without the penalty
+        if (o.pen) return launch_quant_inst<T, MODE, true, true, false>(g, x, o, st);
         if (o.fit_too) return launch_quant_inst<T, MODE, true, false, false, true>(g, x, o, st);
         return launch_quant_inst<T, MODE, true, false, false>(g, x, o, st);
     } else {
@@ -2028,7 +2031,7 @@ static int launch_quant(const Geometry &g, const void *x, int dtype, QuantOpts &
 #ifdef GG_NO_EXP0   // tuning builds
         const bool exp0 = false;
 #else
-        const bool exp0 = o.eg_k == 0 && !o.hist && !o.symbols && !o.pen;
+        const bool exp0 = o.eg_k == 0 && !o.hist && !o.symbols;
 #endif
         if (o.round_mode == GG_FLOOR) return exp0 ? launch_quant_mode<T, 2>(g, x, o, st) : launch_quant_mode<T, 0>(g, x, o, st);
         return exp0 ? launch_quant_mode<T, 3>(g, x, o, st) : launch_quant_mode<T, 1>(g, x, o, st);

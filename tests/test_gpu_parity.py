@@ -197,6 +197,15 @@ def test_lean_rate_kernel_matches_integer_path(gg, dtype, mode):
         r, _, _ = oracle.quantize_rate(host_bits(x), delta, eg_k=0, round_mode=mode)
         check_rate(a, r, f"lean delta={delta}", entropy=False)
         check_rate(b, r, f"full delta={delta}", entropy=False)
+        # the sweep that also writes the penalty gradient takes the exponent path too (short blocks, a slot each)
+        n = x.numel()
+        grad = torch.empty(n, dtype=torch.float32, device=DEV)
+        out = gg.gg_fused_segmented(x, [0, n], ws, delta_div=0.0, delta=torch.tensor([delta], dtype=torch.float32, device=DEV),
+                                    eg_k=0, round_mode=mode, lam=1e-3, grad=grad)
+        check_rate(gg.rate_records(out["rate"])[0], r, f"with penalty delta={delta}", entropy=False)
+        f = gg.fit_records(out["fit"])[0]
+        want = oracle.penalty_grad(host_bits(x), float(f["alpha"]), float(f["beta"]), 1e-3)
+        check_penalty(grad.cpu().numpy(), want, f"penalty beside the lean rate, delta={delta}")
 
 
 def test_solver_alone_from_the_kernel_s_own_moments(gg):
