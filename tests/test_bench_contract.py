@@ -39,3 +39,29 @@ def test_small_run_prints_one_json_line_with_roofline_and_cpu_baseline():
     for key in ("value", "unit", "cores", "kind", "sample"):
         assert key in cpu, key
     assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1
+
+
+def test_counter_traffic_is_quoted_only_for_the_sources_it_was_measured_on(tmp_path, monkeypatch):
+    # `roofline.traffic` comes from the counter summary under profiles/: a line counts when its fingerprint is that of
+    # the kernel sources in the tree, and any other line (or a missing file) gives None -- never a stale figure
+    sys.path.insert(0, ROOT)
+    import bench
+    now = bench.kernel_source_hash()
+    assert len(now) == 16 and now == bench.kernel_source_hash()
+    summary = tmp_path / "hbm_traffic.md"
+    summary.write_text("some text\n"
+                       "traffic k_a fetch_bytes=1000 write_bytes=24 sources=%s\n"
+                       "traffic k_b fetch_bytes=5 write_bytes=6 sources=0123456789abcdef\n" % now)
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(summary))
+    assert bench.measured_traffic("k_a") == 1024
+    assert bench.measured_traffic("k_b") is None          # measured on other sources
+    assert bench.measured_traffic("k_c") is None          # no such line
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(tmp_path / "absent.md"))
+    assert bench.measured_traffic("k_a") is None
+    # the tracked summary parses: every line has the four fields
+    import re
+    text = open(os.path.join(ROOT, "profiles", "hbm_traffic.md")).read()
+    lines = [ln for ln in text.splitlines() if ln.startswith("traffic ")]
+    assert len(lines) >= 8
+    for ln in lines:
+        assert re.match(r"^traffic\s+\S+\s+fetch_bytes=\d+\s+write_bytes=\d+\s+sources=\w{16}$", ln), ln
