@@ -200,7 +200,7 @@ constexpr int64_t kMaxRuns = 256 * 512;  // most blocks a reducing sweep is spli
 // A rate sweep that also writes a stream (penalty gradient, symbols) runs as short blocks, kStreamParts per
 // chunk, like the element-wise sweeps; every such block leaves its sums in a slot of its own (block index =
 // chunk * kStreamParts + part), and one workgroup per unit folds the unit's slots, which are consecutive.
-struct PartSlot { uint32_t bits, u_max, flags, _pad; };
+struct PartSlot { uint32_t bits, u_max, flags, n_clamped; };   // n_clamped: symbols past the last bin (with a histogram)
 static_assert(sizeof(PartSlot) == 16, "one 16-byte store");
 #ifndef GG_STREAM_PARTS
 #define GG_STREAM_PARTS 4                // 4096 elements per block = 256 lanes x 4 loads x 4 elements

@@ -934,9 +934,13 @@ __global__ __launch_bounds__(kBlock) void k_quant(SegView sv, const T *__restric
 // a stream that writes as much as it reads moves fastest in blocks of 16 KiB, all loads of a block issued at
 // once (a plain copy: 5.8 TB/s against 5.1-5.4 TB/s for 64 KiB per block or resident runs on MI355X).  Block
 // chunk * parts + part takes part `part` of chunk `chunk` and leaves its sums in slot [blockIdx.x].
-template <typename T, int MODE, bool PEN, bool SYM>
+// With HIST the block also counts its symbols in private LDS bins and adds the bins it touched to the unit's histogram
+// when it ends: the shape for tensors of a few chunks, where one block per chunk would leave most of the machine idle
+// (a 4 MB tensor is 64 chunks for 256 compute units) and each block would be a chain of four load rounds.
+template <typename T, int MODE, bool PEN, bool SYM, bool HIST = false>
 __global__ __launch_bounds__(kBlock) void k_quant_parts(SegView sv, const T *__restrict__ x, QuantArgs a) {
-    __shared__ uint32_t red[3][kWaves];
+    extern __shared__ uint32_t lds_hist[];
+    __shared__ uint32_t red[5][kWaves];
     const int tid = threadIdx.x;
     const int64_t chunk = blockIdx.x / a.parts;
     if (chunk >= a.n_chunks) return;
@@ -945,12 +949,22 @@ __global__ __launch_bounds__(kBlock) void k_quant_parts(SegView sv, const T *__r
     const bool rate_live = !(P.flags & kSkipRate);
     int64_t start; int len;
     const bool any = chunk_part(L.start, L.len, (int)(blockIdx.x - chunk * a.parts), a.parts, start, len);
-    uint32_t lsum = 0, um = 0, nan = 0;
+    if constexpr (HIST) {
+        for (int b = tid; b < a.lbins; b += kBlock) lds_hist[b] = 0;
+        __syncthreads();
+    }
+    uint32_t lsum = 0, um = 0, nan = 0, ncl = 0, nlast = 0;
+    uint64_t *ghist = HIST ? a.hist + (int64_t)L.seg * a.nbins : nullptr;
     if (any) {                                 // uniform over the block
-        QuantBody<MODE, true, PEN, SYM> body;
+        QuantBody<MODE, true, PEN, SYM || HIST> body;
         body.eg_add = a.eg_add;
         body.symbols = a.symbols; body.grad = a.grad; body.accumulate = a.accumulate;
         body.lds_hist = nullptr; body.ghist = nullptr; body.last_bin = 0; body.lbins = 0; body.hist_live = false;
+        if constexpr (HIST) {
+            body.lds_hist = lds_hist; body.ghist = ghist; body.last_bin = (uint32_t)(a.nbins - 1); body.lbins = (uint32_t)a.lbins;
+            body.hist_live = rate_live;
+            body.fast_lim = rate_live ? (body.lbins < body.last_bin ? body.lbins : body.last_bin) : 0u;
+        }
         body.inv_delta = P.inv_delta; body.inv_alpha = P.inv_alpha; body.beta_m1 = P.beta_m1;
         body.pen_coef = P.pen_coef; body.pen_live = !(P.flags & kPenZero);
         if constexpr (sizeof(T) == 2) process_chunk<ElemBf16x4, 4>(x, start, len, body);
@@ -959,21 +973,49 @@ __global__ __launch_bounds__(kBlock) void k_quant_parts(SegView sv, const T *__r
         lsum = wave_reduce(decltype(body)::kExp0 ? body.exp_sum : body.clz_sum, OpAdd());
         um = wave_reduce(decltype(body)::kExp0 ? body.exp0_u_max() : body.u_max, OpMax());
         nan = wave_reduce((uint32_t)body.nan_seen, OpOr());
+        if constexpr (HIST) {
+            ncl = wave_reduce(body.n_clamped, OpAdd());
+            nlast = wave_reduce(body.n_last, OpAdd());
+        }
     }
-    if ((tid & 63) == 0) { red[0][tid >> 6] = lsum; red[1][tid >> 6] = um; red[2][tid >> 6] = nan; }
-    __syncthreads();
+    if ((tid & 63) == 0) {
+        red[0][tid >> 6] = lsum; red[1][tid >> 6] = um; red[2][tid >> 6] = nan;
+        if constexpr (HIST) { red[3][tid >> 6] = ncl; red[4][tid >> 6] = nlast; }
+    }
+    __syncthreads();                           // also: every increment of the private bins is done
+    uint32_t m = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) m = red[1][w] > m ? red[1][w] : m;
     if (tid == 0) {
         PartSlot v{0u, 0u, 0u, 0u};
         if (any && rate_live) {
-            uint32_t l = 0, m = 0, f = 0;
+            uint32_t l = 0, f = 0, c = 0, nl = 0;
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) { l += red[0][w]; m = red[1][w] > m ? red[1][w] : m; f |= red[2][w]; }
+            for (int w = 0; w < kWaves; ++w) {
+                l += red[0][w]; f |= red[2][w];
+                if constexpr (HIST) { c += red[3][w]; nl += red[4][w]; }
+            }
             // sum of 63 - k - 2 clz(u + 2^k), or with k = 0 on the exponent path of 2 e - 251
             v.bits = (MODE & 2) ? 2u * l - 251u * (uint32_t)len : (uint32_t)len * a.eg_const - 2u * l;
             v.u_max = m;
             v.flags = (f ? GG_F_NONFINITE : 0u) | (m >= 2147483647u ? GG_F_SATURATED : 0u);
+            v.n_clamped = c;
+            if constexpr (HIST) {              // the clamping bin: counted per lane, added once per block
+                if (nl) atomicAdd(reinterpret_cast<unsigned long long *>(&ghist[a.nbins - 1]), (unsigned long long)nl);
+            }
         }
         a.part_slots[blockIdx.x] = v;
+    }
+    if constexpr (HIST) {
+        if (any && rate_live) {                // bins above the largest symbol this block saw are still zero
+            const int touched = m < (uint32_t)a.lbins ? (int)m + 1 : a.lbins;
+#ifndef GG_HIST_PARTS_NOMERGE   // tuning builds (timing only: wrong counts)
+            for (int b = tid; b < touched; b += kBlock) {
+                const uint32_t c = lds_hist[b];
+                if (c) atomicAdd(reinterpret_cast<unsigned long long *>(&ghist[b]), (unsigned long long)c);
+            }
+#endif
+        }
     }
 }
 
@@ -1173,10 +1215,6 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(SegView sv, const T *__re
     int64_t last = first + a.chunks_per_block;
     if (last > a.n_chunks) last = a.n_chunks;
     if (first >= last) return;
-#ifdef GG_HIST_DEBUG
-    const uint64_t t_in = wall_clock64();
-    uint64_t t_probe = 0, t_sweep = 0;
-#endif
     const uint32_t last_bin = (uint32_t)(a.nbins - 1);
     const uint32_t fast_plain = (uint32_t)a.lbins < last_bin ? (uint32_t)a.lbins : last_bin;
     const uint32_t fast_cols = (uint32_t)a.cbins < last_bin ? (uint32_t)a.cbins : last_bin;
@@ -1235,14 +1273,8 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(SegView sv, const T *__re
 #ifdef GG_HIST_FORCE_COLUMNS
             columns = fast_cols > 0;
 #endif
-#ifdef GG_HIST_DEBUG
-            t_probe = wall_clock64();
-#endif
             if (columns) hist_sub_piece<T, NEAREST, 4 * kHistCopies>(walk, a, pc, lds_hist, fast_cols, red64, red);
             else hist_sub_piece<T, NEAREST, 4>(walk, a, pc, lds_hist, fast_plain, red64, red);
-#ifdef GG_HIST_DEBUG
-            t_sweep = wall_clock64();
-#endif
             if (tid == 0) {
                 uint64_t tb = 0; uint32_t tu = 0, tn = 0, tc = 0, tl = 0;
                 for (int w = 0; w < kHistWaves; ++w) {
@@ -1271,12 +1303,6 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(SegView sv, const T *__re
             __syncthreads();                                  // the reduction slots and the (cleared) counters are free again
         }
     }
-#ifdef GG_HIST_DEBUG
-    if (tid == 0 && (blockIdx.x % 64) == 0)
-        printf("block %3d: enter %llu | loads + clear + layout +%llu | count+merge +%llu | record +%llu (x10 ns)\n", (int)blockIdx.x,
-               (unsigned long long)t_in, (unsigned long long)(t_probe - t_in),
-               (unsigned long long)(t_sweep - t_probe), (unsigned long long)(wall_clock64() - t_sweep));
-#endif
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1583,7 +1609,9 @@ __device__ __forceinline__ void fold_part_slots(const PartSlot *__restrict__ slo
             v[k] = j < i1 ? p[j] : gg_u4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) { acc.bits += v[k].x; acc.u_max = v[k].y > acc.u_max ? v[k].y : acc.u_max; acc.flags |= v[k].z; }
+        for (int k = 0; k < 8; ++k) {
+            acc.bits += v[k].x; acc.u_max = v[k].y > acc.u_max ? v[k].y : acc.u_max; acc.flags |= v[k].z; acc.n_clamped += v[k].w;
+        }
     }
 }
 
@@ -1640,7 +1668,8 @@ constexpr int kFinalizeSplitMax = 8;
 __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, const RatePiece *__restrict__ pieces, int32_t cpb,
                                                                     gg_rate_t *__restrict__ rate,
                                                                     const uint64_t *__restrict__ hist, int32_t nbins,
-                                                                    SegParam *__restrict__ params, double *__restrict__ parts, int split) {
+                                                                    SegParam *__restrict__ params, double *__restrict__ parts, int split,
+                                                                    const PartSlot *__restrict__ slots, int32_t slot_parts) {
     __shared__ double red[kFinalizeThreads / 64];
     __shared__ uint64_t red_bits[kFinalizeThreads / 64], red_ncl[kFinalizeThreads / 64];
     __shared__ uint32_t red_u[2][kFinalizeThreads / 64];
@@ -1651,10 +1680,12 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_rate_finalize(SegView sv, 
     const bool live = n > 0 && !(flags & GG_F_DEGENERATE);
     const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
     const int64_t r0 = c1 > c0 ? c0 / cpb : 0, r1 = c1 > c0 ? (c1 - 1) / cpb : 0;
-    const bool shared = live && r0 < r1;           // uniform over the block
+    // a sweep of short blocks left a slot per block (slot_parts of them per chunk): every unit is folded from those
+    const bool shared = live && (slot_parts > 0 ? c1 > c0 : r0 < r1);           // uniform over the block
     if (shared) {                                  // every workgroup of the unit folds the slots: it needs the largest symbol
         PieceSum t;
-        for (int64_t run = r0 + tid; run <= r1; run += kFinalizeThreads) t.add(piece_slot(pieces, run, cpb, c0));
+        if (slot_parts > 0) fold_part_slots<kFinalizeThreads>(slots, c0 * slot_parts, c1 * slot_parts, tid, t);
+        else for (int64_t run = r0 + tid; run <= r1; run += kFinalizeThreads) t.add(piece_slot(pieces, run, cpb, c0));
         t.bits = wave_reduce(t.bits, OpAdd());
         t.u_max = wave_reduce(t.u_max, OpMax());
         t.n_clamped = wave_reduce(t.n_clamped, OpAdd());
@@ -1902,6 +1933,16 @@ struct QuantOpts {
 #define GG_LDS_BINS 12288
 #endif
 constexpr int kMaxLdsBins = GG_LDS_BINS;   // block-private bins (4 bytes each); higher symbols go to atomics on the unit's histogram
+#ifndef GG_HIST_PARTS_MAX_CHUNKS
+#define GG_HIST_PARTS_MAX_CHUNKS 192       // up to 3 M elements: histogram (+ symbols / penalty) as short blocks (equal at 4 M, slower from 8 M)
+#endif
+constexpr int64_t kHistPartsMaxChunks = GG_HIST_PARTS_MAX_CHUNKS;
+#ifndef GG_HIST_PARTS
+#define GG_HIST_PARTS 2
+#endif
+constexpr int kHistParts = GG_HIST_PARTS;  // blocks per chunk there (at most kStreamParts: the slot area is sized for that)
+static_assert(kHistParts >= 1 && kHistParts <= kStreamParts, "slots");
+constexpr int kHistPartsLdsBins = 4096;    // private bins of such a block (cleared and merged per 4096 elements)
 
 template <typename T, int MODE, bool RATE, bool PEN, bool EXTRA, bool FIT = false>
 static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hipStream_t st) {
@@ -1920,6 +1961,20 @@ static int launch_quant_inst(const Geometry &g, const void *x, QuantOpts &o, hip
     // that reduce keep one run per resident block (their per-block epilogue costs more than the balance gains).
     RunSplit rs;
     a.parts = 1;
+    if constexpr (RATE && !FIT && EXTRA) {
+        // a histogram over a few chunks only (a tensor of some megabytes): short blocks with private bins, or one
+        // block per chunk would leave most of the compute units idle
+        if (lds > 0 && g.n_chunks <= kHistPartsMaxChunks) {
+            a.parts = kHistParts;
+            a.part_slots = g.ws ? g.part_slots() : nullptr;
+            if (!a.part_slots) return GG_ERR_WORKSPACE;
+            if (a.lbins > kHistPartsLdsBins) a.lbins = kHistPartsLdsBins;
+            o.parts_out = a.parts;
+            hipLaunchKernelGGL((k_quant_parts<T, MODE, PEN, true, true>), dim3((unsigned)(g.n_chunks * a.parts)), dim3(kBlock),
+                               (size_t)a.lbins * sizeof(uint32_t), st, g.sv, static_cast<const T *>(x), a);
+            return check_launch();
+        }
+    }
     if constexpr (RATE && !FIT && (PEN || EXTRA)) {
         if (lds == 0) {              // rate sums and a written stream, no histogram: short blocks, one slot each
             a.parts = kStreamParts;
@@ -2053,7 +2108,8 @@ static int launch_rate_finalize(const Geometry &g, gg_rate_t *rate, const uint64
             if ((size_t)g.S * split * sizeof(double) > g.wl.partials_bytes) split = 1;
         }
         hipLaunchKernelGGL(k_rate_finalize, dim3((unsigned)(g.S * split)), dim3(kFinalizeThreads), 0, st, g.sv, g.rate_pieces(), cpb,
-                           rate, hist, nbins, g.params(), reinterpret_cast<double *>(g.partials()), split);
+                           rate, hist, nbins, g.params(), reinterpret_cast<double *>(g.partials()), split,
+                           parts > 0 ? g.part_slots() : nullptr, parts);
         return check_launch();
     }
     if (parts > 0) {                                     // short blocks: every unit's record comes from its slots

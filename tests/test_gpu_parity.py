@@ -250,6 +250,46 @@ def test_histogram_beyond_lds_bins_and_overflow_bin(gg):
     assert r.n_clamped > 0
 
 
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_histogram_beside_symbols_and_penalty_in_short_and_resident_blocks(gg, dtype, mode):
+    """A histogram together with a written stream: buckets of a few chunks run as short blocks with 4096 private
+    bins, larger ones as resident runs with 12288.  Both against the oracle, with symbols beyond the private bins
+    and beyond the histogram, NaN / Inf / zeros, empty units, both rounding modes."""
+    for sizes in ([5000, 0, 70_000, 16384, 1, 250_000, 4097], [3_400_000, 0, 50_000, 1000]):
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        n, S = int(off[-1]), len(sizes)
+        x = gg_inputs.make_tensor((n,), 0.5, 0.8, seed=21 + S, device=DEV, dtype=dtype, outlier_frac=1e-3, outlier_scale=20.0)
+        x[off[-2] + 3] = float("nan"); x[off[2] + 5] = float("inf"); x[off[2] + 6] = -float("inf"); x[off[3]: off[3] + 300] = 0
+        hb = host_bits(x)
+        ws = gg.Workspace(n, S)
+        for nbins, div in ((300, 64.0), (4096, 256.0), (4097, 256.0), (20000, 1024.0)):
+            grad = torch.full((n,), 7.0, dtype=torch.float32, device=DEV)
+            clamped, largest = 0, 0
+            out = gg.gg_fused_segmented(x, off, ws, delta_div=div, eg_k=1, round_mode=mode, nbins=nbins, want_symbols=True,
+                                        lam=1e-3, grad=grad)
+            frec, rrec = gg.fit_records(out["fit"]), gg.rate_records(out["rate"])
+            hist = out["hist"].cpu().numpy().view(np.uint64).reshape(S, nbins)
+            sym, g = out["symbols"].cpu().numpy(), grad.cpu().numpy()
+            for s in range(S):
+                lo, hi = int(off[s]), int(off[s + 1])
+                if hi == lo:
+                    assert rrec[s]["flags"] == gg.GG_F_EMPTY and not hist[s].any()
+                    continue
+                if rrec[s]["flags"] & gg.GG_F_DEGENERATE:       # a unit whose fit saw NaN / Inf has no step (the last one and unit 2)
+                    assert s in (2, S - 1)
+                    assert not hist[s].any() and not sym[lo:hi].any()
+                    continue
+                r, ohist, osym = oracle.quantize_rate(hb[lo:hi], float(rrec[s]["delta"]), eg_k=1, round_mode=mode, nbins=nbins,
+                                                      want_symbols=True)
+                check_rate(rrec[s], r, f"sizes={sizes[:2]} nbins={nbins} seg {s}")
+                clamped += r.n_clamped; largest = max(largest, r.u_max)
+                assert np.array_equal(hist[s], ohist) and np.array_equal(sym[lo:hi], osym), (nbins, s)
+                og = oracle.penalty_grad(hb[lo:hi], float(frec[s]["alpha"]), float(frec[s]["beta"]), 1e-3)
+                check_penalty(g[lo:hi], og, f"nbins={nbins} seg {s}")
+            assert largest > 12288 and (clamped > 0 or nbins == 20000), (largest, clamped, [int(f) for f in rrec["flags"]], [float(a) for a in frec["alpha"]])   # the case reaches past every set of private bins
+
+
 def test_quantize_rate_segmented_with_histograms(gg):
     sizes = [0, 17, 4096, 1, 30_000, 0, 99_999, 16384]
     off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
