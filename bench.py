@@ -145,7 +145,8 @@ def other_configs(gg, gg_inputs, torch, dev, args, timer, bucket, want):
         o1 = gg.gg_fused_segmented(x, [0, n], w1, delta_div=16.0, nbins=4096, lam=1e-4, grad=grad)   # and the output buffers of the timed calls
         med, mean = timer.each(lambda: gg.gg_fused_segmented(x, [0, n], w1, delta_div=16.0, nbins=4096, lam=1e-4, grad=grad,
                                                              fit=o1["fit"], rate=o1["rate"], hist=o1["hist"]), 40)
-        res["C1_1024x1024_f32_fit_hist_penalty"] = entry(n, med, mean, 12.0, "launch latency (4 MB tensor, cache resident)", 40)
+        res["C1_1024x1024_f32_fit_hist_penalty"] = entry(n, med, mean, 12.0, "k_quant_parts<float, rate + histogram + penalty> (four dependent launches on a 4 MB tensor)", 40,
+                                                         traffic=measured_traffic("k_quant_c1"))
         del x, grad
     if "C2" in want:
         # 4096x11008 bf16 weight, fit + rate (Delta = alpha/32) + penalty written as fp32
