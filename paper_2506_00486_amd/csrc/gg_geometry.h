@@ -4,6 +4,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <mutex>
 #include <stdint.h>
 #include <string.h>
 
@@ -338,11 +339,33 @@ static RunSplit split_runs(int64_t n_chunks, int blocks_per_cu) {
     return RunSplit{(n_chunks + cpb - 1) / cpb, (int32_t)cpb};
 }
 
-// resident blocks of `kernel` per compute unit, capped at `cap` (a pure function of the code object)
+// Workgroups of `threads` threads and `dyn_lds` bytes of dynamic LDS of `kernel` that fit a compute unit: a pure
+// function of the code object and the device, but a question to the runtime that costs microseconds, so the answers
+// are kept (a small table under a lock; a full table forgets its oldest entry).  The value only sizes grids.
+static int workgroups_per_cu(const void *kernel, int threads, size_t dyn_lds) {
+    struct Entry { const void *kernel; size_t lds; int threads, dev, n; };
+    static Entry table[64];
+    static int used = 0, next = 0;
+    static std::mutex lock;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = -1; }
+    {
+        std::lock_guard<std::mutex> hold(lock);
+        for (int i = 0; i < used; ++i)
+            if (table[i].kernel == kernel && table[i].lds == dyn_lds && table[i].threads == threads && table[i].dev == dev) return table[i].n;
+    }
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, dyn_lds) != hipSuccess || n < 1) { (void)hipGetLastError(); n = 1; }
+    std::lock_guard<std::mutex> hold(lock);
+    const int at = used < 64 ? used++ : (next = (next + 1) % 64);
+    table[at] = Entry{kernel, dyn_lds, threads, dev, n};
+    return n;
+}
+
+// resident blocks of `kernel` per compute unit, capped at `cap`
 template <typename K>
 static int resident_blocks(K kernel, size_t dyn_lds, int cap) {
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, dyn_lds) != hipSuccess || n < 1) n = 1;
+    const int n = workgroups_per_cu(reinterpret_cast<const void *>(kernel), kBlock, dyn_lds);
     return n < cap ? n : cap;
 }
 

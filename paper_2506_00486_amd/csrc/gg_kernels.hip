@@ -2055,13 +2055,18 @@ static int launch_hist_inst(const Geometry &g, const void *x, QuantOpts &o, hipS
     a.lbins = (int32_t)lbins; a.cbins = (int32_t)cbins; a.lds_words = (int32_t)words;
     const size_t lds = (size_t)((words + 3) / 4 * 4) * sizeof(uint32_t);   // cleared 16 bytes at a time
     auto kernel = k_hist<T, NEAREST>;
-    if (lds > (48u << 10) &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-        (void)hipGetLastError();
-        return GG_ERR_HIP;
+    // (the attribute is a property of the kernel on the device and only ever raised: asked for once per size)
+    static std::atomic<uint64_t> lds_allowed[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GG_ERR_HIP;
+    if (lds > (48u << 10) && lds > lds_allowed[dev].load(std::memory_order_relaxed)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
+            return GG_ERR_HIP;
+        }
+        lds_allowed[dev].store(lds, std::memory_order_relaxed);
     }
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kHistThreads, lds) != hipSuccess || per_cu < 1) per_cu = 1;
+    int per_cu = workgroups_per_cu(reinterpret_cast<const void *>(kernel), kHistThreads, lds);
     if (per_cu > 2) per_cu = 2;
     // a few runs per resident workgroup: the compute units finish at different times, and a workgroup that met
     // a piece it has to count in plain bins takes longer than its neighbours
