@@ -540,8 +540,8 @@ __global__ __launch_bounds__(kBlock) void k_eg_encode(Src src, int64_t n, int64_
 // Decoder: one lane per index tile (GG_EG_TILE symbols), a wave decodes 64 tiles side by side.  Each lane
 // keeps the next words of its tile in an LDS ring that is topped up four words at a time by a load issued
 // before four symbols are decoded and stored after them, so decoding does not wait for global memory.
-// Sixteen symbols per lane are collected in LDS and written as one 64-byte piece per tile.  Reads stay
-// below the word that holds the tile's last bit, whatever the stream contains.
+// ROW symbols per lane are collected in LDS and written as one piece per tile (a whole 128-byte line for
+// ROW = 32).  Reads stay within the words that hold bits of the indexed tiles, whatever the stream contains.
 constexpr int kEgDecStep = 4;      // symbols between top-ups
 // Symbols a lane decodes between writes (ROW of k_eg_decode).  32 symbols of a tile are one 128-byte line per
 // store round, written with streaming stores: 16 is 15-20 % slower, 8 and 4 25-80 % (partial lines), 64 15 % (LDS
