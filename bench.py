@@ -180,7 +180,9 @@ def other_configs(gg, gg_inputs, torch, dev, args, timer, bucket, want):
         res["C3_tensor_histogram_32768_bins"] = entry(n, med_h, mean_h, 2.0, "k_hist<bf16>", 40,
                                                       traffic=measured_traffic("k_quant_c3_histogram"))
         # both calls against the 2 + 2 bytes per element the configuration has to move (each call reads the input once)
-        res["C3_both_calls"] = entry(n, med_r + med_h, mean_r + mean_h, 4.0, "k_rows_reg<bf16> + k_hist<bf16>", 40)
+        t_r, t_h = measured_traffic("k_rows_c3"), measured_traffic("k_quant_c3_histogram")
+        res["C3_both_calls"] = entry(n, med_r + med_h, mean_r + mean_h, 4.0, "k_rows_reg<bf16> + k_hist<bf16>", 40,
+                                     traffic=(t_r + t_h) if (t_r is not None and t_h is not None) else None)
         del x
     if "C5" in want and not args.small:
         # 7B-shaped bf16 weight set, fused fit + penalty accumulated into fp32 (the update step), and written
