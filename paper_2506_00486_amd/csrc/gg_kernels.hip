@@ -420,17 +420,19 @@ __device__ __forceinline__ void prepare_unit(const PrepArgs &a, int seg, int64_t
     }
 }
 
-__global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *__restrict__ partials,
-                                                     int32_t chunks_per_block, gg_fit_t *__restrict__ out,
-                                                     PrepArgs prep, int do_prep) {
-    const int seg = blockIdx.x, lane = threadIdx.x;
+constexpr int kFitFinalizeThreads = 256;
+__global__ __launch_bounds__(kFitFinalizeThreads) void k_fit_finalize(SegView sv, const double2 *__restrict__ partials,
+                                                                      int32_t chunks_per_block, gg_fit_t *__restrict__ out,
+                                                                      PrepArgs prep, int do_prep) {
+    __shared__ double red[2][kFitFinalizeThreads / 64];
+    const int seg = blockIdx.x, tid = threadIdx.x;
     const int64_t c0 = unit_chunk0(sv, seg), c1 = unit_chunk1(sv, seg);
     double s1 = 0.0, s2 = 0.0;
     if (c1 > c0) {
-        // one piece per run that overlaps the unit; lane-strided over runs, ascending: a fixed order
+        // one piece per run that overlaps the unit; thread-strided over runs, ascending: a fixed order
         const int64_t r0 = c0 / chunks_per_block, r1 = (c1 - 1) / chunks_per_block;
 #pragma unroll 8
-        for (int64_t r = r0 + lane; r <= r1; r += 64) {    // loads of several rounds in flight; the order of the sums stays
+        for (int64_t r = r0 + tid; r <= r1; r += kFitFinalizeThreads) {    // loads of several rounds in flight; the order of the sums stays
             const int64_t run_first = r * chunks_per_block;
             const double2 p = partials[run_first > c0 ? run_first : c0];
             s1 += p.x; s2 += p.y;
@@ -438,14 +440,19 @@ __global__ __launch_bounds__(64) void k_fit_finalize(SegView sv, const double2 *
     }
     s1 = wave_reduce(s1, OpAdd());
     s2 = wave_reduce(s2, OpAdd());
+    if ((tid & 63) == 0) { red[0][tid >> 6] = s1; red[1][tid >> 6] = s2; }
     const int64_t n = unit_len(sv, seg);
     if (do_prep && prep.hist) {          // the unit's histogram starts at zero; the stores overlap the solve
         uint64_t *bins = prep.hist + (int64_t)seg * prep.nbins;
-        for (int b = lane; b < prep.nbins; b += 64) bins[b] = 0;
+        for (int b = tid; b < prep.nbins; b += kFitFinalizeThreads) bins[b] = 0;
     }
+    __syncthreads();
+    if (tid >= 64) return;               // the first wave solves (all its lanes, identical arguments)
+    s1 = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+    s2 = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
     gg_fit_t f;
     solve_fit_wave(s1, s2, (uint64_t)n, f);
-    if (lane == 0) {
+    if (tid == 0) {
         out[seg] = f;
         if (do_prep) prepare_unit(prep, seg, n, f.alpha, f.beta);
     }
@@ -1889,7 +1896,7 @@ static int launch_fit_finalize(const Geometry &g, int32_t chunks_per_block, gg_f
         hipLaunchKernelGGL(k_fit_finalize_lanes, dim3((unsigned)((g.S + 63) / 64)), dim3(64), 0, st, g.sv, g.partials(),
                            chunks_per_block, out, p, prep ? 1 : 0);
     } else {
-        hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(64), 0, st, g.sv, g.partials(), chunks_per_block, out,
+        hipLaunchKernelGGL(k_fit_finalize, dim3((unsigned)g.S), dim3(kFitFinalizeThreads), 0, st, g.sv, g.partials(), chunks_per_block, out,
                            p, prep ? 1 : 0);
     }
     return check_launch();
